@@ -1,0 +1,352 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against facts fixed by the
+paper or by mathematics, never against the oracle itself or the GPU path.
+
+Citations are to the paper's sections/equations: Eq. 1 (attention), Eq. 2-3 (delta and
+reference update), Eq. 4 (recursive product), Eq. 5 (prefill window), Eq. 6 (sparsity),
+Sec. III-A (strategy 3: key deltas from the top row), Sec. III-B (window shapes),
+Sec. III-C (workflow, decode cache).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19608_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# ----------------------------------------------------------------------------- helpers
+def dense_causal(Q, K, V, scale=None, q_off=0):
+    """Textbook Eq. 1 with a causal mask, via torch's library routine in fp64.
+    Q [Hq, nq, d], K/V [Hkv, nk, d]; query row i sees keys 0..i+q_off."""
+    Q, K, V = (torch.tensor(np.asarray(x), dtype=torch.float64) for x in (Q, K, V))
+    g = Q.shape[0] // K.shape[0]
+    K = K.repeat_interleave(g, dim=0)
+    V = V.repeat_interleave(g, dim=0)
+    nq, nk = Q.shape[1], K.shape[1]
+    allowed = torch.arange(nk)[None, :] <= (torch.arange(nq)[:, None] + q_off)
+    return torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=allowed, scale=scale).numpy()
+
+
+def brute_force_prefill(Q, K, V, theta, W):
+    """Pure-Python loops straight from Eq. 1-4 for one head (tiny inputs only)."""
+    n, d = len(K), len(K[0])
+    th = np.float32(theta)
+    held = [0.0] * d
+    dK = [[0.0] * d for _ in range(n)]
+    mask = [[0] * d for _ in range(n)]
+    for t in range(n):
+        for c in range(d):
+            if t == 0:
+                dK[t][c], mask[t][c], held[c] = K[t][c], 1, K[t][c]
+            else:
+                diff = np.float32(K[t][c]) - np.float32(held[c])
+                if abs(diff) > th:
+                    dK[t][c], mask[t][c], held[c] = K[t][c] - held[c], 1, K[t][c]
+    # Eq. 4: R(j) = dK(j) B + R(j-1), B = Q^T; R(j) is a vector over query rows
+    R = [[0.0] * n for _ in range(n)]
+    for j in range(n):
+        for i in range(n):
+            upd = sum(dK[j][c] * Q[i][c] for c in range(d))
+            R[j][i] = upd + (R[j - 1][i] if j > 0 else 0.0)
+    O = [[0.0] * d for _ in range(n)]
+    for i in range(n):
+        s = []
+        for j in range(i + 1):
+            if i // W == j // W:
+                s.append(sum(Q[i][c] * K[j][c] for c in range(d)) / math.sqrt(d))
+            else:
+                s.append(R[j][i] / math.sqrt(d))
+        m = max(s)
+        e = [math.exp(x - m) for x in s]
+        z = sum(e)
+        for j in range(i + 1):
+            for c in range(d):
+                O[i][c] += e[j] / z * V[j][c]
+    return np.array(O), np.array(mask, dtype=np.uint8)
+
+
+def rand_qkv(seed, Hq, Hkv, n, d, dtype="bf16", walk=True):
+    rng = np.random.default_rng(seed)
+    def one(H):
+        x = rng.standard_normal((H, n, d))
+        if walk:
+            x = np.cumsum(0.15 * x, axis=1) + rng.standard_normal((H, 1, d))
+        return wl.round_to_dtype(x, dtype)
+    return one(Hq), one(Hkv), one(Hkv)
+
+
+# ----------------------------------------------------------------------------- delta matrix
+def test_hand_worked_example(oracle):
+    vals = {}
+    for line in open(os.path.join(HERE, "golden", "hand_delta_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        vals[k] = np.array([float(x) for x in v])
+    K = vals["K"].reshape(5, 2)
+    mask, dK, Khat, knife = oracle.delta_scan(K, vals["theta"][0])
+    assert (mask.ravel() == vals["mask"]).all()
+    assert (dK.ravel() == vals["dK"]).all()
+    assert (Khat.ravel() == vals["Khat"]).all()
+    assert mask.sum() == vals["nnz"][0] and knife == 0
+    s_m, s_c = oracle.sparsity(int(mask.sum()), 5, 2, 1, 1)
+    assert s_m == pytest.approx(vals["s_m"][0], abs=1e-15)
+    assert s_c == pytest.approx(vals["s_c_w1"][0], abs=1e-15)
+
+
+@pytest.mark.parametrize("theta", [0.0, 0.05, 0.3, 1.0])
+def test_reference_stays_within_theta(oracle, theta):
+    """Eq. 2-3: after every row |k(t) - k_hat(t)| <= theta per channel, and the basis row is exact.
+    (A scan that differenced against the previous raw key instead would let k_hat drift.)"""
+    _, K, _ = rand_qkv(1, 1, 1, 400, 16)
+    mask, dK, Khat, knife = oracle.delta_scan(K[0], theta)
+    assert knife == 0
+    assert np.abs(K[0] - Khat).max() <= np.float32(theta)
+    assert (Khat[0] == K[0][0]).all() and (mask[0] == 1).all() and (dK[0] == K[0][0]).all()
+    # zeroed entries are exactly the masked-out ones; kept non-basis entries exceed theta
+    assert ((dK[1:] == 0) == (mask[1:] == 0)).all()
+    assert (np.abs(dK[1:][mask[1:] == 1]) > np.float32(theta)).all()
+    # telescoping: the running sum of the delta rows is the held reference (Eq. 3 vs Eq. 2)
+    assert np.abs(np.cumsum(dK, axis=0) - Khat).max() < 1e-12
+
+
+def test_raw_previous_key_reading_is_rejected():
+    """Plant the other reading (delta against the previous raw key) on the CPU and show the
+    bound of Eq. 2-3 catches it: a slow drift never fires, so the implied reference runs away."""
+    n, theta = 200, 0.5
+    k = 0.125 * np.arange(n)                     # each step moves 0.125 < theta
+    held_raw_prev = k[0]                         # wrong reading: never fires, reference stays k(0)
+    assert abs(k[-1] - held_raw_prev) > theta    # violates the bound ...
+    from oracle import delta_oracle as orc
+    _, _, Khat, _ = orc.delta_scan(k[:, None], theta)
+    assert np.abs(k[:, None] - Khat).max() <= theta   # ... which the oracle's reading keeps
+
+
+def test_strict_inequality_and_binary32_decision(oracle):
+    """Eq. 2: a difference equal to theta does not fire; the comparison is made in binary32."""
+    K = np.array([[0.0], [0.5], [1.0], [1.0 + 2 ** -10]])
+    mask, _, Khat, _ = oracle.delta_scan(K, 0.5)
+    assert mask.ravel().tolist() == [1, 0, 1, 0]
+    assert Khat.ravel().tolist() == [0.0, 0.0, 1.0, 1.0]
+    # theta is a binary32 value: 0.1 (double) is rounded to float before comparing
+    t32 = float(np.float32(0.1))
+    K = np.array([[0.0], [t32]])
+    assert oracle.delta_scan(K, 0.1)[0].ravel().tolist() == [1, 0]
+    K = np.array([[0.0], [float(np.nextafter(np.float32(0.1), np.float32(1.0)))]])
+    assert oracle.delta_scan(K, 0.1)[0].ravel().tolist() == [1, 1]
+
+
+def test_closed_forms_of_the_delta_matrix(oracle):
+    n, d = 64, 8
+    # constant keys: only the basis row survives -> S_m = (n-1)/n
+    K = np.tile(wl.round_to_dtype(np.random.default_rng(0).standard_normal((1, d)), "bf16"), (n, 1))
+    mask, dK, Khat, _ = oracle.delta_scan(K, 0.0)
+    assert mask.sum() == d and (dK[1:] == 0).all()
+    assert oracle.sparsity(int(mask.sum()), n, d, 1, 4)[0] == pytest.approx((n - 1) / n)
+    # theta = 0 keeps every entry that changed at all: k_hat == k
+    _, K2, _ = rand_qkv(3, 1, 1, n, d)
+    mask, dK, Khat, _ = oracle.delta_scan(K2[0], 0.0)
+    assert (Khat == K2[0]).all() and (mask[1:] == (np.diff(K2[0], axis=0) != 0)).all()
+    # every step larger than theta in every channel: all ones, S_m = 0
+    K3 = np.cumsum(np.ones((n, d)), axis=0)
+    mask, _, _, _ = oracle.delta_scan(K3, 0.5)
+    assert mask.all()
+    # theta = +inf: nothing after the basis fires
+    mask, _, Khat, _ = oracle.delta_scan(K2[0], np.inf)
+    assert mask[1:].sum() == 0 and (Khat == K2[0][0]).all()
+
+
+def test_sparsity_formula_eq6(oracle):
+    s_m, s_c = oracle.sparsity(400, 100, 10, 1, 20)
+    assert s_m == pytest.approx(0.6) and s_c == pytest.approx(0.6 * 0.8)
+    # pooled over several KV heads; window larger than the sequence leaves no sparse region
+    s_m, s_c = oracle.sparsity(1000, 100, 10, 4, 500)
+    assert s_m == pytest.approx(0.75) and s_c == 0.0
+    # table 3's relation: S_c = S_m (1 - W_d / n)
+    assert oracle.sparsity(0, 1000, 1, 1, 4)[1] == pytest.approx(1.0 * (1 - 4 / 1000))
+
+
+def test_window_eq5(oracle):
+    assert oracle.window_from_gamma(100, 0.25, 1000) == 25
+    assert oracle.window_from_gamma(10, 0.25, 1000) == 2          # floor(2.5)
+    assert oracle.window_from_gamma(1000, 0.05, 32) == 32         # capped by W_max
+    assert oracle.window_from_gamma(10, 0.05, 32) == 1            # floor(0.5) = 0 -> clamped to 1
+
+
+# ----------------------------------------------------------------------------- hybrid scores
+def test_score_structure(oracle):
+    """First score column exact (Sec. III-A, strategy 3); outside the window the score equals
+    q . k_hat(j) (telescoped Eq. 4); the exact region is the causal part of W x W diagonal
+    squares whose area is W/n of the map (Sec. III-B, Eq. 6)."""
+    Q, K, _ = rand_qkv(5, 1, 1, 96, 16)
+    n, d, W, theta = 96, 16, 8, 0.4
+    mask, dK, Khat, _ = oracle.delta_scan(K[0], theta)
+    S, ex = oracle.hybrid_scores(Q[0], K[0], dK, W)
+    sc = 1 / math.sqrt(d)
+    full = Q[0] @ K[0].T * sc
+    approx = Q[0] @ Khat.T * sc
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    causal = jj <= ii
+    assert np.isneginf(S[~causal]).all()
+    assert np.abs(S[:, 0] - full[:, 0]).max() < 1e-12
+    inside = causal & (ii // W == jj // W)
+    assert (ex.astype(bool) == inside).all()
+    assert np.abs(S[inside] - full[inside]).max() < 1e-12
+    out = causal & ~inside
+    assert np.abs(S[out] - approx[out]).max() < 1e-10
+    assert np.abs(S[out] - full[out]).max() > 1e-3          # and it really is an approximation
+    # area: squares before masking cover n*W cells = W/n of n^2; after masking (n/W) W(W+1)/2
+    assert inside.sum() == (n // W) * W * (W + 1) // 2
+    assert (2 * inside.sum() - n) / n ** 2 == pytest.approx(W / n)
+    # |error| of an outside score is bounded by theta * ||q||_1 * scale (Eq. 2-3 bound)
+    bound = theta * np.abs(Q[0]).sum(axis=1)[:, None] * sc
+    assert (np.abs(S - full)[out] <= (bound * np.ones((1, n)))[out] + 1e-12).all()
+
+
+def test_truncated_last_square(oracle):
+    Q, K, _ = rand_qkv(6, 1, 1, 21, 8)
+    _, dK, _, _ = oracle.delta_scan(K[0], 0.3)
+    _, ex = oracle.hybrid_scores(Q[0], K[0], dK, 8)
+    assert ex[20, 16:21].all() and not ex[20, :16].any() and ex[15, 8:16].all() and not ex[16, 15]
+
+
+# ----------------------------------------------------------------------------- full path vs dense attention
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 2)])
+def test_theta_zero_is_dense_causal_attention(oracle, Hq, Hkv):
+    Q, K, V = rand_qkv(7, Hq, Hkv, 150, 16)
+    r = oracle.prefill(Q[None], K[None], V[None], 0.0, 16)
+    assert np.abs(r["O"][0] - dense_causal(Q, K, V)).max() < 1e-12
+    assert r["knife"] == 0
+
+
+@pytest.mark.parametrize("W", [150, 151, 4096])
+def test_window_covering_sequence_is_dense(oracle, W):
+    Q, K, V = rand_qkv(8, 4, 2, 150, 16)
+    r = oracle.prefill(Q[None], K[None], V[None], 0.7, W)
+    assert np.abs(r["O"][0] - dense_causal(Q, K, V)).max() < 1e-12
+    assert r["s_c"] == 0.0 and r["s_m"] > 0.2
+
+
+def test_special_inputs_reduce_to_dense(oracle):
+    n, d = 80, 8
+    rng = np.random.default_rng(9)
+    Q = wl.round_to_dtype(rng.standard_normal((2, n, d)), "bf16")
+    V = wl.round_to_dtype(rng.standard_normal((1, n, d)), "bf16")
+    Kc = np.tile(wl.round_to_dtype(rng.standard_normal((1, 1, d)), "bf16"), (1, n, 1))   # constant keys
+    r = oracle.prefill(Q[None], Kc[None], V[None], 0.3, 8)
+    assert np.abs(r["O"][0] - dense_causal(Q, Kc, V)).max() < 1e-12
+    assert r["s_m"] == pytest.approx((n - 1) / n)
+    Kbig = np.cumsum(np.ones((1, n, d)), axis=1) * 0.75                                  # all steps fire
+    r = oracle.prefill(Q[None], Kbig[None], V[None], 0.5, 8)
+    assert np.abs(r["O"][0] - dense_causal(Q, Kbig, V)).max() < 1e-12 and r["s_m"] == 0.0
+
+
+def test_theta_infinite_freezes_outside_scores(oracle):
+    Q, K, V = rand_qkv(10, 1, 1, 40, 8)
+    _, dK, _, _ = oracle.delta_scan(K[0], np.inf)
+    S, ex = oracle.hybrid_scores(Q[0], K[0], dK, 4)
+    base = (Q[0] @ K[0][0]) / math.sqrt(8)
+    for i in range(40):
+        for j in range(i + 1):
+            if not ex[i, j]:
+                assert S[i, j] == pytest.approx(base[i], abs=1e-12)
+
+
+@pytest.mark.parametrize("n,d,W,theta", [(8, 4, 1, 0.3), (8, 4, 2, 0.5), (7, 3, 3, 0.2), (6, 2, 4, 1.0), (5, 4, 8, 0.4)])
+def test_brute_force_tiny_prefill(oracle, n, d, W, theta):
+    Q, K, V = rand_qkv(100 + n + W, 1, 1, n, d)
+    O_ref, mask_ref = brute_force_prefill(Q[0].tolist(), K[0].tolist(), V[0].tolist(), theta, W)
+    r = oracle.prefill(Q[None], K[None], V[None], theta, W)
+    assert (r["mask"][0, 0] == mask_ref).all()
+    assert np.abs(r["O"][0, 0] - O_ref).max() < 1e-12
+
+
+def test_gqa_shares_one_delta_matrix_per_kv_head(oracle):
+    Q, K, V = rand_qkv(11, 6, 2, 64, 8)
+    r = oracle.prefill(Q[None], K[None], V[None], 0.4, 8)
+    for h in range(6):
+        single = oracle.prefill(Q[None, h:h + 1], K[None, h // 3:h // 3 + 1], V[None, h // 3:h // 3 + 1], 0.4, 8)
+        assert (single["O"][0, 0] == r["O"][0, h]).all()
+    assert r["mask"].shape == (1, 2, 64, 8)
+
+
+def test_row_subset_matches_full(oracle):
+    Q, K, V = rand_qkv(12, 2, 1, 90, 8)
+    full = oracle.prefill(Q[None], K[None], V[None], 0.4, 16)
+    part = oracle.prefill(Q[None], K[None], V[None], 0.4, 16, rows=(33, 57))
+    assert (part["O"] == full["O"][:, :, 33:57]).all()
+
+
+# ----------------------------------------------------------------------------- decode workflow
+def brute_force_decode_row(q, K, V, theta, Wd):
+    """Eq. 1-4 for the last position of K with a sliding exact window of Wd keys."""
+    t, d = len(K) - 1, len(q)
+    th = np.float32(theta)
+    held = list(K[0])
+    R, run = [], sum(q[c] * K[0][c] for c in range(d))
+    R.append(run)
+    for j in range(1, t + 1):
+        for c in range(d):
+            diff = np.float32(K[j][c]) - np.float32(held[c])
+            if abs(diff) > th:
+                run += q[c] * (K[j][c] - held[c])
+                held[c] = K[j][c]
+        R.append(run)
+    s = [(sum(q[c] * K[j][c] for c in range(d)) if t - j < Wd else R[j]) / math.sqrt(d) for j in range(t + 1)]
+    m = max(s)
+    e = [math.exp(x - m) for x in s]
+    return np.array([sum(e[j] * V[j][c] for j in range(t + 1)) / sum(e) for c in range(d)])
+
+
+def test_decode_matches_brute_force_and_masks_match_prefill(oracle):
+    """Sec. III-C: the cache built by prefill and extended token by token holds the same
+    delta matrix as one scan over the whole sequence (masks do not depend on stage or
+    window), and each decode step is Eq. 1-4 with the W_d most recent keys exact."""
+    B, Hq, Hkv, n, m, d, theta, Wd = 2, 4, 2, 12, 9, 4, 0.35, 3
+    rng = np.random.default_rng(13)
+    def mk(H):
+        return wl.round_to_dtype(np.cumsum(0.2 * rng.standard_normal((B, H, n + m, d)), axis=2), "bf16")
+    Q, K, V = mk(Hq), mk(Hkv), mk(Hkv)
+    st = oracle.DecodeState(theta, Wd)
+    st.append(K[:, :, :n], V[:, :, :n])
+    for t in range(n, n + m):
+        o, mrow = st.step(Q[:, :, t], K[:, :, t], V[:, :, t])
+        for b in range(B):
+            for h in range(Hq):
+                ref = brute_force_decode_row(Q[b, h, t].tolist(), K[b, h // 2, :t + 1].tolist(),
+                                             V[b, h // 2, :t + 1].tolist(), theta, Wd)
+                assert np.abs(o[b, h] - ref).max() < 1e-12
+    whole = oracle.prefill(Q, K, V, theta, 5)
+    assert (whole["mask"] == st.mask).all()
+    assert (whole["nnz"] == st.nnz()).all()
+
+
+def test_decode_window_covering_history_is_dense(oracle):
+    Q, K, V = rand_qkv(14, 2, 1, 30, 8)
+    for theta, Wd in [(0.0, 2), (0.6, 30), (0.6, 64)]:
+        st = oracle.DecodeState(theta, Wd)
+        st.append(K[None, :, :20], V[None, :, :20])
+        for t in range(20, 30):
+            o, _ = st.step(Q[None, :, t], K[None, :, t], V[None, :, t])
+            ref = dense_causal(Q[:, t:t + 1], K[:, :t + 1], V[:, :t + 1], q_off=t)[:, 0]
+            assert np.abs(o[0] - ref).max() < 1e-12
+
+
+def test_decode_window_is_sliding_and_includes_new_token(oracle):
+    Q, K, _ = rand_qkv(15, 1, 1, 20, 4)
+    _, dK, _, _ = oracle.delta_scan(K[0], 0.5)
+    _, ex = oracle.hybrid_scores(Q[0][19:20], K[0], dK, 4, mode=1, q_off=19)
+    assert ex[0].tolist() == [0] * 16 + [1] * 4
+
+
+# ----------------------------------------------------------------------------- workloads
+def test_no_knife_edges_on_benchmark_inputs(oracle):
+    x = wl.generate(wl.C1, ("K",))["K"]
+    assert oracle.delta_scan(x[0, 0], wl.theta_for(wl.C1))[3] == 0
+    x = wl.generate(wl.C2, ("K",))["K"]
+    m, _, _, knife = oracle.delta_scan(x[0, 3], wl.theta_for(wl.C2))
+    assert knife == 0 and 0.2 < 1 - m.mean() < 0.9
