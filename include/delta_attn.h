@@ -1,0 +1,134 @@
+/*
+ * delta_attn.h - C ABI of the MI355X (gfx950) hybrid delta attention library.
+ *
+ * One attention layer of DeltaLLM (arXiv 2507.19608): keys are turned into a
+ * thresholded delta matrix (Sec. II-C Eq. 2-3, applied to K from its first row,
+ * Sec. III-A strategy 3); attention scores are exact inside a local window and
+ * rebuilt incrementally from the delta matrix outside it (Sec. III-B, Eq. 4);
+ * softmax and PV follow Eq. 1.  Prefill and decode (Sec. III-C) are covered.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller, contiguous,
+ *     last dimension fastest.  The library owns only da_cache objects.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = default stream).  All
+ *     work is enqueued on it; only delta_attn_sparsity synchronises.
+ *   - Every entry returns a da_status; on an error nothing has been enqueued.
+ *   - Grouped-query attention: n_q_heads % n_kv_heads == 0; query head h reads
+ *     KV head h / (n_q_heads / n_kv_heads).  There is one delta matrix, mask and
+ *     nnz per (batch, KV head).
+ *   - Threshold decision: fabsf((float)k - (float)held) > theta in IEEE binary32,
+ *     strict inequality (Eq. 2); the first row of a sequence is the basis and is
+ *     kept whole.  NaN keys never fire (not checked).
+ */
+#ifndef DELTA_ATTN_H
+#define DELTA_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DA_OK = 0,
+    DA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, Hq % Hkv != 0, window < 1, theta < 0 or NaN */
+    DA_ERR_UNSUPPORTED = 2,   /* head_dim not a multiple of 32 or > 256, unknown dtype or mode */
+    DA_ERR_WORKSPACE = 3,     /* workspace pointer null or smaller than *_workspace_bytes() */
+    DA_ERR_STATE = 4,         /* cache full, cache/params mismatch, decode on an empty cache */
+    DA_ERR_HIP = 5            /* a HIP runtime call failed */
+} da_status;
+
+typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
+
+/* How scores outside the window are produced.  Both give the same real-number result.
+ *   DA_SCORE_GATHER  Eq. 4 as written: a running score per query row, updated per key
+ *                    column with only the surviving (channel, delta) entries.
+ *   DA_SCORE_REBASE  the telescoped form of Eq. 4: sum_{u<=j} dk(u) = k_hat(j), so the
+ *                    score is the dense product q . k_hat(j) (no multiply is skipped). */
+typedef enum { DA_SCORE_GATHER = 0, DA_SCORE_REBASE = 1 } da_score_mode;
+
+typedef struct {
+    int32_t batch, n_q_heads, n_kv_heads, head_dim, seq_len;
+    int32_t window;     /* W >= 1: side of the exact squares on the diagonal (Sec. III-B);
+                           W >= seq_len gives dense causal attention */
+    float theta;        /* >= 0 (may be +inf) */
+    float scale;        /* score scale; 0 selects 1/sqrt(head_dim) (Eq. 1) */
+    int32_t dtype;      /* da_dtype of Q, K, V, O */
+    int32_t score_mode; /* da_score_mode */
+} da_prefill_params;
+
+typedef struct da_cache da_cache;   /* decode-time cache (Sec. III-C), opaque */
+
+const char *delta_attn_version(void);
+const char *delta_attn_status_string(da_status s);
+
+/* Eq. 5: min(floor(gamma * n), w_max), clamped to >= 1.  Host only. */
+int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);
+
+/* Bytes of device scratch delta_attn_prefill / delta_attn_delta_scan need for these params
+ * (0 if the params are invalid). */
+size_t delta_attn_prefill_workspace_bytes(const da_prefill_params *p);
+
+/*
+ * Delta matrix only (Eq. 2-3 on K; Sec. III-A).  Uses batch, n_kv_heads, head_dim, seq_len,
+ * theta, dtype of p.
+ *   K         [B, Hkv, n, d]   in
+ *   mask_bits [B, Hkv, n, d/32] uint32 out: bit (c % 32) of word c/32 is 1 iff delta entry
+ *             (t, c) is kept; row 0 is all ones
+ *   nnz       [B, Hkv] uint64 out: number of set mask bits
+ *   k_hat     [B, Hkv, n, d] out or NULL: reference keys after each row (Eq. 3), dtype of K
+ */
+da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint32_t *mask_bits,
+                                uint64_t *nnz, void *k_hat, void *hip_stream);
+
+/*
+ * Prefill (Sec. III-B prefill stage + Sec. III-C): builds the delta matrix of K, then for every
+ * query row i and key j <= i the score is q_i.k_j if floor(i/W) == floor(j/W), else the Eq. 4
+ * running score; scaled, softmaxed over j <= i, multiplied with V (Eq. 1).
+ *   Q, O      [B, Hq, n, d];  K, V [B, Hkv, n, d]
+ *   mask_bits, nnz as in delta_attn_delta_scan
+ *   cache     NULL, or an EMPTY cache with matching batch/heads/head_dim/theta/dtype and
+ *             max_seq >= n: left holding the n rows, ready for delta_attn_decode at position n
+ *   workspace device scratch of at least delta_attn_prefill_workspace_bytes(p)
+ */
+da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const void *K, const void *V,
+                             void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Decode cache: per (batch, KV head) the delta matrix in compact form (mask bits + surviving key
+ * values), reference-key checkpoints, the current reference key, a ring of the last decode_window
+ * raw keys, and V (Sec. III-A last paragraph, Sec. III-C).  All sequences of the batch advance
+ * together.  Allocates device memory on the current device. */
+da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim, int32_t max_seq, int32_t decode_window, float theta,
+                                  float scale, int32_t dtype);
+da_status delta_attn_cache_destroy(da_cache *c);
+da_status delta_attn_cache_reset(da_cache *c, void *hip_stream);   /* back to length 0 */
+int64_t delta_attn_cache_length(const da_cache *c);                /* rows held, -1 if c is NULL */
+const uint64_t *delta_attn_cache_nnz(const da_cache *c);           /* device [B, Hkv] uint64 */
+/* mask bits of the cached rows: device [B, Hkv, max_seq, d/32] (rows >= length undefined) */
+const uint32_t *delta_attn_cache_mask(const da_cache *c);
+
+/*
+ * One decode step at position t = cache length (Sec. III-B decode stage, Sec. III-C): appends
+ * the delta row of k_new and v_new to the cache, then attends q_new over keys 0..t with exact
+ * scores for the decode_window most recent keys (the new one included) and Eq. 4 scores for
+ * older keys.
+ *   q_new [B, Hq, d], k_new, v_new [B, Hkv, d] in;  o [B, Hq, d] out
+ *   mask_row [B, Hkv, d/32] out or NULL: mask of the appended row
+ */
+da_status delta_attn_decode(da_cache *c, const void *q_new, const void *k_new, const void *v_new,
+                            void *o, uint32_t *mask_row, void *hip_stream);
+
+/* Eq. 6.  Reads nnz (device, [batch * n_kv_heads]) after synchronising the stream.
+ *   s_m = 1 - sum(nnz) / (batch * n_kv_heads * rows * head_dim)
+ *   s_c = s_m * (1 - min(window, rows) / rows) */
+da_status delta_attn_sparsity(const uint64_t *nnz_dev, int32_t batch, int32_t n_kv_heads, int64_t rows,
+                              int32_t head_dim, int32_t window, void *hip_stream, double *s_m,
+                              double *s_c);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTA_ATTN_H */

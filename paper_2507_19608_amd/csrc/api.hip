@@ -1,0 +1,166 @@
+// C ABI of the hybrid delta attention library: argument checks, workspace carving, launches.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "../../include/delta_attn.h"
+#include "cache.hpp"
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace da;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
+
+struct WsLayout {
+    size_t khat, ents, counts, total;
+};
+
+da_status check_params(const da_prefill_params *p) {
+    if (!p) return DA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->head_dim < 1 || p->seq_len < 1)
+        return DA_ERR_INVALID_ARG;
+    if (p->n_q_heads % p->n_kv_heads != 0) return DA_ERR_INVALID_ARG;
+    if (p->window < 1) return DA_ERR_INVALID_ARG;
+    if (!(p->theta >= 0.f)) return DA_ERR_INVALID_ARG;          // also rejects NaN
+    if (!(p->scale >= 0.f) || isinf(p->scale)) return DA_ERR_INVALID_ARG;
+    if (p->head_dim % 32 != 0 || p->head_dim > 256) return DA_ERR_UNSUPPORTED;
+    if (p->dtype != DA_F32 && p->dtype != DA_BF16) return DA_ERR_UNSUPPORTED;
+    if (p->score_mode != DA_SCORE_GATHER && p->score_mode != DA_SCORE_REBASE) return DA_ERR_UNSUPPORTED;
+    if ((int64_t)p->batch * p->n_q_heads > 65535 * 64) return DA_ERR_UNSUPPORTED;
+    return DA_OK;
+}
+
+WsLayout layout(const da_prefill_params *p) {
+    const size_t units = (size_t)p->batch * p->n_kv_heads;
+    const size_t rows = units * (size_t)p->seq_len;
+    WsLayout w;
+    size_t off = 0;
+    w.khat = off;
+    off += align_up(rows * p->head_dim * elt_size(p->dtype));
+    w.ents = off;
+    off += align_up(rows * p->head_dim * sizeof(Entry));
+    w.counts = off;
+    off += align_up(rows * sizeof(uint32_t));
+    w.total = off;
+    return w;
+}
+
+inline float score_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f / sqrtf((float)d); }
+
+}  // namespace
+
+extern "C" {
+
+const char *delta_attn_version(void) { return "delta_attn 0.1 (gfx950)"; }
+
+const char *delta_attn_status_string(da_status s) {
+    switch (s) {
+        case DA_OK: return "ok";
+        case DA_ERR_INVALID_ARG: return "invalid argument";
+        case DA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case DA_ERR_WORKSPACE: return "workspace missing or too small";
+        case DA_ERR_STATE: return "cache state does not allow this call";
+        case DA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max) {
+    if (n < 1 || w_max < 1 || !(gamma > 0.0)) return 1;
+    double w = floor(gamma * (double)n);
+    if (w > (double)w_max) w = (double)w_max;
+    if (w < 1.0) w = 1.0;
+    return (int32_t)w;
+}
+
+size_t delta_attn_prefill_workspace_bytes(const da_prefill_params *p) {
+    if (check_params(p) != DA_OK) return 0;
+    return layout(p).total;
+}
+
+da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint32_t *mask_bits, uint64_t *nnz,
+                                void *k_hat, void *hip_stream) {
+    da_status st = check_params(p);
+    if (st != DA_OK) return st;
+    if (!K || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    launch_delta_scan(p->dtype, K, k_hat, mask_bits, nnz, p->batch * p->n_kv_heads, p->seq_len, p->head_dim,
+                      p->theta, s);
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
+                             uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+    da_status st = check_params(p);
+    if (st != DA_OK) return st;
+    if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
+    const WsLayout w = layout(p);
+    if (!workspace || workspace_bytes < w.total) return DA_ERR_WORKSPACE;
+    if (cache) {
+        st = cache_check_for_prefill(cache, p);
+        if (st != DA_OK) return st;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    void *khat = ws + w.khat;
+    void *ents = ws + w.ents;
+    uint32_t *counts = (uint32_t *)(ws + w.counts);
+    const int units = p->batch * p->n_kv_heads;
+
+    launch_delta_scan(p->dtype, K, khat, mask_bits, nnz, units, p->seq_len, p->head_dim, p->theta, s);
+    if (p->score_mode == DA_SCORE_GATHER || cache)
+        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, units, p->seq_len, p->head_dim, s);
+
+    PrefillArgs a;
+    a.dtype = p->dtype;
+    a.B = p->batch;
+    a.Hq = p->n_q_heads;
+    a.Hkv = p->n_kv_heads;
+    a.d = p->head_dim;
+    a.n = p->seq_len;
+    a.W = p->window;
+    a.scale_log2 = score_scale(p->scale, p->head_dim) * 1.4426950408889634f;
+    a.rebase = p->score_mode == DA_SCORE_REBASE;
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.Khat = khat;
+    a.O = O;
+    a.ents = ents;
+    a.counts = counts;
+    if (!launch_prefill_generic(a, s)) return DA_ERR_UNSUPPORTED;
+    if (cache) cache_fill_from_prefill(cache, p, K, V, khat, mask_bits, counts, nnz, s);
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+da_status delta_attn_sparsity(const uint64_t *nnz_dev, int32_t batch, int32_t n_kv_heads, int64_t rows,
+                              int32_t head_dim, int32_t window, void *hip_stream, double *s_m, double *s_c) {
+    if (!nnz_dev || !s_m || !s_c || batch < 1 || n_kv_heads < 1 || rows < 1 || head_dim < 1 || window < 1)
+        return DA_ERR_INVALID_ARG;
+    const size_t units = (size_t)batch * n_kv_heads;
+    uint64_t *host = new (std::nothrow) uint64_t[units];
+    if (!host) return DA_ERR_HIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e = hipMemcpyAsync(host, nnz_dev, units * sizeof(uint64_t), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        delete[] host;
+        return DA_ERR_HIP;
+    }
+    uint64_t total = 0;
+    for (size_t u = 0; u < units; ++u) total += host[u];
+    delete[] host;
+    const double all = (double)units * (double)rows * (double)head_dim;
+    *s_m = 1.0 - (double)total / all;
+    const double w = (double)(window < rows ? window : rows);
+    *s_c = *s_m * (1.0 - w / (double)rows);
+    return DA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Shared device helpers for the hybrid delta attention kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace da {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+
+constexpr int kWave = 64;
+constexpr int kGroup = 4;        // compacted entry lists are padded to a multiple of this
+
+// One surviving delta entry of a key column: channel index and delta value (binary32).
+struct __attribute__((aligned(8))) Entry {
+    uint32_t chan;
+    float delta;
+};
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_from_f32(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_from_f32(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// number of set bits of a 64-bit wave mask below this lane
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+}  // namespace da

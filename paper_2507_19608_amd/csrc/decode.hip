@@ -1,0 +1,387 @@
+// Decode stage (Sec. III-B decode stage, Sec. III-C): cache object, append of the new key's delta
+// row, history scores from the compact delta cache, window scores from the raw-key ring, softmax, PV.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "cache.hpp"
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace da;
+
+namespace {
+
+inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------------------------- cache fill
+__global__ __launch_bounds__(256) void row_offsets_kernel(const uint32_t *__restrict__ counts,
+                                                          uint32_t *__restrict__ roff, const uint64_t *nnz_in,
+                                                          uint64_t *nnz_out, int n, int max_seq) {
+    __shared__ uint32_t buf[256];
+    const int unit = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *cp = counts + (size_t)unit * n;
+    uint32_t *rp = roff + (size_t)unit * (max_seq + 1);
+    uint32_t carry = 0;
+    for (int base = 0; base < n; base += 256) {
+        const uint32_t v = (base + tid < n) ? cp[base + tid] : 0u;
+        buf[tid] = v;
+        __syncthreads();
+        for (int s = 1; s < 256; s <<= 1) {
+            const uint32_t add = (tid >= s) ? buf[tid - s] : 0u;
+            __syncthreads();
+            buf[tid] += add;
+            __syncthreads();
+        }
+        if (base + tid < n) rp[base + tid] = carry + buf[tid] - v;   // exclusive
+        carry += buf[255];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        rp[n] = carry;
+        nnz_out[unit] = nnz_in[unit];
+    }
+}
+
+// one wave per cached row
+template <typename T>
+__global__ __launch_bounds__(256) void cache_fill_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                         const T *__restrict__ Khat,
+                                                         const uint32_t *__restrict__ mask_bits, da_cache c, int n) {
+    const int unit = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const int d = c.d, wpr = d >> 5;
+    const size_t src = ((size_t)unit * n + row) * d;
+    const uint32_t *Mp = mask_bits + ((size_t)unit * n + row) * wpr;
+    uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + row) * wpr;
+    T *surv = (T *)c.surv + (size_t)unit * c.max_seq * d;
+    uint32_t off = c.roff[(size_t)unit * (c.max_seq + 1) + row];
+    for (int c0 = 0; c0 < d; c0 += kWave) {
+        const int ch = c0 + lane;
+        const bool act = ch < d;
+        bool bit = false;
+        if (act) bit = (Mp[ch >> 5] >> (ch & 31)) & 1u;
+        const uint64_t b = __ballot(bit);
+        if (act) {
+            const T k = K[src + ch];
+            if (bit) surv[off + lanes_below(b)] = k;
+            ((T *)c.V)[((size_t)unit * c.max_seq + row) * d + ch] = V[src + ch];
+            if (row >= n - c.Wd) ((T *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = k;
+            if (row > 0 && row % kChunk == 0)
+                ((T *)c.ck)[((size_t)unit * c.nck + row / kChunk) * d + ch] = Khat[src - d + ch];
+            if (row == n - 1) ((T *)c.khat)[(size_t)unit * d + ch] = Khat[src + ch];
+        }
+        off += __popcll(b);
+    }
+    if (lane < wpr) Mc[lane] = Mp[lane];
+}
+
+// ---------------------------------------------------------------------------------- decode step
+// D1: delta of the new key against the carried reference key, append to the compact cache.
+template <typename T>
+__global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *__restrict__ k_new,
+                                                           const T *__restrict__ v_new,
+                                                           uint32_t *__restrict__ mask_row, int t) {
+    const int unit = blockIdx.x, lane = threadIdx.x;
+    const int d = c.d, wpr = d >> 5;
+    T *surv = (T *)c.surv + (size_t)unit * c.max_seq * d;
+    uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
+    const uint32_t start = (t == 0) ? 0u : rp[t];
+    uint32_t off = start;
+    for (int c0 = 0; c0 < d; c0 += kWave) {
+        const int ch = c0 + lane;
+        const bool act = ch < d;
+        bool fire = false;
+        T kraw = 0;
+        if (act) {
+            kraw = k_new[(size_t)unit * d + ch];
+            T *hp = (T *)c.khat + (size_t)unit * d + ch;
+            if (t == 0) {
+                fire = true;   // basis row
+            } else {
+                const T hraw = *hp;
+                const float diff = load_f32(&kraw, 0) - load_f32(&hraw, 0);
+                fire = fabsf(diff) > c.theta;
+                if (t % kChunk == 0) ((T *)c.ck)[((size_t)unit * c.nck + t / kChunk) * d + ch] = hraw;
+            }
+            if (fire) *hp = kraw;
+            ((T *)c.ring)[((size_t)unit * c.Wd + t % c.Wd) * d + ch] = kraw;
+            ((T *)c.V)[((size_t)unit * c.max_seq + t) * d + ch] = v_new[(size_t)unit * d + ch];
+        }
+        const uint64_t b = __ballot(fire);
+        if (fire) surv[off + lanes_below(b)] = kraw;
+        if (act && (lane & 31) == 0) {
+            const uint32_t w = (uint32_t)(b >> (lane & 32));
+            c.mask[((size_t)unit * c.max_seq + t) * wpr + (ch >> 5)] = w;
+            if (mask_row) mask_row[(size_t)unit * wpr + (ch >> 5)] = w;
+        }
+        off += __popcll(b);
+    }
+    if (lane == 0) {
+        if (t == 0) rp[0] = 0;
+        rp[t + 1] = off;
+        c.nnz[unit] = (t == 0 ? 0ull : c.nnz[unit]) + (off - start);
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s);
+    return v;
+}
+
+// D2-D4 for one chunk of kChunk cached rows of one unit, all query heads of the unit's group.
+// Phase A (lanes = channels): rebuild the reference keys k_hat(j) of the chunk from the chunk's
+// checkpoint, the mask bits and the surviving values; by telescoping Eq. 4 the history score of
+// row j is q . k_hat(j).  Phase B (lanes = rows): scores (raw-key ring inside the window), chunk
+// softmax partials.  Phase C (lanes = channels): partial PV.
+template <typename T>
+__global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *__restrict__ q_new, int t,
+                                                          float scale_log2) {
+    extern __shared__ float lds[];
+    const int d = c.d, wpr = d >> 5;
+    const int ldk = d + 1;
+    float *kh = lds;                    // [kChunk][d + 1]
+    float *pb = lds + kChunk * ldk;     // [kChunk]
+    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
+    const int r0 = chunk * kChunk;
+    const int r1 = min(r0 + kChunk, t + 1);
+    const int g = c.Hq / c.Hkv;
+    const int b = unit / c.Hkv, hk = unit % c.Hkv;
+    const int win_begin = t + 1 - c.Wd;   // rows >= win_begin use raw keys (may be negative)
+    const T *surv = (const T *)c.surv + (size_t)unit * c.max_seq * d;
+    const uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
+    const uint32_t *Mp = c.mask + (size_t)unit * c.max_seq * wpr;
+
+    if (r0 < win_begin) {   // some row of the chunk is history
+        float held[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r0 > 0) {
+            const T *ckp = (const T *)c.ck + ((size_t)unit * c.nck + chunk) * d;
+            for (int w = 0; w * kWave < d; ++w)
+                if (w * kWave + lane < d) held[w] = load_f32(ckp, w * kWave + lane);
+        }
+        const int hist_end = min(r1, win_begin);
+        for (int row = r0; row < hist_end; ++row) {
+            uint32_t off = rp[row];
+            for (int w = 0; w * kWave < d; ++w) {
+                const int ch = w * kWave + lane;
+                bool bit = false;
+                if (ch < d) bit = (Mp[(size_t)row * wpr + (ch >> 5)] >> (ch & 31)) & 1u;
+                const uint64_t bal = __ballot(bit);
+                if (bit) held[w] = load_f32(surv, off + lanes_below(bal));
+                off += __popcll(bal);
+                if (ch < d) kh[(row - r0) * ldk + ch] = held[w];
+            }
+        }
+    }
+    __syncthreads();
+
+    const int row = r0 + lane;
+    const bool valid = row < r1;
+    const bool in_win = row >= win_begin;
+    const T *ringrow = (const T *)c.ring + ((size_t)unit * c.Wd + (valid ? row % c.Wd : 0)) * d;
+    for (int hh = 0; hh < g; ++hh) {
+        const int h = hk * g + hh;
+        const T *q = q_new + ((size_t)b * c.Hq + h) * d;
+        float s = 0.f;
+        if (valid) {
+            if (in_win) {
+                for (int ch = 0; ch < d; ++ch) s = fmaf(load_f32(q, ch), load_f32(ringrow, ch), s);
+            } else {
+                for (int ch = 0; ch < d; ++ch) s = fmaf(load_f32(q, ch), kh[lane * ldk + ch], s);
+            }
+        }
+        s = valid ? s * scale_log2 : -INFINITY;
+        const float m = wave_max(s);              // at least row r0 is valid, so m is finite
+        const float p = valid ? exp2f(s - m) : 0.f;
+        const float l = wave_sum(p);
+        __syncthreads();
+        pb[lane] = p;
+        __syncthreads();
+        float *out = c.part + (((size_t)b * c.Hq + h) * c.max_chunks + chunk) * (d + 2);
+        const T *Vp = (const T *)c.V + ((size_t)unit * c.max_seq + r0) * d;
+        for (int w = 0; w * kWave < d; ++w) {
+            const int ch = w * kWave + lane;
+            if (ch < d) {
+                float acc = 0.f;
+                for (int r = 0; r < r1 - r0; ++r) acc = fmaf(pb[r], load_f32(Vp, (size_t)r * d + ch), acc);
+                out[ch] = acc;
+            }
+        }
+        if (lane == 0) {
+            out[d] = m;
+            out[d + 1] = l;
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void decode_combine_kernel(da_cache c, T *__restrict__ o, int nchunks) {
+    const int bh = blockIdx.x, lane = threadIdx.x;
+    const int d = c.d;
+    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
+    float M = -INFINITY;
+    for (int k = 0; k < nchunks; ++k) M = fmaxf(M, part[(size_t)k * (d + 2) + d]);
+    float L = 0.f;
+    for (int k = 0; k < nchunks; ++k)
+        L += part[(size_t)k * (d + 2) + d + 1] * exp2f(part[(size_t)k * (d + 2) + d] - M);
+    const float inv = 1.f / L;
+    for (int ch = lane; ch < d; ch += kWave) {
+        float acc = 0.f;
+        for (int k = 0; k < nchunks; ++k)
+            acc = fmaf(part[(size_t)k * (d + 2) + ch], exp2f(part[(size_t)k * (d + 2) + d] - M), acc);
+        store_from_f32(o + (size_t)bh * d, ch, acc * inv);
+    }
+}
+
+template <typename T>
+void decode_launch(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row,
+                   hipStream_t s) {
+    const int t = (int)c->len;
+    const int units = c->B * c->Hkv;
+    const float sc = (c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d)) * 1.4426950408889634f;
+    hipLaunchKernelGGL(decode_append_kernel<T>, dim3(units), dim3(64), 0, s, *c, (const T *)k, (const T *)v,
+                       mask_row, t);
+    const int nchunks = t / kChunk + 1;
+    const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
+    static bool attr_done = false;   // per instantiation; d = 256 needs slightly more than 64 KiB
+    if (!attr_done) {
+        (void)hipFuncSetAttribute((const void *)decode_chunk_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(decode_chunk_kernel<T>, dim3(nchunks, units), dim3(64), lds, s, *c, (const T *)q, t, sc);
+    hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+}
+
+void free_all(da_cache *c) {
+    void *ptrs[] = {c->mask, c->surv, c->roff, c->ck, c->khat, c->ring, c->V, c->nnz, c->part};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+}  // namespace
+
+namespace da {
+
+da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p) {
+    if (c->len != 0) return DA_ERR_STATE;
+    if (c->B != p->batch || c->Hq != p->n_q_heads || c->Hkv != p->n_kv_heads || c->d != p->head_dim ||
+        c->dtype != p->dtype || c->theta != p->theta || c->max_seq < p->seq_len)
+        return DA_ERR_STATE;
+    return DA_OK;
+}
+
+void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void *K, const void *V,
+                             const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,
+                             const uint64_t *nnz, hipStream_t s) {
+    const int units = c->B * c->Hkv, n = p->seq_len;
+    hipLaunchKernelGGL(row_offsets_kernel, dim3(units), dim3(256), 0, s, counts, c->roff, nnz, c->nnz, n,
+                       c->max_seq);
+    dim3 grid((n + 3) / 4, units), block(256);
+    if (c->dtype == DA_F32)
+        hipLaunchKernelGGL(cache_fill_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)V,
+                           (const float *)Khat, mask_bits, *c, n);
+    else
+        hipLaunchKernelGGL(cache_fill_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K, (const bf16_t *)V,
+                           (const bf16_t *)Khat, mask_bits, *c, n);
+    c->len = n;
+}
+
+}  // namespace da
+
+extern "C" {
+
+da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim, int32_t max_seq, int32_t decode_window, float theta,
+                                  float scale, int32_t dtype) {
+    if (!out) return DA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || max_seq < 1 || decode_window < 1)
+        return DA_ERR_INVALID_ARG;
+    if (n_q_heads % n_kv_heads != 0 || !(theta >= 0.f) || !(scale >= 0.f) || isinf(scale)) return DA_ERR_INVALID_ARG;
+    if (head_dim % 32 != 0 || head_dim > 256) return DA_ERR_UNSUPPORTED;
+    if (dtype != DA_F32 && dtype != DA_BF16) return DA_ERR_UNSUPPORTED;
+    if ((int64_t)batch * n_kv_heads > 65535) return DA_ERR_UNSUPPORTED;
+    if ((int64_t)max_seq * head_dim >= (int64_t)1 << 31) return DA_ERR_UNSUPPORTED;
+    da_cache *c = new (std::nothrow) da_cache();
+    if (!c) return DA_ERR_HIP;
+    memset(c, 0, sizeof(*c));
+    c->B = batch;
+    c->Hq = n_q_heads;
+    c->Hkv = n_kv_heads;
+    c->d = head_dim;
+    c->max_seq = max_seq;
+    c->Wd = decode_window < max_seq ? decode_window : max_seq;
+    c->dtype = dtype;
+    c->theta = theta;
+    c->scale = scale;
+    c->len = 0;
+    c->nck = max_seq / kChunk + 1;
+    c->max_chunks = (max_seq + kChunk - 1) / kChunk;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return DA_ERR_HIP;
+    }
+    const size_t units = (size_t)batch * n_kv_heads, es = elt_size(dtype), d = head_dim;
+    bool ok = true;
+    ok = ok && hipMalloc((void **)&c->mask, units * max_seq * (d / 32) * 4) == hipSuccess;
+    ok = ok && hipMalloc(&c->surv, units * max_seq * d * es) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->roff, units * ((size_t)max_seq + 1) * 4) == hipSuccess;
+    ok = ok && hipMalloc(&c->ck, units * c->nck * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->khat, units * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->ring, units * c->Wd * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->V, units * max_seq * d * es) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->nnz, units * 8) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->part, (size_t)batch * n_q_heads * c->max_chunks * (d + 2) * 4) == hipSuccess;
+    if (ok) ok = hipMemset(c->nnz, 0, units * 8) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        free_all(c);
+        delete c;
+        return DA_ERR_HIP;
+    }
+    *out = c;
+    return DA_OK;
+}
+
+da_status delta_attn_cache_destroy(da_cache *c) {
+    if (!c) return DA_ERR_INVALID_ARG;
+    free_all(c);
+    delete c;
+    return DA_OK;
+}
+
+da_status delta_attn_cache_reset(da_cache *c, void *hip_stream) {
+    if (!c) return DA_ERR_INVALID_ARG;
+    launch_fill_u64(c->nnz, 0, c->B * c->Hkv, (hipStream_t)hip_stream);
+    c->len = 0;
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+int64_t delta_attn_cache_length(const da_cache *c) { return c ? c->len : -1; }
+const uint64_t *delta_attn_cache_nnz(const da_cache *c) { return c ? c->nnz : nullptr; }
+const uint32_t *delta_attn_cache_mask(const da_cache *c) { return c ? c->mask : nullptr; }
+
+da_status delta_attn_decode(da_cache *c, const void *q_new, const void *k_new, const void *v_new, void *o,
+                            uint32_t *mask_row, void *hip_stream) {
+    if (!c || !q_new || !k_new || !v_new || !o) return DA_ERR_INVALID_ARG;
+    if (c->len >= c->max_seq) return DA_ERR_STATE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (c->dtype == DA_F32)
+        decode_launch<float>(c, q_new, k_new, v_new, o, mask_row, s);
+    else
+        decode_launch<bf16_t>(c, q_new, k_new, v_new, o, mask_row, s);
+    if (hipGetLastError() != hipSuccess) return DA_ERR_HIP;
+    c->len += 1;
+    return DA_OK;
+}
+
+}  // extern "C"

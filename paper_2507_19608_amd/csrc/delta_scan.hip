@@ -1,0 +1,144 @@
+// Delta matrix construction on the key matrix (Sec. II-C Eq. 2-3; Sec. III-A strategy 3) and
+// compaction of the surviving entries per key column.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace da {
+
+// Sequential in t, parallel over channels: one lane per channel, one wave per 64 channels of a
+// (batch, KV head) unit.  The wave ballot of the threshold decision is the mask word itself.
+template <typename T>
+__global__ __launch_bounds__(64) void delta_scan_kernel(const T *__restrict__ K, T *__restrict__ Khat,
+                                                        uint32_t *__restrict__ mask_bits,
+                                                        unsigned long long *__restrict__ nnz, int n, int d,
+                                                        float theta) {
+    const int unit = blockIdx.y;
+    const int lane = threadIdx.x;
+    const int c = blockIdx.x * kWave + lane;
+    const bool active = c < d;
+    const int wpr = d >> 5;
+    const T *Kp = K + (size_t)unit * n * d;
+    T *Hp = Khat ? Khat + (size_t)unit * n * d : nullptr;
+    uint32_t *Mp = mask_bits + (size_t)unit * n * wpr;
+    const bool writer = active && ((lane & 31) == 0);
+    const int word = c >> 5;
+
+    // row 0 is the basis: kept whole
+    float held = active ? load_f32(Kp, c) : 0.f;
+    if (Hp && active) Hp[c] = Kp[c];
+    if (writer) Mp[word] = 0xffffffffu;
+    unsigned long long cnt = __popcll(__ballot(active));
+
+    constexpr int U = 8;
+    int t = 1;
+    for (; t + U <= n; t += U) {
+        float k[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) k[u] = active ? load_f32(Kp, (size_t)(t + u) * d + c) : 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float diff = k[u] - held;                  // Eq. 2 condition in binary32
+            const bool fire = active && (fabsf(diff) > theta);
+            held = fire ? k[u] : held;                        // Eq. 3
+            const uint64_t b = __ballot(fire);
+            if (writer) Mp[(size_t)(t + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
+            if (Hp && active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
+            cnt += __popcll(b);
+        }
+    }
+    for (; t < n; ++t) {
+        const float k = active ? load_f32(Kp, (size_t)t * d + c) : 0.f;
+        const float diff = k - held;
+        const bool fire = active && (fabsf(diff) > theta);
+        held = fire ? k : held;
+        const uint64_t b = __ballot(fire);
+        if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(b >> (lane & 32));
+        if (Hp && active) store_from_f32(Hp, (size_t)t * d + c, held);
+        cnt += __popcll(b);
+    }
+    if (lane == 0) atomicAdd(nnz + unit, cnt);
+}
+
+// One wave per key column: ballot + prefix count turn the mask row into a dense list of
+// (channel, delta) pairs, padded with (0, 0.0f) to a multiple of kGroup.  The list of column j
+// of a unit starts at entry (unit * n + j) * d; counts holds the unpadded length.
+template <typename T>
+__global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__ K, const T *__restrict__ Khat,
+                                                           const uint32_t *__restrict__ mask_bits,
+                                                           Entry *__restrict__ ents, uint32_t *__restrict__ counts,
+                                                           int n, int d) {
+    const int unit = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= n) return;
+    const int wpr = d >> 5;
+    const size_t row = (size_t)unit * n + j;
+    const T *Kp = K + row * d;
+    const T *Hprev = Khat + (row - (j > 0 ? 1 : 0)) * d;
+    const uint32_t *Mp = mask_bits + row * wpr;
+    Entry *out = ents + row * d;
+    uint32_t off = 0;
+    for (int c0 = 0; c0 < d; c0 += kWave) {
+        const int c = c0 + lane;
+        const bool act = c < d;
+        bool bit = false;
+        float delta = 0.f;
+        if (act) {
+            bit = (Mp[c >> 5] >> (c & 31)) & 1u;
+            const float k = load_f32(Kp, c);
+            delta = (j == 0) ? k : k - load_f32(Hprev, c);
+        }
+        const uint64_t b = __ballot(bit);
+        if (bit) {
+            Entry e;
+            e.chan = (uint32_t)c;
+            e.delta = delta;
+            out[off + lanes_below(b)] = e;
+        }
+        off += __popcll(b);
+    }
+    const uint32_t padded = (off + kGroup - 1) & ~(uint32_t)(kGroup - 1);
+    if (off + lane < padded) {
+        Entry e;
+        e.chan = 0;
+        e.delta = 0.f;
+        out[off + lane] = e;
+    }
+    if (lane == 0) counts[row] = off;
+}
+
+__global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (unsigned long long *)p,
+                       (unsigned long long)v, n);
+}
+
+void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, uint64_t *nnz, int units,
+                       int n, int d, float theta, hipStream_t s) {
+    launch_fill_u64(nnz, 0, units, s);
+    dim3 grid((d + kWave - 1) / kWave, units), block(kWave);
+    if (dtype == 0)
+        hipLaunchKernelGGL(delta_scan_kernel<float>, grid, block, 0, s, (const float *)K, (float *)Khat, mask_bits,
+                           (unsigned long long *)nnz, n, d, theta);
+    else
+        hipLaunchKernelGGL(delta_scan_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K, (bf16_t *)Khat,
+                           mask_bits, (unsigned long long *)nnz, n, d, theta);
+}
+
+void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
+                         uint32_t *counts, int units, int n, int d, hipStream_t s) {
+    dim3 grid((n + 3) / 4, units), block(256);
+    if (dtype == 0)
+        hipLaunchKernelGGL(emit_entries_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)Khat,
+                           mask_bits, (Entry *)ents, counts, n, d);
+    else
+        hipLaunchKernelGGL(emit_entries_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K,
+                           (const bf16_t *)Khat, mask_bits, (Entry *)ents, counts, n, d);
+}
+
+}  // namespace da

@@ -40,29 +40,28 @@ def _gen(seed: int, tensor: str, b: int, h: int, purpose: int) -> np.random.Gene
     return np.random.Generator(np.random.Philox(key=key))
 
 
-def ar1_jump(seed: int, tensor: str, batch: int, heads: int, n: int, d: int, p_jump: float,
+def ar1_jump(seed: int, tensor: str, batch_ids, heads: int, n: int, d: int, p_jump: float,
              per_head_scale: bool) -> np.ndarray:
-    """float64 array [batch, heads, n, d] following the recipe above."""
-    S = batch * heads
-    noise = np.empty((S, n, d))
-    jumpv = np.empty((S, n, d))
-    jumpf = np.empty((S, n), dtype=bool)
-    scale = np.ones(S)
-    for b in range(batch):
+    """float64 array [len(batch_ids), heads, n, d] following the recipe above."""
+    out = np.empty((len(batch_ids), heads, n, d))
+    for bi, b in enumerate(batch_ids):
+        noise = np.empty((heads, n, d))
+        jumpv = np.empty((heads, n, d))
+        jumpf = np.empty((heads, n), dtype=bool)
+        scale = np.ones(heads)
         for h in range(heads):
-            s = b * heads + h
-            noise[s] = _gen(seed, tensor, b, h, 0).standard_normal((n, d))
-            jumpv[s] = _gen(seed, tensor, b, h, 1).standard_normal((n, d))
-            jumpf[s] = _gen(seed, tensor, b, h, 2).random(n) < p_jump
+            noise[h] = _gen(seed, tensor, b, h, 0).standard_normal((n, d))
+            jumpv[h] = _gen(seed, tensor, b, h, 1).standard_normal((n, d))
+            jumpf[h] = _gen(seed, tensor, b, h, 2).random(n) < p_jump
             if per_head_scale:
-                scale[s] = 0.5 + 1.5 * _gen(seed, tensor, b, h, 3).random()
-    x = np.empty((S, n, d))
-    x[:, 0] = noise[:, 0] * (_SIGMA / np.sqrt(1.0 - _RHO * _RHO))
-    for t in range(1, n):
-        step = _RHO * x[:, t - 1] + _SIGMA * noise[:, t]
-        x[:, t] = np.where(jumpf[:, t, None], jumpv[:, t], step)
-    x *= scale[:, None, None]
-    return x.reshape(batch, heads, n, d)
+                scale[h] = 0.5 + 1.5 * _gen(seed, tensor, b, h, 3).random()
+        x = out[bi]
+        x[:, 0] = noise[:, 0] * (_SIGMA / np.sqrt(1.0 - _RHO * _RHO))
+        for t in range(1, n):
+            step = _RHO * x[:, t - 1] + _SIGMA * noise[:, t]
+            x[:, t] = np.where(jumpf[:, t, None], jumpv[:, t], step)
+        x *= scale[:, None, None]
+    return out
 
 
 @dataclass(frozen=True)
@@ -122,17 +121,16 @@ def theta_for(w: Workload) -> float:
     return float.fromhex(table[w.key()]["theta_hex"])
 
 
-def generate(w: Workload, tensors: Tuple[str, ...] = ("Q", "K", "V"), kv_heads=None, q_heads=None,
-             batch=None) -> Dict[str, np.ndarray]:
+def generate(w: Workload, tensors: Tuple[str, ...] = ("Q", "K", "V"), batch_ids=None) -> Dict[str, np.ndarray]:
     """float64 arrays (already rounded to w.dtype's grid) of length w.total_len.
 
-    Q: [B, Hq, L, d], K/V: [B, Hkv, L, d].  `batch` limits the batch entries generated
-    (streams are independent, so a sub-batch equals the slice of the full tensor)."""
-    B = w.batch if batch is None else batch
+    Q: [B, Hq, L, d], K/V: [B, Hkv, L, d].  `batch_ids` picks batch entries (streams are
+    independent, so a subset equals the same entries of the full tensor)."""
+    ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
     out = {}
     for name in tensors:
         H = w.n_q_heads if name == "Q" else w.n_kv_heads
-        x = ar1_jump(w.seed, name, B, H, w.total_len, w.head_dim, w.p_jump, w.per_head_scale)
+        x = ar1_jump(w.seed, name, ids, H, w.total_len, w.head_dim, w.p_jump, w.per_head_scale)
         out[name] = round_to_dtype(x, w.dtype)
     return out
 

@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports every symbol include/delta_attn.h declares; host-only
+entry points and argument checks behave as documented.  No GPU compute here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_19608_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "delta_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(delta_attn_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_symbols()
+    assert len(names) >= 14
+    L = binding.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_host_only_entry_points():
+    assert "gfx950" in binding.version()
+    assert binding.status_string(0) == "ok"
+    assert "workspace" in binding.status_string(3)
+    # Eq. 5
+    assert binding.delta_attn_window_from_gamma(100, 0.25, 1000) == 25
+    assert binding.delta_attn_window_from_gamma(10, 0.25, 1000) == 2
+    assert binding.delta_attn_window_from_gamma(1000, 0.05, 32) == 32
+    assert binding.delta_attn_window_from_gamma(10, 0.05, 32) == 1
+
+
+def _params(**kw):
+    base = dict(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, seq_len=128, window=16, theta=0.1, scale=0.0,
+                dtype=1, score_mode=0)
+    base.update(kw)
+    return binding.PrefillParams(**base)
+
+
+def test_workspace_size_and_argument_checks():
+    L = binding.lib()
+    p = _params()
+    need = binding.delta_attn_prefill_workspace_bytes(p)
+    rows = 2 * 128
+    assert need >= rows * 64 * 2 + rows * 64 * 8 + rows * 4
+    for bad in (dict(n_q_heads=3), dict(window=0), dict(theta=-1.0), dict(theta=float("nan")), dict(seq_len=0),
+                dict(head_dim=48), dict(head_dim=512), dict(dtype=7), dict(score_mode=5)):
+        assert binding.delta_attn_prefill_workspace_bytes(_params(**bad)) == 0, bad
+    # invalid arguments are rejected before anything touches the GPU
+    st = L.delta_attn_prefill(ctypes.byref(_params(n_q_heads=3)), 1, 1, 1, 1, 1, 1, None, 1, 1 << 40, None)
+    assert st == 1
+    st = L.delta_attn_prefill(ctypes.byref(_params(head_dim=48)), 1, 1, 1, 1, 1, 1, None, 1, 1 << 40, None)
+    assert st == 2
+    st = L.delta_attn_prefill(ctypes.byref(p), None, 1, 1, 1, 1, 1, None, 1, 1 << 40, None)
+    assert st == 1
+    st = L.delta_attn_prefill(ctypes.byref(p), 1, 1, 1, 1, 1, 1, None, 1, need - 1, None)
+    assert st == 3
+    assert L.delta_attn_decode(None, 1, 1, 1, 1, None, None) == 1
+    assert L.delta_attn_cache_length(None) == -1
+    h = ctypes.c_void_p()
+    assert L.delta_attn_cache_create(ctypes.byref(h), 1, 3, 2, 64, 128, 4, 0.1, 0.0, 1) == 1
+    assert L.delta_attn_cache_create(ctypes.byref(h), 1, 4, 2, 48, 128, 4, 0.1, 0.0, 1) == 2
+
+
+def test_binding_refuses_to_run_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        binding.delta_attn_prefill(torch.zeros(1, 1, 8, 32), torch.zeros(1, 1, 8, 32), torch.zeros(1, 1, 8, 32), 0.1, 4)

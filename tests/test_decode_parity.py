@@ -1,0 +1,125 @@
+"""GPU parity of the decode path (cache hand-off from prefill + delta_attn_decode) against the
+oracle's decode workflow.  Mask rows / nnz bit-exact, outputs within tolerance at every step."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19608_amd import binding as da
+from paper_2507_19608_amd import workloads as wl
+from oracle import delta_oracle as orc
+from util import check_output, rand_walk, to_dev, unpack_mask
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode(Q, K, V, n, steps, theta, Wd, dtype, W_prefill=16, check_every=1, scale=0.0):
+    """Prefill n rows into a cache, then `steps` decode steps; compares every check_every-th step."""
+    B, Hq, _, d = Q.shape
+    Hkv = K.shape[1]
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    cache = da.Cache(B, Hq, Hkv, d, n + steps, Wd, theta, tdt, scale=scale)
+    st = orc.DecodeState(theta, Wd, scale=None if scale == 0.0 else scale)
+    Qd, Kd, Vd = (to_dev(x, dtype) for x in (Q, K, V))
+    if n > 0:
+        _, maskg, nnzg = da.delta_attn_prefill(Qd[:, :, :n].contiguous(), Kd[:, :, :n].contiguous(),
+                                               Vd[:, :, :n].contiguous(), theta, W_prefill, scale=scale, cache=cache)
+        mref = st.append(K[:, :, :n], V[:, :, :n])
+        assert (unpack_mask(maskg, d) == mref).all()
+        assert len(cache) == n
+    for t in range(n, n + steps):
+        o, mrow = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(),
+                                       Vd[:, :, t].contiguous())
+        if (t - n) % check_every == 0 or t == n + steps - 1:
+            o_ref, m_ref = st.step(Q[:, :, t], K[:, :, t], V[:, :, t])
+            assert (unpack_mask(mrow, d) == m_ref).all(), t
+            check_output(o, o_ref, dtype)
+        else:
+            st.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
+    torch.cuda.synchronize()
+    assert len(cache) == n + steps
+    assert (cache.nnz().cpu().numpy() == st.nnz()).all()
+    assert (unpack_mask(cache.mask_rows(), d) == st.mask).all()
+    assert st.knife == 0
+    # Sec. III-C: the incrementally built delta matrix equals one scan over the whole sequence
+    maskw, nnzw, _ = da.delta_attn_delta_scan(Kd[:, :, :n + steps].contiguous(), theta)
+    assert (unpack_mask(maskw, d) == st.mask).all()
+    assert (nnzw.cpu().numpy() == st.nnz()).all()
+    s_m, s_c = da.delta_attn_sparsity(cache.nnz(), n + steps, d, Wd)
+    ref = orc.sparsity(int(st.nnz().sum()), n + steps, d, B * Hkv, Wd)
+    assert s_m == ref[0] and s_c == pytest.approx(ref[1], abs=1e-15)
+    cache.close()
+
+
+@pytest.mark.parametrize("n,steps,d,Wd,B,Hq,Hkv,theta,dtype", [
+    (70, 70, 64, 5, 2, 4, 2, 0.2, "bf16"),      # crosses chunk boundaries at 64 and 128
+    (100, 40, 128, 4, 1, 4, 1, 0.15, "bf16"),   # the paper's W_d = 4
+    (33, 20, 32, 1, 1, 2, 2, 0.3, "bf16"),      # W_d = 1: only the new key is exact
+    (64, 66, 96, 70, 1, 3, 1, 0.25, "bf16"),    # window wider than a chunk
+    (50, 30, 64, 8, 1, 2, 1, 0.05, "f32"),
+])
+def test_decode_small(n, steps, d, Wd, B, Hq, Hkv, theta, dtype):
+    L = n + steps
+    step = 0.05 if dtype == "f32" else 0.15
+    Q, K, V = rand_walk(11, B, Hq, L, d, dtype), rand_walk(12, B, Hkv, L, d, dtype, step), rand_walk(13, B, Hkv, L, d, dtype)
+    run_decode(Q, K, V, n, steps, theta, Wd, dtype, scale=0.0 if dtype == "bf16" else 0.15)
+
+
+def test_decode_from_empty_cache_and_dense_limits():
+    B, Hq, Hkv, L, d = 1, 2, 1, 40, 64
+    Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d)
+    run_decode(Q, K, V, 0, 40, 0.2, 6, "bf16")            # first decoded token is the basis row
+    run_decode(Q, K, V, 10, 30, 0.0, 3, "bf16")           # theta = 0: dense attention
+    run_decode(Q, K, V, 10, 30, 0.4, 1000, "bf16")        # window covers everything
+    run_decode(Q, K, V, 10, 30, float("inf"), 3, "bf16")  # history frozen at the basis key
+
+
+def test_cache_state_errors():
+    cache = da.Cache(1, 2, 1, 64, 4, 2, 0.1, torch.bfloat16)
+    z = lambda h: torch.zeros(1, h, 64, dtype=torch.bfloat16, device="cuda")
+    for _ in range(4):
+        da.delta_attn_decode(cache, z(2), z(1), z(1))
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_decode(cache, z(2), z(1), z(1))
+    assert e.value.status == 4                                # cache full
+    Q = torch.zeros(1, 2, 4, 64, dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros(1, 1, 4, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill(Q, K, K, 0.1, 2, cache=cache)   # not empty
+    assert e.value.status == 4
+    cache.reset()
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill(Q, K, K, 0.2, 2, cache=cache)   # theta differs from the cache's
+    assert e.value.status == 4
+    da.delta_attn_prefill(Q, K, K, 0.1, 2, cache=cache)
+    assert len(cache) == 4
+    cache.close()
+
+
+def test_c4_decode_llama_shape_sampled_batch():
+    """Config 4 at full size on the GPU (batch 32, 2048 cached + 256 steps); the oracle follows
+    three batch entries (streams are independent per batch entry)."""
+    w = wl.C4
+    ids = [0, 17, 31]
+    x = wl.generate(w)
+    theta = wl.theta_for(w)
+    B, Hq, Hkv, d, n, steps = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.decode_steps
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    cache = da.Cache(B, Hq, Hkv, d, n + steps, w.window, theta, torch.bfloat16)
+    da.delta_attn_prefill(Qd[:, :, :n].contiguous(), Kd[:, :, :n].contiguous(), Vd[:, :, :n].contiguous(), theta,
+                          w.window, cache=cache)
+    st = orc.DecodeState(theta, w.window)
+    xs = {k: x[k][ids] for k in "QKV"}
+    st.append(xs["K"][:, :, :n], xs["V"][:, :, :n])
+    for t in range(n, n + steps):
+        o, mrow = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(),
+                                       Vd[:, :, t].contiguous())
+        if (t - n) % 37 == 0 or t == n + steps - 1:
+            o_ref, m_ref = st.step(xs["Q"][:, :, t], xs["K"][:, :, t], xs["V"][:, :, t])
+            assert (unpack_mask(mrow, d)[ids] == m_ref).all()
+            check_output(o[ids], o_ref, w.dtype)
+        else:
+            st.append(xs["K"][:, :, t:t + 1], xs["V"][:, :, t:t + 1])
+    assert (cache.nnz().cpu().numpy()[ids] == st.nnz()).all()
+    s_m, _ = da.delta_attn_sparsity(cache.nnz(), n + steps, d, w.window)
+    assert abs(s_m - 0.57) < 0.01
+    cache.close()

@@ -1,0 +1,141 @@
+"""GPU parity: delta_attn_prefill / delta_attn_delta_scan (through the C ABI) against the fp64
+oracle on the same seeded inputs.  Masks and nnz bit-exact; outputs within the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19608_amd import binding as da
+from paper_2507_19608_amd import workloads as wl
+from oracle import delta_oracle as orc
+from util import check_output, rand_walk, to_dev, unpack_mask
+
+pytestmark = pytest.mark.gpu
+
+MODES = [da.DA_SCORE_GATHER, da.DA_SCORE_REBASE]
+
+
+def run_case(Q, K, V, theta, W, dtype, mode, rows=None, q_heads=None, scale=0.0):
+    d = Q.shape[-1]
+    Og, maskg, nnzg = da.delta_attn_prefill(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), theta, W,
+                                            scale=scale, score_mode=mode)
+    torch.cuda.synchronize()
+    ref = orc.prefill(Q, K, V, theta, W, scale=None if scale == 0.0 else scale, rows=rows, q_heads=q_heads)
+    assert ref["knife"] == 0
+    assert (unpack_mask(maskg, d) == ref["mask"]).all()
+    assert (nnzg.cpu().numpy() == ref["nnz"]).all()
+    s_m, s_c = da.delta_attn_sparsity(nnzg, K.shape[2], d, W)
+    assert s_m == ref["s_m"] and s_c == pytest.approx(ref["s_c"], abs=1e-15)
+    r0, r1 = (0, Q.shape[2]) if rows is None else rows
+    heads = range(Q.shape[1]) if q_heads is None else q_heads
+    errs = [check_output(Og[:, h, r0:r1], ref["O"][:, h], dtype) for h in heads]
+    return max(errs)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_c1_fp32_single_head(mode):
+    x = wl.generate(wl.C1)
+    w = wl.C1
+    run_case(x["Q"], x["K"], x["V"], wl.theta_for(w), w.window, w.dtype, mode)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n,d,W,B,Hq,Hkv,theta", [
+    (333, 64, 32, 2, 4, 2, 0.2),     # several tiles, ragged tail, windows smaller than a tile
+    (200, 128, 64, 1, 4, 1, 0.15),
+    (257, 32, 7, 1, 2, 2, 0.3),      # odd window, tile spans many squares
+    (130, 96, 1, 1, 3, 1, 0.25),     # W = 1 (the paper's illustration), head_dim 96
+    (190, 64, 128, 1, 8, 2, 0.2),    # truncated last square
+    (64, 256, 16, 1, 1, 1, 0.2),     # largest head_dim
+])
+def test_small_shapes_bf16(mode, n, d, W, B, Hq, Hkv, theta):
+    Q = rand_walk(1, B, Hq, n, d)
+    K = rand_walk(2, B, Hkv, n, d)
+    V = rand_walk(3, B, Hkv, n, d)
+    run_case(Q, K, V, theta, W, "bf16", mode)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n,d,W,theta", [(300, 64, 32, 0.1), (150, 128, 50, 0.05)])
+def test_small_shapes_fp32(mode, n, d, W, theta):
+    Q = rand_walk(4, 1, 2, n, d, "f32")
+    K = rand_walk(5, 1, 1, n, d, "f32", step=0.05)
+    V = rand_walk(6, 1, 1, n, d, "f32")
+    run_case(Q, K, V, theta, W, "f32", mode, scale=0.2)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_degenerate_cases(mode):
+    B, Hq, Hkv, n, d = 1, 2, 1, 150, 64
+    Q, K, V = rand_walk(7, B, Hq, n, d), rand_walk(8, B, Hkv, n, d), rand_walk(9, B, Hkv, n, d)
+    run_case(Q, K, V, 0.0, 16, "bf16", mode)                 # theta = 0: dense attention
+    run_case(Q, K, V, 0.3, n, "bf16", mode)                  # window covers the sequence
+    run_case(Q, K, V, 0.3, 100000, "bf16", mode)
+    run_case(Q, K, V, float("inf"), 16, "bf16", mode)        # nothing fires after the basis
+    Kc = np.tile(K[:, :, :1], (1, 1, n, 1))                   # constant keys
+    run_case(Q, Kc, V, 0.2, 16, "bf16", mode)
+    Kall = wl.round_to_dtype(np.cumsum(np.ones((B, Hkv, n, d)), axis=2) * 0.75, "bf16")  # every entry fires
+    run_case(Q * 0.05, Kall * 0.02, V, 0.01, 16, "bf16", mode)
+    run_case(Q[:, :, :1], K[:, :, :1], V[:, :, :1], 0.2, 4, "bf16", mode)   # a single token
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_c2_llama_shape_full(mode):
+    w = wl.C2
+    x = wl.generate(w)
+    run_case(x["Q"], x["K"], x["V"], wl.theta_for(w), w.window, w.dtype, mode)
+
+
+def _sampled(w, mode, row_ranges, heads):
+    x = wl.generate(w)
+    d = w.head_dim
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    theta = wl.theta_for(w)
+    Og, maskg, nnzg = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+    torch.cuda.synchronize()
+    first = True
+    for rows in row_ranges:
+        ref = orc.prefill(x["Q"], x["K"], x["V"], theta, w.window, rows=rows, q_heads=heads)
+        if first:   # masks of every unit, all rows
+            assert (unpack_mask(maskg, d) == ref["mask"]).all()
+            assert (nnzg.cpu().numpy() == ref["nnz"]).all()
+            s_m, _ = da.delta_attn_sparsity(nnzg, w.seq_len, d, w.window)
+            assert s_m == ref["s_m"]
+            first = False
+        for h in heads:
+            check_output(Og[:, h, rows[0]:rows[1]], ref["O"][:, h], w.dtype)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_c3_bitnet_shape_sampled(mode):
+    _sampled(wl.C3, mode, [(0, 40), (2030, 2070), (4064, 4096)], [0, 7, 19])
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_c5_long_context_sampled(mode):
+    _sampled(wl.C5, mode, [(500, 530), (4090, 4110), (8170, 8192)], [3, 16])
+
+
+def test_c5_sweep_masks_and_sparsity():
+    """Delta masks over the compaction-density sweep (theta x jump rate): bit-exact, one unit each."""
+    for w in wl.C5_SWEEP:
+        K = wl.generate(w, ("K",), batch_ids=[1])["K"][:, 2:3]
+        theta = wl.theta_for(w)
+        maskg, nnzg, khat = da.delta_attn_delta_scan(to_dev(K, "bf16"), theta, want_khat=True)
+        m, _, Kh, knife = orc.delta_scan(K[0, 0], theta)
+        assert knife == 0
+        assert (unpack_mask(maskg, w.head_dim)[0, 0] == m).all()
+        assert int(nnzg[0, 0]) == int(m.sum())
+        assert (khat.double().cpu().numpy()[0, 0] == Kh).all()
+
+
+def test_binding_rejects_bad_arguments():
+    Q = torch.zeros(1, 4, 64, 64, dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros(1, 2, 64, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill(Q, K, K, -1.0, 8)
+    assert e.value.status == 1
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill(Q, K, K, 0.1, 8, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 3
+    with pytest.raises(ValueError):
+        da.delta_attn_prefill(Q, K.float(), K.float(), 0.1, 8)
