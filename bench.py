@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid delta attention hot path on one MI355X.
+
+One "step" = one pass of the whole prefill path (delta scan, compaction, hybrid attention) over one
+synthetic batch already resident in HBM.  Headline workload: the 8K-token long-context
+configuration (batch 4, 20 query / 5 KV heads, head_dim 128, window 512) at the ~60 % delta
+sparsity point with 5 % jump rate.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5|C3|C2] [--mode gather|rebase]
+                    [--no-decode] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
+PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS = 78.6   # same without packed-fp32 instructions (not emitted by this build)
+
+
+def outside_rows(n, W):
+    """rows_out[j]: number of query rows for which key column j lies outside the exact window."""
+    import numpy as np
+    j = np.arange(n)
+    return np.maximum(0, n - np.minimum(n, (j // W + 1) * W))
+
+
+def prefill_bench(args, da, wl, torch, np):
+    w = {"C5": wl.C5, "C3": wl.C3, "C2": wl.C2}[args.workload]
+    mode = da.DA_SCORE_GATHER if args.mode == "gather" else da.DA_SCORE_REBASE
+    theta = wl.theta_for(w)
+    x = wl.generate(w)
+    tdt = torch.bfloat16
+    Q, K, V = (torch.from_numpy(x[k]).to(tdt).cuda().contiguous() for k in "QKV")
+    B, Hq, n, d = Q.shape
+    Hkv = K.shape[1]
+    g = Hq // Hkv
+    p = da.make_params(Q, K, w.window, theta, 0.0, mode)
+    ws = torch.empty(da.delta_attn_prefill_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    out = (torch.empty_like(Q), torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device="cuda"),
+           torch.empty((B, Hkv), dtype=torch.int64, device="cuda"))
+
+    def step():
+        da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    da.delta_attn_stage_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = da.delta_attn_stage_timing_read()
+    da.delta_attn_stage_timing_enable(False)
+
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = B * n / (dt / args.steps)
+    s_m, s_c = da.delta_attn_sparsity(out[2], n, d, w.window)
+
+    # algorithmic work of the attention kernel (dominant kernel)
+    mask = out[1].cpu().numpy().view(np.uint32)
+    nnz_col = np.bitwise_count(mask).sum(axis=-1).astype(np.int64)   # [B, Hkv, n]
+    rows_out = outside_rows(n, w.window)
+    sparse_macs = float((nnz_col * rows_out[None, None, :]).sum()) * g
+    outside_pairs = float(rows_out.sum()) * B * Hq
+    causal_pairs = n * (n + 1) / 2.0 * B * Hq
+    window_pairs = causal_pairs - outside_pairs
+    attn_ms = stages["attn"][0] / max(stages["attn"][1], 1)
+    if mode == da.DA_SCORE_GATHER:
+        alu_flops = 2.0 * sparse_macs
+        mfma_flops = 2.0 * (window_pairs + causal_pairs) * d
+        roof = {"bound": "alu", "achieved": alu_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_VALU_F32_TFLOPS,
+                "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof["peak_scalar_issue_fp32"] = PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS
+        roof["frac_scalar_issue_fp32"] = roof["achieved"] / PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS
+    else:
+        alu_flops = 0.0
+        mfma_flops = 2.0 * (2.0 * causal_pairs) * d
+        roof = {"bound": "mfma", "achieved": mfma_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16_TFLOPS,
+                "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+    es = 2
+    hbm_bytes = (2 * B * Hq * n * d + 2 * B * Hkv * n * d) * es + B * Hkv * n * d / 8
+    roof.update({"traffic": None, "kernel": "prefill attention", "kernel_ms": attn_ms,
+                 "algorithmic_sparse_gmac": sparse_macs / 1e9, "row_weighted_density": sparse_macs / max(outside_pairs * d, 1),
+                 "mfma_tflops": mfma_flops / (attn_ms * 1e-3) / 1e12,
+                 "mfma_frac": mfma_flops / (attn_ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+                 "hbm_gbs": hbm_bytes / (attn_ms * 1e-3) / 1e9, "hbm_frac": hbm_bytes / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+    res = {
+        "metric": "hybrid delta-attention tokens/s per layer at ~60% sparsity",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.key()}: prefill B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} W{w.window} theta={theta:.6g} "
+                               f"p_jump={w.p_jump}", "score_mode": args.mode, "s_m": s_m, "s_c": s_c},
+        "stage_ms": {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items() if v[1]},
+        "roofline": roof,
+    }
+    return res, (w, x, theta)
+
+
+def cpu_baseline(w, x, theta, np):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: blocks of 32 query
+    rows spread evenly over the sequence, every query head of batch entry 0."""
+    from oracle import delta_oracle as orc
+    n, d, g = w.seq_len, w.head_dim, w.n_q_heads // w.n_kv_heads
+    nblocks, blk = 64, 32
+    starts = [int((k + 0.5) * n / nblocks) - blk // 2 for k in range(nblocks)]
+    t0 = time.perf_counter()
+    for hk in range(w.n_kv_heads):
+        _, dK, _, _ = orc.delta_scan(x["K"][0, hk], theta)
+        for h in range(hk * g, (hk + 1) * g):
+            for s in starts:
+                orc.hybrid_rows(x["Q"][0, h], x["K"][0, hk], x["V"][0, hk], dK, w.window, 0, None, 0, (s, s + blk))
+    dt = time.perf_counter() - t0
+    rows = nblocks * blk
+    return {"value": rows / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{rows} query rows ({nblocks} blocks of {blk}, evenly spread) x all {w.n_q_heads} query heads "
+                      f"of batch entry 0 of the same workload, fp64, {dt:.1f} s"}
+
+
+def decode_bench(args, da, wl, torch, np):
+    w = wl.C4
+    theta = wl.theta_for(w)
+    x = wl.generate(w)
+    tdt = torch.bfloat16
+    Q, K, V = (torch.from_numpy(x[k]).to(tdt).cuda().contiguous() for k in "QKV")
+    del x
+    B, Hq, L, d = Q.shape
+    Hkv, n, steps = K.shape[1], w.seq_len, w.decode_steps
+    cache = da.Cache(B, Hq, Hkv, d, L, w.window, theta, tdt)
+    qs = [Q[:, :, t].contiguous() for t in range(n, L)]
+    ks = [K[:, :, t].contiguous() for t in range(n, L)]
+    vs = [V[:, :, t].contiguous() for t in range(n, L)]
+    Qp, Kp, Vp = Q[:, :, :n].contiguous(), K[:, :, :n].contiguous(), V[:, :, :n].contiguous()
+    o = torch.empty_like(qs[0])
+    mrow = torch.empty((B, Hkv, d // 32), dtype=torch.int32, device="cuda")
+
+    def run(timed):
+        cache.reset()
+        da.delta_attn_prefill(Qp, Kp, Vp, theta, w.window, cache=cache)
+        torch.cuda.synchronize()
+        if timed:
+            da.delta_attn_stage_timing_enable(True)
+        t0 = time.perf_counter()
+        for i in range(steps):
+            da.delta_attn_decode(cache, qs[i], ks[i], vs[i], out=o, mask_row=mrow)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run(False)
+    dt = run(True)
+    stages = da.delta_attn_stage_timing_read()
+    da.delta_attn_stage_timing_enable(False)
+    nnz = int(cache.nnz().sum())
+    s_m, s_c = da.delta_attn_sparsity(cache.nnz(), L, d, w.window)
+    units = B * Hkv
+    t_avg = n + (steps - 1) / 2.0 + 1
+    # algorithmic bytes per step: V rows, mask bits, surviving key values (bf16), raw-key ring, q and o
+    bytes_step = units * (t_avg * d * 2 + t_avg * d / 8 + (nnz / units) * (t_avg / L) * 2 + w.window * d * 2) \
+        + 2 * B * Hq * d * 2
+    chunk_ms = stages["chunk"][0] / max(stages["chunk"][1], 1)
+    cache.close()
+    return {"workload": f"{w.key()}: decode B{B} Hq{Hq} Hkv{Hkv} d{d} cached {n} + {steps} steps W_d{w.window} "
+                        f"theta={theta:.6g}", "value": B * steps / dt, "unit": "tokens/s",
+            "ms_per_step": dt / steps * 1e3, "s_m": s_m, "s_c": s_c,
+            "stage_ms": {k: v[0] / v[1] for k, v in stages.items() if v[1]},
+            "roofline": {"bound": "hbm", "kernel": "decode chunk", "kernel_ms": chunk_ms,
+                         "achieved": bytes_step / (chunk_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": bytes_step / (chunk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                         "algorithmic_mb_per_step": bytes_step / 1e6}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C5", choices=["C5", "C3", "C2"])
+    ap.add_argument("--mode", default="gather", choices=["gather", "rebase"])
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build is a single-GPU kernel library; run with --gpus 1\n")
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2507_19608_amd import binding as da
+    from paper_2507_19608_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
+        sys.exit(1)
+    da.lib()
+    res, (w, x, theta) = prefill_bench(args, da, wl, torch, np)
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(w, x, theta, np)
+    del x
+    torch.cuda.empty_cache()
+    if not args.no_decode:
+        res["decode"] = decode_bench(args, da, wl, torch, np)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -62,6 +62,22 @@ typedef struct da_cache da_cache;   /* decode-time cache (Sec. III-C), opaque */
 
 const char *delta_attn_version(void);
 const char *delta_attn_status_string(da_status s);
+/* Text of the last DA_ERR_HIP on the calling thread: "<stage>: <hip error name> (<description>)";
+ * empty if none occurred.  Points to thread-local storage owned by the library. */
+const char *delta_attn_last_error(void);
+
+/*
+ * Per-stage timing for benchmarks.  While enabled, prefill and decode calls bracket each of their
+ * kernels with HIP events on the call's own stream (at most 8192 brackets between reads).
+ * delta_attn_stage_timing_read, called after the caller has synchronised those streams, sums the
+ * elapsed milliseconds and the number of launches per stage since the previous read and returns
+ * the number of brackets read (-1 on a null pointer).  Both arrays have DA_NUM_STAGES entries.
+ * Not thread-safe; meant for a single benchmarking thread.
+ */
+enum { DA_STAGE_SCAN = 0, DA_STAGE_EMIT = 1, DA_STAGE_ATTN = 2, DA_STAGE_CACHE_FILL = 3,
+       DA_STAGE_APPEND = 4, DA_STAGE_CHUNK = 5, DA_STAGE_COMBINE = 6, DA_NUM_STAGES = 7 };
+void delta_attn_stage_timing_enable(int32_t on);
+int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_stage);
 
 /* Eq. 5: min(floor(gamma * n), w_max), clamped to >= 1.  Host only. */
 int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);

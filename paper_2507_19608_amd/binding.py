@@ -16,7 +16,8 @@ DA_F32, DA_BF16 = 0, 1
 DA_SCORE_GATHER, DA_SCORE_REBASE = 0, 1
 
 EXPORTS = [
-    "delta_attn_version", "delta_attn_status_string", "delta_attn_window_from_gamma",
+    "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
+    "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
     "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
@@ -34,7 +35,8 @@ class PrefillParams(ctypes.Structure):
 class DeltaAttnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (da_status {status})")
+        detail = lib().delta_attn_last_error().decode() if status == 5 else ""
+        super().__init__(f"{where}: {status_string(status)} (da_status {status}) {detail}")
 
 
 _lib = None
@@ -51,6 +53,11 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_version.restype = ctypes.c_char_p
         L.delta_attn_status_string.restype = ctypes.c_char_p
         L.delta_attn_status_string.argtypes = [ctypes.c_int]
+        L.delta_attn_last_error.restype = ctypes.c_char_p
+        L.delta_attn_stage_timing_enable.restype = None
+        L.delta_attn_stage_timing_enable.argtypes = [i32]
+        L.delta_attn_stage_timing_read.restype = i32
+        L.delta_attn_stage_timing_read.argtypes = [ctypes.POINTER(dbl), ctypes.POINTER(i32)]
         L.delta_attn_window_from_gamma.restype = i32
         L.delta_attn_window_from_gamma.argtypes = [i32, dbl, i32]
         L.delta_attn_prefill_workspace_bytes.restype = ctypes.c_size_t
@@ -89,6 +96,21 @@ def version() -> str:
 
 def delta_attn_window_from_gamma(n: int, gamma: float, w_max: int) -> int:
     return int(lib().delta_attn_window_from_gamma(n, gamma, w_max))
+
+
+STAGES = ("scan", "emit", "attn", "cache_fill", "append", "chunk", "combine")
+
+
+def delta_attn_stage_timing_enable(on: bool):
+    lib().delta_attn_stage_timing_enable(1 if on else 0)
+
+
+def delta_attn_stage_timing_read():
+    """{stage: (total_ms, launches)} since the previous read; synchronise the device first."""
+    ms = (ctypes.c_double * len(STAGES))()
+    calls = (ctypes.c_int32 * len(STAGES))()
+    lib().delta_attn_stage_timing_read(ms, calls)
+    return {name: (ms[i], calls[i]) for i, name in enumerate(STAGES)}
 
 
 def _check(st: int, where: str):

@@ -56,6 +56,15 @@ inline float score_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f
 
 extern "C" {
 
+const char *delta_attn_last_error(void) { return last_error_text(); }
+
+void delta_attn_stage_timing_enable(int32_t on) { timing_enable(on != 0); }
+
+int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_stage) {
+    if (!ms_per_stage || !calls_per_stage) return -1;
+    return timing_collect(ms_per_stage, calls_per_stage);
+}
+
 const char *delta_attn_version(void) { return "delta_attn 0.1 (gfx950)"; }
 
 const char *delta_attn_status_string(da_status s) {
@@ -89,9 +98,10 @@ da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint3
     if (st != DA_OK) return st;
     if (!K || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
+    (void)hipGetLastError();
     launch_delta_scan(p->dtype, K, k_hat, mask_bits, nnz, p->batch * p->n_kv_heads, p->seq_len, p->head_dim,
                       p->theta, s);
-    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+    return launch_ok("delta_scan") ? DA_OK : DA_ERR_HIP;
 }
 
 da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
@@ -113,9 +123,17 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     uint32_t *counts = (uint32_t *)(ws + w.counts);
     const int units = p->batch * p->n_kv_heads;
 
+    (void)hipGetLastError();   // do not inherit an earlier, unrelated error
+    stage_begin(kStageScan, s);
     launch_delta_scan(p->dtype, K, khat, mask_bits, nnz, units, p->seq_len, p->head_dim, p->theta, s);
-    if (p->score_mode == DA_SCORE_GATHER || cache)
+    stage_end(kStageScan, s);
+    if (!launch_ok("delta_scan")) return DA_ERR_HIP;
+    if (p->score_mode == DA_SCORE_GATHER || cache) {
+        stage_begin(kStageEmit, s);
         launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, units, p->seq_len, p->head_dim, s);
+        stage_end(kStageEmit, s);
+        if (!launch_ok("emit_entries")) return DA_ERR_HIP;
+    }
 
     PrefillArgs a;
     a.dtype = p->dtype;
@@ -134,9 +152,18 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.O = O;
     a.ents = ents;
     a.counts = counts;
-    if (!launch_prefill_generic(a, s)) return DA_ERR_UNSUPPORTED;
-    if (cache) cache_fill_from_prefill(cache, p, K, V, khat, mask_bits, counts, nnz, s);
-    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+    stage_begin(kStageAttn, s);
+    const bool launched = launch_prefill_generic(a, s);
+    stage_end(kStageAttn, s);
+    if (!launched) return DA_ERR_UNSUPPORTED;
+    if (!launch_ok("prefill_generic")) return DA_ERR_HIP;
+    if (cache) {
+        stage_begin(kStageCacheFill, s);
+        cache_fill_from_prefill(cache, p, K, V, khat, mask_bits, counts, nnz, s);
+        stage_end(kStageCacheFill, s);
+        if (!launch_ok("cache_fill")) return DA_ERR_HIP;
+    }
+    return DA_OK;
 }
 
 da_status delta_attn_sparsity(const uint64_t *nnz_dev, int32_t batch, int32_t n_kv_heads, int64_t rows,

@@ -247,8 +247,10 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const int t = (int)c->len;
     const int units = c->B * c->Hkv;
     const float sc = (c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d)) * 1.4426950408889634f;
+    stage_begin(kStageAppend, s);
     hipLaunchKernelGGL(decode_append_kernel<T>, dim3(units), dim3(64), 0, s, *c, (const T *)k, (const T *)v,
                        mask_row, t);
+    stage_end(kStageAppend, s);
     const int nchunks = t / kChunk + 1;
     const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
     static bool attr_done = false;   // per instantiation; d = 256 needs slightly more than 64 KiB
@@ -257,8 +259,12 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
                                   (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)));
         attr_done = true;
     }
+    stage_begin(kStageChunk, s);
     hipLaunchKernelGGL(decode_chunk_kernel<T>, dim3(nchunks, units), dim3(64), lds, s, *c, (const T *)q, t, sc);
+    stage_end(kStageChunk, s);
+    stage_begin(kStageCombine, s);
     hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+    stage_end(kStageCombine, s);
 }
 
 void free_all(da_cache *c) {
@@ -363,7 +369,7 @@ da_status delta_attn_cache_reset(da_cache *c, void *hip_stream) {
     if (!c) return DA_ERR_INVALID_ARG;
     launch_fill_u64(c->nnz, 0, c->B * c->Hkv, (hipStream_t)hip_stream);
     c->len = 0;
-    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+    return launch_ok("cache_reset") ? DA_OK : DA_ERR_HIP;
 }
 
 int64_t delta_attn_cache_length(const da_cache *c) { return c ? c->len : -1; }
@@ -375,11 +381,12 @@ da_status delta_attn_decode(da_cache *c, const void *q_new, const void *k_new, c
     if (!c || !q_new || !k_new || !v_new || !o) return DA_ERR_INVALID_ARG;
     if (c->len >= c->max_seq) return DA_ERR_STATE;
     hipStream_t s = (hipStream_t)hip_stream;
+    (void)hipGetLastError();
     if (c->dtype == DA_F32)
         decode_launch<float>(c, q_new, k_new, v_new, o, mask_row, s);
     else
         decode_launch<bf16_t>(c, q_new, k_new, v_new, o, mask_row, s);
-    if (hipGetLastError() != hipSuccess) return DA_ERR_HIP;
+    if (!launch_ok("decode")) return DA_ERR_HIP;
     c->len += 1;
     return DA_OK;
 }

@@ -3,7 +3,77 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <stdio.h>
+
 namespace da {
+
+static thread_local char g_last_error[256] = "";
+
+bool launch_ok(const char *stage) {
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return true;
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%s)", stage, hipGetErrorName(e), hipGetErrorString(e));
+    return false;
+}
+
+const char *last_error_text() { return g_last_error; }
+
+// ---- stage timing: a pool of event pairs, filled in call order, summed and recycled by the reader
+namespace {
+constexpr int kMaxPairs = 8192;
+struct Pair {
+    hipEvent_t a, b;
+    int stage;
+};
+bool g_timing = false;
+Pair g_pairs[kMaxPairs];
+int g_created = 0, g_used = 0, g_open[kNumStages];
+}  // namespace
+
+void stage_begin(int stage, hipStream_t s) {
+    if (!g_timing || g_used >= kMaxPairs) return;
+    if (g_used >= g_created) {
+        if (hipEventCreate(&g_pairs[g_created].a) != hipSuccess) return;
+        if (hipEventCreate(&g_pairs[g_created].b) != hipSuccess) return;
+        ++g_created;
+    }
+    g_pairs[g_used].stage = stage;
+    g_open[stage] = g_used;
+    (void)hipEventRecord(g_pairs[g_used].a, s);
+    ++g_used;
+}
+
+void stage_end(int stage, hipStream_t s) {
+    if (!g_timing || g_open[stage] < 0) return;
+    (void)hipEventRecord(g_pairs[g_open[stage]].b, s);
+    g_open[stage] = -1;
+}
+
+void timing_enable(bool on) {
+    g_timing = on;
+    g_used = 0;
+    for (int i = 0; i < kNumStages; ++i) g_open[i] = -1;
+}
+
+// Sums elapsed ms per stage over everything recorded since the last read; the caller has
+// synchronised the streams involved.  Returns the number of event pairs read.
+int timing_collect(double *ms_per_stage, int *calls_per_stage) {
+    for (int i = 0; i < kNumStages; ++i) {
+        ms_per_stage[i] = 0.0;
+        calls_per_stage[i] = 0;
+    }
+    int n = 0;
+    for (int i = 0; i < g_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_pairs[i].a, g_pairs[i].b) == hipSuccess) {
+            ms_per_stage[g_pairs[i].stage] += ms;
+            calls_per_stage[g_pairs[i].stage] += 1;
+            ++n;
+        }
+    }
+    g_used = 0;
+    return n;
+}
 
 // Sequential in t, parallel over channels: one lane per channel, one wave per 64 channels of a
 // (batch, KV head) unit.  The wave ballot of the threshold decision is the mask word itself.

@@ -5,6 +5,19 @@
 
 namespace da {
 
+// Checks hipGetLastError(); on failure records "<stage>: <hip error>" for delta_attn_last_error()
+// and returns false.
+bool launch_ok(const char *stage);
+const char *last_error_text();
+
+// Optional per-stage timing with HIP events recorded on the caller's stream (off by default).
+enum Stage { kStageScan = 0, kStageEmit, kStageAttn, kStageCacheFill, kStageAppend, kStageChunk, kStageCombine,
+             kNumStages };
+void stage_begin(int stage, hipStream_t s);   // no-ops unless timing is enabled
+void stage_end(int stage, hipStream_t s);
+void timing_enable(bool on);
+int timing_collect(double *ms_per_stage, int *calls_per_stage);
+
 struct PrefillArgs {
     int dtype;            // 0 f32, 1 bf16
     int B, Hq, Hkv, d, n, W;

@@ -60,13 +60,13 @@ def run_decode(Q, K, V, n, steps, theta, Wd, dtype, W_prefill=16, check_every=1,
 def test_decode_small(n, steps, d, Wd, B, Hq, Hkv, theta, dtype):
     L = n + steps
     step = 0.05 if dtype == "f32" else 0.15
-    Q, K, V = rand_walk(11, B, Hq, L, d, dtype), rand_walk(12, B, Hkv, L, d, dtype, step), rand_walk(13, B, Hkv, L, d, dtype)
+    Q, K, V = rand_walk(11, B, Hq, L, d, dtype), rand_walk(12, B, Hkv, L, d, dtype, step), rand_walk(13, B, Hkv, L, d, dtype, clip=3.5)
     run_decode(Q, K, V, n, steps, theta, Wd, dtype, scale=0.0 if dtype == "bf16" else 0.15)
 
 
 def test_decode_from_empty_cache_and_dense_limits():
     B, Hq, Hkv, L, d = 1, 2, 1, 40, 64
-    Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d)
+    Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d, clip=3.5)
     run_decode(Q, K, V, 0, 40, 0.2, 6, "bf16")            # first decoded token is the basis row
     run_decode(Q, K, V, 10, 30, 0.0, 3, "bf16")           # theta = 0: dense attention
     run_decode(Q, K, V, 10, 30, 0.4, 1000, "bf16")        # window covers everything

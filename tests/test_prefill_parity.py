@@ -50,7 +50,7 @@ def test_c1_fp32_single_head(mode):
 def test_small_shapes_bf16(mode, n, d, W, B, Hq, Hkv, theta):
     Q = rand_walk(1, B, Hq, n, d)
     K = rand_walk(2, B, Hkv, n, d)
-    V = rand_walk(3, B, Hkv, n, d)
+    V = rand_walk(3, B, Hkv, n, d, clip=3.5)
     run_case(Q, K, V, theta, W, "bf16", mode)
 
 
@@ -59,22 +59,22 @@ def test_small_shapes_bf16(mode, n, d, W, B, Hq, Hkv, theta):
 def test_small_shapes_fp32(mode, n, d, W, theta):
     Q = rand_walk(4, 1, 2, n, d, "f32")
     K = rand_walk(5, 1, 1, n, d, "f32", step=0.05)
-    V = rand_walk(6, 1, 1, n, d, "f32")
+    V = rand_walk(6, 1, 1, n, d, "f32", clip=3.5)
     run_case(Q, K, V, theta, W, "f32", mode, scale=0.2)
 
 
 @pytest.mark.parametrize("mode", MODES)
 def test_degenerate_cases(mode):
     B, Hq, Hkv, n, d = 1, 2, 1, 150, 64
-    Q, K, V = rand_walk(7, B, Hq, n, d), rand_walk(8, B, Hkv, n, d), rand_walk(9, B, Hkv, n, d)
+    Q, K, V = rand_walk(7, B, Hq, n, d), rand_walk(8, B, Hkv, n, d), rand_walk(9, B, Hkv, n, d, clip=3.5)
     run_case(Q, K, V, 0.0, 16, "bf16", mode)                 # theta = 0: dense attention
     run_case(Q, K, V, 0.3, n, "bf16", mode)                  # window covers the sequence
     run_case(Q, K, V, 0.3, 100000, "bf16", mode)
     run_case(Q, K, V, float("inf"), 16, "bf16", mode)        # nothing fires after the basis
     Kc = np.tile(K[:, :, :1], (1, 1, n, 1))                   # constant keys
     run_case(Q, Kc, V, 0.2, 16, "bf16", mode)
-    Kall = wl.round_to_dtype(np.cumsum(np.ones((B, Hkv, n, d)), axis=2) * 0.75, "bf16")  # every entry fires
-    run_case(Q * 0.05, Kall * 0.02, V, 0.01, 16, "bf16", mode)
+    Kall = wl.round_to_dtype(np.cumsum(np.ones((B, Hkv, n, d)), axis=2) * 0.015, "bf16")  # every entry fires
+    run_case(wl.round_to_dtype(Q * 0.05, "bf16"), Kall, V, 0.005, 16, "bf16", mode)
     run_case(Q[:, :, :1], K[:, :, :1], V[:, :, :1], 0.2, 4, "bf16", mode)   # a single token
 
 

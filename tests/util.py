@@ -20,9 +20,14 @@ def unpack_mask(bits: torch.Tensor, d: int) -> np.ndarray:
     return out.reshape(*w.shape[:-1], d)
 
 
-def rand_walk(seed, B, H, n, d, dtype="bf16", step=0.15):
+def rand_walk(seed, B, H, n, d, dtype="bf16", step=0.15, clip=None):
+    """Random-walk rows (temporally correlated like real keys).  `clip` bounds the magnitude: value
+    tensors are kept below 4 so that rounding the output to bf16 (half an ulp = 2^-8 relative)
+    stays well inside the absolute 2e-2 tolerance."""
     rng = np.random.default_rng(seed)
     x = np.cumsum(step * rng.standard_normal((B, H, n, d)), axis=2) + rng.standard_normal((B, H, 1, d))
+    if clip is not None:
+        x = np.clip(x, -clip, clip)
     return wl.round_to_dtype(x, dtype)
 
 
