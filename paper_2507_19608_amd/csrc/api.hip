@@ -1,6 +1,7 @@
 // C ABI of the hybrid delta attention library: argument checks, workspace carving, launches.
 #include <math.h>
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 
 #include "../../include/delta_attn.h"
@@ -17,7 +18,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, ents, counts, total;
+    size_t khat, ents, counts, vt, total;
 };
 
 da_status check_params(const da_prefill_params *p) {
@@ -46,8 +47,19 @@ WsLayout layout(const da_prefill_params *p) {
     off += align_up(rows * p->head_dim * sizeof(Entry));
     w.counts = off;
     off += align_up(rows * sizeof(uint32_t));
+    w.vt = off;
+    off += align_up(units * (size_t)p->head_dim * prefill_mfma_n_pad(p->seq_len) * 2);
     w.total = off;
     return w;
+}
+
+// DELTA_ATTN_FORCE_GENERIC=1 routes every prefill through the generic vector-ALU kernel (testing aid)
+inline bool force_generic() {
+    static const bool v = [] {
+        const char *e = getenv("DELTA_ATTN_FORCE_GENERIC");
+        return e && e[0] == '1';
+    }();
+    return v;
 }
 
 inline float score_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f / sqrtf((float)d); }
@@ -153,7 +165,11 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.ents = ents;
     a.counts = counts;
     stage_begin(kStageAttn, s);
-    const bool launched = launch_prefill_generic(a, s);
+    bool launched = true;
+    if (prefill_mfma_supported(a) && !force_generic())
+        launch_prefill_mfma(a, ws + w.vt, s);
+    else
+        launched = launch_prefill_generic(a, s);
     stage_end(kStageAttn, s);
     if (!launched) return DA_ERR_UNSUPPORTED;
     if (!launch_ok("prefill_generic")) return DA_ERR_HIP;

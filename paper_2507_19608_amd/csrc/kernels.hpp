@@ -37,5 +37,9 @@ void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint3
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if
 // the head_dim has no instantiation.
 bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);
+// Matrix-core path: bf16, head_dim 64 or 128.  vt is scratch for V^T: units * d * prefill_mfma_n_pad(n) bf16.
+bool prefill_mfma_supported(const PrefillArgs &a);
+int prefill_mfma_n_pad(int n);
+void launch_prefill_mfma(const PrefillArgs &a, void *vt, hipStream_t s);
 
 }  // namespace da
