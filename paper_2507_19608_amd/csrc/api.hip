@@ -18,7 +18,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, ents, counts, vt, total;
+    size_t khat, ents, counts, nch8, vt, total;
 };
 
 da_status check_params(const da_prefill_params *p) {
@@ -44,9 +44,11 @@ WsLayout layout(const da_prefill_params *p) {
     w.khat = off;
     off += align_up(rows * p->head_dim * elt_size(p->dtype));
     w.ents = off;
-    off += align_up(rows * p->head_dim * sizeof(Entry));
+    off += align_up(rows * p->head_dim * 8);   // EntryChunk storage: 8 bytes per possible entry
     w.counts = off;
     off += align_up(rows * sizeof(uint32_t));
+    w.nch8 = off;
+    off += align_up(units * (size_t)prefill_mfma_n_pad(p->seq_len));
     w.vt = off;
     off += align_up(units * (size_t)p->head_dim * prefill_mfma_n_pad(p->seq_len) * 2);
     w.total = off;
@@ -133,6 +135,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     void *khat = ws + w.khat;
     void *ents = ws + w.ents;
     uint32_t *counts = (uint32_t *)(ws + w.counts);
+    uint8_t *nch8 = (uint8_t *)(ws + w.nch8);
     const int units = p->batch * p->n_kv_heads;
 
     (void)hipGetLastError();   // do not inherit an earlier, unrelated error
@@ -142,7 +145,8 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
     if (p->score_mode == DA_SCORE_GATHER || cache) {
         stage_begin(kStageEmit, s);
-        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, units, p->seq_len, p->head_dim, s);
+        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, units, p->seq_len,
+                            prefill_mfma_n_pad(p->seq_len), p->head_dim, s);
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
     }
@@ -164,6 +168,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.O = O;
     a.ents = ents;
     a.counts = counts;
+    a.nch8 = nch8;
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a) && !force_generic())

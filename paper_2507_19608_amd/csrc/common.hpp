@@ -8,12 +8,14 @@ namespace da {
 typedef unsigned short bf16_t;   // raw bfloat16 bits
 
 constexpr int kWave = 64;
-constexpr int kGroup = 4;        // compacted entry lists are padded to a multiple of this
+constexpr int kGroup = 8;        // compacted entry lists are padded to a multiple of this (one "chunk")
 
-// One surviving delta entry of a key column: channel index and delta value (binary32).
-struct __attribute__((aligned(8))) Entry {
-    uint32_t chan;
-    float delta;
+// Compacted delta entries of a key column are stored in chunks of kGroup entries: 8 channel
+// indices (uint32) followed by 8 delta values (binary32), 64 bytes.  Unused slots hold channel 0
+// with delta 0.  A column of head_dim d owns room for d / 8 chunks.
+struct __attribute__((aligned(64))) EntryChunk {
+    uint32_t chan[8];
+    float delta[8];
 };
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }

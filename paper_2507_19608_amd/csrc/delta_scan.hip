@@ -130,13 +130,14 @@ __global__ __launch_bounds__(64) void delta_scan_kernel(const T *__restrict__ K,
 }
 
 // One wave per key column: ballot + prefix count turn the mask row into a dense list of
-// (channel, delta) pairs, padded with (0, 0.0f) to a multiple of kGroup.  The list of column j
-// of a unit starts at entry (unit * n + j) * d; counts holds the unpadded length.
+// (channel, delta) pairs in EntryChunk form, padded with (0, 0.0f) to whole chunks and to at
+// least one chunk.  The chunks of column j of a unit start at chunk (unit * n + j) * d / 8;
+// counts holds the unpadded length, nch8 (stride n_pad per unit) the number of chunks.
 template <typename T>
 __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__ K, const T *__restrict__ Khat,
                                                            const uint32_t *__restrict__ mask_bits,
-                                                           Entry *__restrict__ ents, uint32_t *__restrict__ counts,
-                                                           int n, int d) {
+                                                           EntryChunk *__restrict__ ents, uint32_t *__restrict__ counts,
+                                                           uint8_t *__restrict__ nch8, int n, int n_pad, int d) {
     const int unit = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
     const T *Kp = K + row * d;
     const T *Hprev = Khat + (row - (j > 0 ? 1 : 0)) * d;
     const uint32_t *Mp = mask_bits + row * wpr;
-    Entry *out = ents + row * d;
+    EntryChunk *out = ents + row * (d / kGroup);
     uint32_t off = 0;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int c = c0 + lane;
@@ -160,21 +161,23 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
         }
         const uint64_t b = __ballot(bit);
         if (bit) {
-            Entry e;
-            e.chan = (uint32_t)c;
-            e.delta = delta;
-            out[off + lanes_below(b)] = e;
+            const uint32_t slot = off + lanes_below(b);
+            out[slot / kGroup].chan[slot % kGroup] = (uint32_t)c;
+            out[slot / kGroup].delta[slot % kGroup] = delta;
         }
         off += __popcll(b);
     }
-    const uint32_t padded = (off + kGroup - 1) & ~(uint32_t)(kGroup - 1);
+    uint32_t padded = (off + kGroup - 1) & ~(uint32_t)(kGroup - 1);
+    if (padded == 0) padded = kGroup;
     if (off + lane < padded) {
-        Entry e;
-        e.chan = 0;
-        e.delta = 0.f;
-        out[off + lane] = e;
+        const uint32_t slot = off + lane;
+        out[slot / kGroup].chan[slot % kGroup] = 0u;
+        out[slot / kGroup].delta[slot % kGroup] = 0.f;
     }
-    if (lane == 0) counts[row] = off;
+    if (lane == 0) {
+        counts[row] = off;
+        nch8[(size_t)unit * n_pad + j] = (uint8_t)(padded / kGroup);
+    }
 }
 
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n) {
@@ -201,14 +204,14 @@ void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits
 }
 
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, int units, int n, int d, hipStream_t s) {
+                         uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s) {
     dim3 grid((n + 3) / 4, units), block(256);
     if (dtype == 0)
         hipLaunchKernelGGL(emit_entries_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)Khat,
-                           mask_bits, (Entry *)ents, counts, n, d);
+                           mask_bits, (EntryChunk *)ents, counts, nch8, n, n_pad, d);
     else
         hipLaunchKernelGGL(emit_entries_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K,
-                           (const bf16_t *)Khat, mask_bits, (Entry *)ents, counts, n, d);
+                           (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, n, n_pad, d);
 }
 
 }  // namespace da

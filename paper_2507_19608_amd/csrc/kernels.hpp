@@ -25,15 +25,16 @@ struct PrefillArgs {
     int rebase;           // 1: outside scores from q . k_hat instead of the entry lists
     const void *Q, *K, *V, *Khat;
     void *O;
-    const void *ents;     // Entry lists, column (unit, j) at (unit * n + j) * d
+    const void *ents;     // EntryChunk lists, column (unit, j) at chunk (unit * n + j) * d / 8
     const uint32_t *counts;
+    const uint8_t *nch8;  // chunks per column, stride prefill_mfma_n_pad(n) per unit
 };
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, uint64_t *nnz, int units,
                        int n, int d, float theta, hipStream_t s);
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, int units, int n, int d, hipStream_t s);
+                         uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if
 // the head_dim has no instantiation.
 bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);

@@ -18,7 +18,7 @@ struct KArgs {
     const T *__restrict__ V;
     const T *__restrict__ Khat;
     T *__restrict__ O;
-    const Entry *__restrict__ ents;
+    const EntryChunk *__restrict__ ents;
     const uint32_t *__restrict__ counts;
     int Hq, Hkv, n, W, rebase;
     float scale_log2;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
     const T *Kp = a.K + (size_t)unit * n * D;
     const T *Vp = a.V + (size_t)unit * n * D;
     const T *Hp = a.Khat + (size_t)unit * n * D;
-    const Entry *Ep = a.ents + (size_t)unit * n * D;
+    const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
     const uint32_t *Cp = a.counts + (size_t)unit * n;
 
     for (int c = 0; c < D; ++c) qt[c * 64 + lane] = valid ? load_f32(Qp, (size_t)i * D + c) : 0.f;
@@ -72,13 +72,11 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
                         for (int c = 0; c < D; ++c) approx = fmaf(qt[c * 64 + lane], load_f32(hj, c), approx);
                     } else {
                         const uint32_t cnt = Cp[j];
-                        const Entry *e = Ep + (size_t)j * D;
+                        const EntryChunk *e = Ep + (size_t)j * (D / kGroup);
                         for (uint32_t k = 0; k < cnt; k += kGroup) {
+                            const EntryChunk ch = e[k / kGroup];
 #pragma unroll
-                            for (int u = 0; u < kGroup; ++u) {
-                                const Entry en = e[k + u];
-                                r = fmaf(qt[en.chan * 64 + lane], en.delta, r);
-                            }
+                            for (int u = 0; u < kGroup; ++u) r = fmaf(qt[ch.chan[u] * 64 + lane], ch.delta[u], r);
                         }
                         approx = r;
                     }
@@ -131,7 +129,7 @@ static void launch_one(const PrefillArgs &p, hipStream_t s) {
     a.V = (const T *)p.V;
     a.Khat = (const T *)p.Khat;
     a.O = (T *)p.O;
-    a.ents = (const Entry *)p.ents;
+    a.ents = (const EntryChunk *)p.ents;
     a.counts = p.counts;
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;

@@ -31,6 +31,8 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) _Float16 half4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
@@ -44,8 +46,8 @@ struct MfmaArgs {
     const bf16_t *__restrict__ Khat;
     const bf16_t *__restrict__ Vt;      // [unit][D][n_pad]
     bf16_t *__restrict__ O;
-    const Entry *__restrict__ ents;
-    const uint32_t *__restrict__ counts;
+    const EntryChunk *__restrict__ ents;
+    const uint8_t *__restrict__ nch8;
     int Hq, Hkv, n, n_pad, W, rebase;
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     float scale_log2;
@@ -57,18 +59,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+
 template <int D>
 __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     extern __shared__ char lds_raw[];
     _Float16 *qt = (_Float16 *)lds_raw;                                   // [D][256] fp16, scaled by 2^qexp
-    float *ubuf = (float *)(lds_raw + (size_t)D * kRows * 2);             // [2][kTB][256]
+    float *ubuf = (float *)(lds_raw + (size_t)D * kRows * 2);             // [kTB][256]; then 8 entry rings
     __shared__ float red[kWaves];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction; tell the compiler
     const int half = lane >> 5, li = lane & 31;
 
-    // ---- which tile: heavy (late) row tiles first, units interleaved below them
+    // ---- which tile: within a unit, heavy (late) row tiles first
     int bid = blockIdx.x;
     const int per_unit = a.tiles * a.hgroups;
     const int unit = bid / per_unit;
@@ -85,8 +89,8 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const bf16_t *Kp = a.K + (size_t)unit * n * D;
     const bf16_t *Hp = a.Khat + (size_t)unit * n * D;
     const bf16_t *Vtp = a.Vt + (size_t)unit * D * a.n_pad;
-    const Entry *Ep = a.ents + (size_t)unit * n * D;
-    const uint32_t *Cp = a.counts + (size_t)unit * n;
+    const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
+    const uint8_t *Np = a.nch8 + (size_t)unit * a.n_pad;
 
     // score row sr = hh * RT + r  ->  query row i0 + r of head head0 + hh
     auto q_row_ptr = [&](int sr) -> const bf16_t * {
@@ -143,9 +147,6 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
     constexpr int KS = D / 16;     // k-steps of Q K^T
     constexpr int MT = D / 32;     // channel tiles of the output
-    u32x4 qreg[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
 
     f32x16 oacc[MT];
 #pragma unroll
@@ -161,39 +162,13 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
     __syncthreads();   // Q tile staged
 
-    // One block of PV: scores s[16] (already scaled, -inf where masked) for this lane's keys of block jb
-    auto softmax_pv = [&](float (&s)[16], int jb) {
-        float bm = s[0];
+    // V^T operands of one block: vreg[ka * MT + mt] for k-step ka, channel tile mt
+    auto load_v = [&](u32x4 (&vreg)[2 * MT], int jb) {
 #pragma unroll
-        for (int r = 1; r < 16; ++r) bm = fmaxf(bm, s[r]);
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
-        const float m_new = fmaxf(m_run, bm);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            p[r] = exp2f(s[r] - m_use);
-            psum += p[r];
-        }
-        l_run = l_run * alpha + psum;
-        if (__any(alpha != 1.f)) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
-        }
-#pragma unroll
-        for (int ka = 0; ka < 2; ++ka) {
-            u32x4 pb;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) pb[k] = pack_bf16x2(p[8 * ka + 2 * k], p[8 * ka + 2 * k + 1]);
-            const int key0 = jb + 16 * ka + 4 * half;
+        for (int ka = 0; ka < 2; ++ka)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const bf16_t *vrow = Vtp + (size_t)(mt * 32 + li) * a.n_pad + key0;
+                const bf16_t *vrow = Vtp + (size_t)(mt * 32 + li) * a.n_pad + (jb + 16 * ka + 4 * half);
                 const u32x2 v0 = *(const u32x2 *)(vrow);
                 const u32x2 v1 = *(const u32x2 *)(vrow + 8);
                 u32x4 va;
@@ -201,121 +176,280 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 va[1] = v0[1];
                 va[2] = v1[0];
                 va[3] = v1[1];
-                oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(pb), oacc[mt], 0, 0, 0);
+                vreg[ka * MT + mt] = va;
             }
-        }
     };
 
-    // transposed score tile S^T[key][score row] = X[jb + key] . q for X = K or K_hat
-    auto score_tile = [&](const bf16_t *X, int jb) -> f32x16 {
-        f32x16 acc;
+    // Online softmax + PV for one block; s[16] are this lane's scaled scores (-inf where masked).
+    // The running maximum is only raised when the block maximum exceeds it by more than 2^8 in the
+    // exponent, so probabilities stay <= 256 and the accumulator is rarely rescaled.
+    auto softmax_pv = [&](float (&s)[16], const u32x4 (&vreg)[2 * MT]) {
+        float bm = s[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const bf16_t *xrow = X + (size_t)min(jb + li, n - 1) * D + half * 8;
+        for (int r = 1; r < 16; ++r) bm = fmaxf(bm, s[r]);
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        if (__any(bm > m_run + 8.f)) {
+            const float m_new = fmaxf(m_run, bm);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m_run - m_use);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const u32x4 xa = *(const u32x4 *)(xrow + ks * 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xa), as_bf16x8(qreg[ks]), acc, 0, 0, 0);
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
         }
-        return acc;
+        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+        float psum = 0.f;
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            p[r] = exp2f(s[r] - m_use);
+            psum += p[r];
+        }
+        l_run += psum;
+#pragma unroll
+        for (int ka = 0; ka < 2; ++ka) {
+            u32x4 pb;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                f32x2 pr;
+                pr[0] = p[8 * ka + 2 * k];
+                pr[1] = p[8 * ka + 2 * k + 1];
+                pb[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vreg[ka * MT + mt]), as_bf16x8(pb),
+                                                                  oacc[mt], 0, 0, 0);
+        }
     };
 
     // ---------------------------------------------------------------- far blocks: gather (Eq. 4)
-    auto gather_block = [&](int blk) {
-        float *ub = ubuf + (size_t)(blk & 1) * kTB * kRows;
+    // Wave w owns columns 4w .. 4w+3 of every block.  The entry chunks of those columns travel
+    // global memory -> registers (one 16-byte load per lane, a whole block ahead) -> a private LDS
+    // ring where the block's chunks sit back to back -> uniform 16-byte LDS reads that every lane
+    // sees.  No scalar memory load sits in the inner loop, so all its LDS traffic completes in order
+    // and the loop is software-pipelined two chunks deep (register sets A and B).
+    if (far_blocks > 0) {
+        const char *qtb = (const char *)qt;
         const uint32_t lane_off = (uint32_t)lane * 8u;
-#pragma unroll 1
-        for (int cc = 0; cc < kTB / kWaves; ++cc) {
-            const int jj = wave + cc * kWaves;
-            const int j = blk * kTB + jj;                    // wave-uniform, < win_first <= n
-            const uint32_t cnt = Cp[j];
-            const u32x4 *e = (const u32x4 *)(Ep + (size_t)j * D);
-            float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
-            for (uint32_t k = 0; k < cnt; k += 4) {
-                const u32x4 ea = e[k >> 1], eb = e[(k >> 1) + 1];
-                const half4 q0 = *(const half4 *)((const char *)qt + (ea[0] * (kRows * 2) + lane_off));
-                const half4 q1 = *(const half4 *)((const char *)qt + (ea[2] * (kRows * 2) + lane_off));
-                const half4 q2 = *(const half4 *)((const char *)qt + (eb[0] * (kRows * 2) + lane_off));
-                const half4 q3 = *(const half4 *)((const char *)qt + (eb[2] * (kRows * 2) + lane_off));
-                const float d0 = __uint_as_float(ea[1]), d1 = __uint_as_float(ea[3]);
-                const float d2 = __uint_as_float(eb[1]), d3 = __uint_as_float(eb[3]);
-                u0 = fmaf((float)q0[0], d0, u0); u1 = fmaf((float)q0[1], d0, u1);
-                u2 = fmaf((float)q0[2], d0, u2); u3 = fmaf((float)q0[3], d0, u3);
-                u0 = fmaf((float)q1[0], d1, u0); u1 = fmaf((float)q1[1], d1, u1);
-                u2 = fmaf((float)q1[2], d1, u2); u3 = fmaf((float)q1[3], d1, u3);
-                u0 = fmaf((float)q2[0], d2, u0); u1 = fmaf((float)q2[1], d2, u1);
-                u2 = fmaf((float)q2[2], d2, u2); u3 = fmaf((float)q2[3], d2, u3);
-                u0 = fmaf((float)q3[0], d3, u0); u1 = fmaf((float)q3[1], d3, u1);
-                u2 = fmaf((float)q3[2], d3, u2); u3 = fmaf((float)q3[3], d3, u3);
-            }
-            f32x4 uv;
-            uv[0] = u0; uv[1] = u1; uv[2] = u2; uv[3] = u3;
-            *(f32x4 *)(ub + jj * kRows + lane * 4) = uv;
-        }
-    };
+        constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 2 * 64;
+        char *ring = lds_raw + (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
+        for (int o = lane * 16; o < kRingBytes; o += 64 * 16) *(u32x4 *)(ring + o) = u32x4{0u, 0u, 0u, 0u};
 
-    if (far_blocks > 0) gather_block(0);
-    for (int blk = 0; blk < far_blocks; ++blk) {
-        __syncthreads();                                     // u of block blk complete
-        // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1 (the
-        // matrix-core D layout).  A lane sums inside its own groups and gets the other half's group
-        // totals from its partner lane, so the running Eq. 4 score advances in column order.
-        const float *ub = ubuf + (size_t)(blk & 1) * kTB * kRows + (4 * half) * kRows + my_sr;
-        float w[16], t_own[4], t_oth[4];
+        auto pack_of = [&](int blk) -> uint32_t {   // chunk counts of this wave's 4 columns, one byte each
+            return blk < far_blocks ? *(const_u32_ptr)(uintptr_t)(Np + blk * kTB + 4 * wave) : 0u;
+        };
+        auto g_issue = [&](u32x4 (&st)[4], int blk, uint32_t pk) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            float run = 0.f;
-#pragma unroll
-            for (int bb = 0; bb < 4; ++bb) {
-                run += ub[(8 * q + bb) * kRows];
-                w[4 * q + bb] = run;
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t nch = (pk >> (8 * cc)) & 0xffu;
+                st[cc] = u32x4{0u, 0u, 0u, 0u};
+                if ((uint32_t)lane < 4u * nch)
+                    st[cc] = *(const u32x4 *)((const char *)(Ep + (size_t)(blk * kTB + 4 * wave + cc) * (D / kGroup)) +
+                                              lane * 16);
             }
-            t_own[q] = run;
+        };
+        auto w_store = [&](const u32x4 (&st)[4], uint32_t pk) {
+            uint32_t base = 0;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t nch = (pk >> (8 * cc)) & 0xffu;
+                if ((uint32_t)lane < 4u * nch) *(u32x4 *)(ring + base * 64 + lane * 16) = st[cc];
+                base += nch;
+            }
+        };
+
+        struct Set {
+            half4 q[8];     // q values of 4 score rows at the chunk's 8 channels
+            f32x4 d[2];     // the chunk's 8 deltas
+            u32x4 ch[2];    // the chunk's 8 channel indices
+        };
+        auto rd_ch = [&](Set &x, uint32_t t) {
+            x.ch[0] = *(const u32x4 *)(ring + t * 64);
+            x.ch[1] = *(const u32x4 *)(ring + t * 64 + 16);
+        };
+        auto rd_d = [&](Set &x, uint32_t t) {
+            x.d[0] = *(const f32x4 *)(ring + t * 64 + 32);
+            x.d[1] = *(const f32x4 *)(ring + t * 64 + 48);
+        };
+        auto issue_q = [&](Set &x) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                x.q[i] = *(const half4 *)(qtb + (x.ch[i >> 2][i & 3] * (uint32_t)(kRows * 2) + lane_off));
+        };
+
+        uint32_t pk_cur = pack_of(0), pk_nxt = pack_of(1);
+        u32x4 st[4];
+        g_issue(st, 0, pk_cur);
+
+        auto gather_block = [&](uint32_t pk) {
+            const uint32_t total = (pk & 0xffu) + ((pk >> 8) & 0xffu) + ((pk >> 16) & 0xffu) + (pk >> 24);
+            uint32_t cend = pk & 0xffu;
+            int cc = 0;
+            float u[4] = {0.f, 0.f, 0.f, 0.f};
+            Set A, B;
+            rd_ch(A, 0);
+            rd_d(A, 0);
+            rd_ch(B, 1);
+            issue_q(A);
+            // consume chunk t (set x) while the q reads of chunk t+1 (set y) and the entry reads of
+            // chunks t+1 / t+2 are in flight
+            auto step = [&](Set &x, Set &y, uint32_t t) {
+                issue_q(y);
+                rd_d(y, t + 1);
+                rd_ch(x, t + 2);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float dl = x.d[i >> 2][i & 3];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) u[r] = fmaf((float)x.q[i][r], dl, u[r]);
+                }
+                if (t + 1 == cend) {   // column finished: hand its update vector to the score-row owners
+                    f32x4 uv;
+                    uv[0] = u[0]; uv[1] = u[1]; uv[2] = u[2]; uv[3] = u[3];
+                    *(f32x4 *)(ubuf + (4 * wave + cc) * kRows + lane * 4) = uv;
+                    u[0] = u[1] = u[2] = u[3] = 0.f;
+                    ++cc;
+                    cend += (pk >> (8 * cc)) & 0xffu;
+                }
+            };
+            uint32_t t = 0;
+            for (; t + 1 < total; t += 2) {
+                step(A, B, t);
+                step(B, A, t + 1);
+            }
+            if (t < total) step(A, B, t);
+        };
+
+        for (int blk = 0; blk <= far_blocks; ++blk) {
+            u32x4 vreg[2 * MT];
+            float s[16];
+            if (blk > 0) {
+                __syncthreads();                                 // u of block blk-1 complete
+                // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1
+                // (the matrix-core D layout).  A lane sums inside its own groups and gets the other
+                // half's group totals from its partner lane, so the running Eq. 4 score advances in
+                // column order.
+                const float *up = ubuf + (4 * half) * kRows + my_sr;
+                float w[16], t_own[4], t_oth[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float run = 0.f;
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        run += up[(8 * q + bb) * kRows];
+                        w[4 * q + bb] = run;
+                    }
+                    t_own[q] = run;
+                }
+                __syncthreads();                                 // u buffer free for the next block
+#pragma unroll
+                for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
+                float base = r_run;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float mine = half ? base + t_oth[q] : base;
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = (mine + w[4 * q + bb]) * far_scale;
+                    base += t_own[q] + t_oth[q];
+                }
+                r_run = base;
+                load_v(vreg, (blk - 1) * kTB);                   // in flight during the next gather
+            }
+            if (blk < far_blocks) {
+                w_store(st, pk_cur);                             // this block's chunks into the ring
+                const uint32_t pk = pk_cur;
+                pk_cur = pk_nxt;
+                g_issue(st, blk + 1, pk_cur);                    // next block's chunks into registers
+                pk_nxt = pack_of(blk + 2);
+                gather_block(pk);
+            }
+            if (blk > 0) softmax_pv(s, vreg);
         }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
-        float s[16];
-        float base = r_run;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float mine = half ? base + t_oth[q] : base;
-#pragma unroll
-            for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = (mine + w[4 * q + bb]) * far_scale;
-            base += t_own[q] + t_oth[q];
-        }
-        r_run = base;
-        if (blk + 1 < far_blocks) gather_block(blk + 1);     // overlaps with slower waves still reading blk
-        softmax_pv(s, blk * kTB);
     }
 
     // ---------------------------------------------------------------- near blocks (and all blocks in rebase mode)
-    for (int blk = far_blocks; blk < nblocks; ++blk) {
-        const int jb = blk * kTB;
-        float s[16];
-        const bool all_far = jb + kTB <= win_first;          // rebase mode only
-        if (all_far) {
-            const f32x16 sh = score_tile(Hp, jb);
+    if (far_blocks < nblocks) {
+        u32x4 qreg[KS];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = sh[r] * a.scale_log2;
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
+        auto load_x = [&](u32x4 (&xr)[KS], const bf16_t *X, int jb) {
+            const bf16_t *xrow = X + (size_t)min(jb + li, n - 1) * D + half * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xr[ks] = *(const u32x4 *)(xrow + ks * 16);
+        };
+        // transposed score tile S^T[key][score row] = X[jb + key] . q
+        auto score_tile = [&](const u32x4 (&xr)[KS]) -> f32x16 {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xr[ks]), as_bf16x8(qreg[ks]), acc, 0, 0, 0);
+            return acc;
+        };
+        // operand X of a block: K_hat while every row has the block outside its window (rebase mode), else K
+        auto first_src = [&](int jb) -> const bf16_t * { return (jb + kTB <= win_first) ? Hp : Kp; };
+        if (aligned) {
+            // every row of the tile has the same window: blocks left of it use K_hat (rebase mode), the
+            // window itself uses K with the causal mask
+            for (int blk = far_blocks; blk < nblocks; ++blk) {
+                const int jb = blk * kTB;
+                float s[16];
+                {
+                    u32x4 xk[KS];
+                    load_x(xk, first_src(jb), jb);
+                    const f32x16 sk = score_tile(xk);
+                    if (jb + kTB <= i0 + 1) {   // no masked entry for any row of the tile
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s[r] = sk[r] * a.scale_log2;
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
+                            s[r] = (j <= my_i) ? sk[r] * a.scale_log2 : -INFINITY;
+                        }
+                    }
+                }
+                u32x4 vreg[2 * MT];
+                load_v(vreg, jb);
+                softmax_pv(s, vreg);
+            }
         } else {
-            const f32x16 sk = score_tile(Kp, jb);
-            if (aligned) {
+            // the tile straddles window squares: per element, exact score inside the row's own window,
+            // K_hat score (telescoped Eq. 4) left of it
+            for (int blk = far_blocks; blk < nblocks; ++blk) {
+                const int jb = blk * kTB;
+                float s[16];
+                {
+                    u32x4 xk[KS];
+                    load_x(xk, first_src(jb), jb);
+                    const f32x16 sk = score_tile(xk);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] = sk[r];
+                }
+                if (first_src(jb) == Kp) {
+                    u32x4 xh[KS];
+                    load_x(xh, Hp, jb);
+                    const f32x16 sh = score_tile(xh);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
+                        s[r] = (j >= my_win) ? s[r] : sh[r];
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                    s[r] = (j <= my_i) ? sk[r] * a.scale_log2 : -INFINITY;
+                    s[r] = (j <= my_i) ? s[r] * a.scale_log2 : -INFINITY;
                 }
-            } else {
-                const f32x16 sh = score_tile(Hp, jb);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const float pick = (j >= my_win) ? sk[r] : sh[r];
-                    s[r] = (j <= my_i) ? pick * a.scale_log2 : -INFINITY;
-                }
+                u32x4 vreg[2 * MT];
+                load_v(vreg, jb);
+                softmax_pv(s, vreg);
             }
         }
-        softmax_pv(s, jb);
     }
 
     // ---------------------------------------------------------------- epilogue
@@ -365,8 +499,8 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.Khat = (const bf16_t *)p.Khat;
     a.Vt = (const bf16_t *)vt;
     a.O = (bf16_t *)p.O;
-    a.ents = (const Entry *)p.ents;
-    a.counts = p.counts;
+    a.ents = (const EntryChunk *)p.ents;
+    a.nch8 = p.nch8;
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.n = p.n;
@@ -379,7 +513,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.n + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
-    const size_t lds = (size_t)D * kRows * 2 + (size_t)2 * kTB * kRows * 4;
+    const size_t lds = (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 2 * 64);
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
