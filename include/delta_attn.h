@@ -86,6 +86,9 @@ int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);
  * (0 if the params are invalid). */
 size_t delta_attn_prefill_workspace_bytes(const da_prefill_params *p);
 
+/* Bytes of device scratch delta_attn_delta_scan needs (0 if the params are invalid). */
+size_t delta_attn_delta_scan_workspace_bytes(const da_prefill_params *p);
+
 /*
  * Delta matrix only (Eq. 2-3 on K; Sec. III-A).  Uses batch, n_kv_heads, head_dim, seq_len,
  * theta, dtype of p.
@@ -94,9 +97,11 @@ size_t delta_attn_prefill_workspace_bytes(const da_prefill_params *p);
  *             (t, c) is kept; row 0 is all ones
  *   nnz       [B, Hkv] uint64 out: number of set mask bits
  *   k_hat     [B, Hkv, n, d] out or NULL: reference keys after each row (Eq. 3), dtype of K
+ *   workspace device scratch of at least delta_attn_delta_scan_workspace_bytes(p)
  */
 da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint32_t *mask_bits,
-                                uint64_t *nnz, void *k_hat, void *hip_stream);
+                                uint64_t *nnz, void *k_hat, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 /*
  * Prefill (Sec. III-B prefill stage + Sec. III-C): builds the delta matrix of K, then for every

@@ -18,7 +18,7 @@ DA_SCORE_GATHER, DA_SCORE_REBASE = 0, 1
 EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
     "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
-    "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
+    "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
     "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
     "delta_attn_sparsity",
@@ -63,7 +63,9 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_prefill_workspace_bytes.restype = ctypes.c_size_t
         L.delta_attn_prefill_workspace_bytes.argtypes = [pp]
         L.delta_attn_delta_scan.restype = ctypes.c_int
-        L.delta_attn_delta_scan.argtypes = [pp, vp, vp, vp, vp, vp]
+        L.delta_attn_delta_scan_workspace_bytes.restype = ctypes.c_size_t
+        L.delta_attn_delta_scan_workspace_bytes.argtypes = [pp]
+        L.delta_attn_delta_scan.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.delta_attn_prefill.restype = ctypes.c_int
         L.delta_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.delta_attn_cache_create.restype = ctypes.c_int
@@ -235,8 +237,10 @@ def delta_attn_delta_scan(K, theta: float, want_khat: bool = False):
     mask = torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device=K.device)
     nnz = torch.empty((B, Hkv), dtype=torch.int64, device=K.device)
     khat = torch.empty_like(K) if want_khat else None
+    ws = torch.empty(max(int(lib().delta_attn_delta_scan_workspace_bytes(ctypes.byref(p))), 1), dtype=torch.uint8,
+                     device=K.device)
     _check(lib().delta_attn_delta_scan(ctypes.byref(p), K.data_ptr(), mask.data_ptr(), nnz.data_ptr(), _ptr(khat),
-                                       _stream()), "delta_attn_delta_scan")
+                                       ws.data_ptr(), ws.numel(), _stream()), "delta_attn_delta_scan")
     return mask, nnz, khat
 
 

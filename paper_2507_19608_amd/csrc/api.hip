@@ -18,7 +18,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, ents, counts, nch8, vt, total;
+    size_t khat, chunk_out, ents, counts, nch8, vt, total;
 };
 
 da_status check_params(const da_prefill_params *p) {
@@ -43,6 +43,8 @@ WsLayout layout(const da_prefill_params *p) {
     size_t off = 0;
     w.khat = off;
     off += align_up(rows * p->head_dim * elt_size(p->dtype));
+    w.chunk_out = off;
+    off += align_up(units * (size_t)delta_scan_num_chunks(p->seq_len) * p->head_dim * elt_size(p->dtype));
     w.ents = off;
     off += align_up(rows * p->head_dim * 8);   // EntryChunk storage: 8 bytes per possible entry
     w.counts = off;
@@ -106,15 +108,24 @@ size_t delta_attn_prefill_workspace_bytes(const da_prefill_params *p) {
     return layout(p).total;
 }
 
+size_t delta_attn_delta_scan_workspace_bytes(const da_prefill_params *p) {
+    if (check_params(p) != DA_OK) return 0;
+    const WsLayout w = layout(p);
+    return w.ents;   // reference keys + per-chunk states: the first two regions of the prefill layout
+}
+
 da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint32_t *mask_bits, uint64_t *nnz,
-                                void *k_hat, void *hip_stream) {
+                                void *k_hat, void *workspace, size_t workspace_bytes, void *hip_stream) {
     da_status st = check_params(p);
     if (st != DA_OK) return st;
     if (!K || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
+    const WsLayout w = layout(p);
+    if (!workspace || workspace_bytes < w.ents) return DA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
     (void)hipGetLastError();
-    launch_delta_scan(p->dtype, K, k_hat, mask_bits, nnz, p->batch * p->n_kv_heads, p->seq_len, p->head_dim,
-                      p->theta, s);
+    launch_delta_scan(p->dtype, K, k_hat ? k_hat : ws + w.khat, mask_bits, ws + w.chunk_out, nnz,
+                      p->batch * p->n_kv_heads, p->seq_len, p->head_dim, p->theta, s);
     return launch_ok("delta_scan") ? DA_OK : DA_ERR_HIP;
 }
 
@@ -140,7 +151,8 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
 
     (void)hipGetLastError();   // do not inherit an earlier, unrelated error
     stage_begin(kStageScan, s);
-    launch_delta_scan(p->dtype, K, khat, mask_bits, nnz, units, p->seq_len, p->head_dim, p->theta, s);
+    launch_delta_scan(p->dtype, K, khat, mask_bits, ws + w.chunk_out, nnz, units, p->seq_len, p->head_dim,
+                      p->theta, s);
     stage_end(kStageScan, s);
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
     if (p->score_mode == DA_SCORE_GATHER || cache) {

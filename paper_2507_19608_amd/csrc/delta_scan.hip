@@ -75,33 +75,56 @@ int timing_collect(double *ms_per_stage, int *calls_per_stage) {
     return n;
 }
 
-// Sequential in t, parallel over channels: one lane per channel, one wave per 64 channels of a
-// (batch, KV head) unit.  The wave ballot of the threshold decision is the mask word itself.
+// The recurrence of Eq. 2-3 is sequential in t and is not an associative scan, but it forgets its
+// past every time a channel fires: from then on the held value is k(t) whatever it was before.
+// So time is cut into chunks that are scanned in parallel from a guessed state, and a short serial
+// pass repairs the start of each chunk:
+//
+//   pass A  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row and is
+//           exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and writes mask words, held
+//           keys and its final held value as if the guess were true.
+//   pass B  (one wave per (unit, 64 channels), chunks in order): carries the true held value into
+//           each chunk and re-runs rows from the chunk start only while some channel's true held value
+//           still differs from the guessed chain's; after the first row where they agree (both fired, or
+//           the values coincide) the guessed results are the true ones.  Rows walked get their mask word,
+//           held keys and the nnz count corrected.  Exact for any input; the walk is a handful of rows
+//           per chunk when channels fire often and the whole chunk when nothing ever fires.
+//
+// One lane per channel; the wave ballot of the threshold decision is the mask word itself.
+constexpr int kScanPrefetch = 16;   // rows of the next chunk that pass B holds in registers
+
 template <typename T>
-__global__ __launch_bounds__(64) void delta_scan_kernel(const T *__restrict__ K, T *__restrict__ Khat,
-                                                        uint32_t *__restrict__ mask_bits,
-                                                        unsigned long long *__restrict__ nnz, int n, int d,
-                                                        float theta) {
-    const int unit = blockIdx.y;
+__global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restrict__ K, T *__restrict__ Khat,
+                                                               uint32_t *__restrict__ mask_bits,
+                                                               T *__restrict__ chunk_out,
+                                                               unsigned long long *__restrict__ nnz, int n, int d,
+                                                               int L, int nchunks, float theta) {
+    const int unit = blockIdx.z, chunk = blockIdx.y;
     const int lane = threadIdx.x;
     const int c = blockIdx.x * kWave + lane;
     const bool active = c < d;
     const int wpr = d >> 5;
     const T *Kp = K + (size_t)unit * n * d;
-    T *Hp = Khat ? Khat + (size_t)unit * n * d : nullptr;
+    T *Hp = Khat + (size_t)unit * n * d;
     uint32_t *Mp = mask_bits + (size_t)unit * n * wpr;
     const bool writer = active && ((lane & 31) == 0);
     const int word = c >> 5;
+    const int t0 = chunk * L, t1 = min(n, t0 + L);
 
-    // row 0 is the basis: kept whole
-    float held = active ? load_f32(Kp, c) : 0.f;
-    if (Hp && active) Hp[c] = Kp[c];
-    if (writer) Mp[word] = 0xffffffffu;
-    unsigned long long cnt = __popcll(__ballot(active));
-
-    constexpr int U = 8;
-    int t = 1;
-    for (; t + U <= n; t += U) {
+    float held;
+    unsigned long long cnt = 0;
+    int t = t0;
+    if (chunk == 0) {   // row 0 is the basis: kept whole
+        held = active ? load_f32(Kp, c) : 0.f;
+        if (active) Hp[c] = Kp[c];
+        if (writer) Mp[word] = 0xffffffffu;
+        cnt = __popcll(__ballot(active));
+        t = 1;
+    } else {
+        held = active ? load_f32(Kp, (size_t)(t0 - 1) * d + c) : 0.f;
+    }
+    constexpr int U = 16;
+    for (; t + U <= t1; t += U) {
         float k[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) k[u] = active ? load_f32(Kp, (size_t)(t + u) * d + c) : 0.f;
@@ -112,21 +135,106 @@ __global__ __launch_bounds__(64) void delta_scan_kernel(const T *__restrict__ K,
             held = fire ? k[u] : held;                        // Eq. 3
             const uint64_t b = __ballot(fire);
             if (writer) Mp[(size_t)(t + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
-            if (Hp && active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
+            if (active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
             cnt += __popcll(b);
         }
     }
-    for (; t < n; ++t) {
+    for (; t < t1; ++t) {
         const float k = active ? load_f32(Kp, (size_t)t * d + c) : 0.f;
-        const float diff = k - held;
-        const bool fire = active && (fabsf(diff) > theta);
+        const bool fire = active && (fabsf(k - held) > theta);
         held = fire ? k : held;
         const uint64_t b = __ballot(fire);
         if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(b >> (lane & 32));
-        if (Hp && active) store_from_f32(Hp, (size_t)t * d + c, held);
+        if (active) store_from_f32(Hp, (size_t)t * d + c, held);
         cnt += __popcll(b);
     }
+    if (active) store_from_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + c, held);
     if (lane == 0) atomicAdd(nnz + unit, cnt);
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restrict__ K, T *__restrict__ Khat,
+                                                              uint32_t *__restrict__ mask_bits,
+                                                              const T *__restrict__ chunk_out,
+                                                              unsigned long long *__restrict__ nnz, int n, int d,
+                                                              int L, int nchunks, float theta) {
+    const int unit = blockIdx.y;
+    const int lane = threadIdx.x;
+    const int c = blockIdx.x * kWave + lane;
+    const bool active = c < d;
+    const int cs = active ? c : 0;
+    const int wpr = d >> 5;
+    const T *Kp = K + (size_t)unit * n * d;
+    T *Hp = Khat + (size_t)unit * n * d;
+    uint32_t *Mp = mask_bits + (size_t)unit * n * wpr;
+    const bool writer = active && ((lane & 31) == 0);
+    const int word = c >> 5;
+    constexpr int P = kScanPrefetch;
+
+    float held = load_f32(chunk_out, ((size_t)unit * nchunks) * d + cs);   // true state after chunk 0
+    long long adjust = 0;
+    // rows t0-1 .. t0+P-1 of the next chunk, loaded one chunk ahead (addresses do not depend on the state)
+    float kn[P + 1];
+    auto prefetch = [&](int chunk) {
+        const int t0 = chunk * L;
+#pragma unroll
+        for (int u = 0; u <= P; ++u) {
+            const int t = min(t0 - 1 + u, n - 1);
+            kn[u] = load_f32(Kp, (size_t)t * d + cs);
+        }
+    };
+    if (nchunks > 1) prefetch(1);
+    for (int chunk = 1; chunk < nchunks; ++chunk) {
+        const int t0 = chunk * L, t1 = min(n, t0 + L);
+        float kc[P + 1];
+#pragma unroll
+        for (int u = 0; u <= P; ++u) kc[u] = kn[u];
+        const float spec_out = load_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + cs);
+        if (chunk + 1 < nchunks) prefetch(chunk + 1);
+        float spec = kc[0];                       // the guess pass A started from: k(t0 - 1)
+        bool synced = !active || (__float_as_uint(held) == __float_as_uint(spec));
+        int t = t0;
+        // rows held in registers
+#pragma unroll
+        for (int u = 1; u <= P; ++u) {
+            if (t < t1 && __any(!synced)) {
+                const float k = kc[u];
+                const bool fs = fabsf(k - spec) > theta;
+                const bool ft = fabsf(k - held) > theta;
+                spec = fs ? k : spec;
+                if (!synced) {
+                    held = ft ? k : held;
+                    store_from_f32(Hp, (size_t)t * d + c, held);
+                }
+                const uint64_t bt = __ballot(synced ? fs : ft);
+                const uint64_t bs = __ballot(fs);
+                if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
+                adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
+                synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
+                ++t;
+            }
+        }
+        // rare: still not synced after the prefetched rows
+        while (t < t1 && __any(!synced)) {
+            const float k = load_f32(Kp, (size_t)t * d + cs);
+            const bool fs = fabsf(k - spec) > theta;
+            const bool ft = fabsf(k - held) > theta;
+            spec = fs ? k : spec;
+            if (!synced) {
+                held = ft ? k : held;
+                store_from_f32(Hp, (size_t)t * d + c, held);
+            }
+            const uint64_t bt = __ballot(synced ? fs : ft);
+            const uint64_t bs = __ballot(fs);
+            if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
+            adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
+            synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
+            ++t;
+        }
+        // a synced channel ends the chunk where the guessed chain ended; an unsynced one walked to t1
+        held = synced ? spec_out : held;
+    }
+    if (lane == 0 && adjust != 0) atomicAdd(nnz + unit, (unsigned long long)adjust);
 }
 
 // One wave per key column: ballot + prefix count turn the mask row into a dense list of
@@ -191,16 +299,29 @@ void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s) {
                        (unsigned long long)v, n);
 }
 
-void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, uint64_t *nnz, int units,
+int delta_scan_chunk_len(int n) { return n >= 4096 ? 128 : 64; }
+int delta_scan_num_chunks(int n) { return (n + delta_scan_chunk_len(n) - 1) / delta_scan_chunk_len(n); }
+
+template <typename T>
+static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz, int units,
                        int n, int d, float theta, hipStream_t s) {
+    const int L = delta_scan_chunk_len(n), nchunks = delta_scan_num_chunks(n);
+    const int cw = (d + kWave - 1) / kWave;
+    hipLaunchKernelGGL(delta_scan_chunks_kernel<T>, dim3(cw, nchunks, units), dim3(kWave), 0, s, (const T *)K,
+                       (T *)Khat, mask_bits, (T *)chunk_out, (unsigned long long *)nnz, n, d, L, nchunks, theta);
+    if (nchunks > 1)
+        hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw, units), dim3(kWave), 0, s, (const T *)K, (T *)Khat,
+                           mask_bits, (const T *)chunk_out, (unsigned long long *)nnz, n, d, L, nchunks, theta);
+}
+
+// Khat [units][n][d] and chunk_out [units][delta_scan_num_chunks(n)][d] are required scratch/outputs.
+void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
+                       int units, int n, int d, float theta, hipStream_t s) {
     launch_fill_u64(nnz, 0, units, s);
-    dim3 grid((d + kWave - 1) / kWave, units), block(kWave);
     if (dtype == 0)
-        hipLaunchKernelGGL(delta_scan_kernel<float>, grid, block, 0, s, (const float *)K, (float *)Khat, mask_bits,
-                           (unsigned long long *)nnz, n, d, theta);
+        scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, s);
     else
-        hipLaunchKernelGGL(delta_scan_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K, (bf16_t *)Khat,
-                           mask_bits, (unsigned long long *)nnz, n, d, theta);
+        scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, s);
 }
 
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,

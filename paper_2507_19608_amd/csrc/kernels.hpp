@@ -31,8 +31,9 @@ struct PrefillArgs {
 };
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
-void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, uint64_t *nnz, int units,
-                       int n, int d, float theta, hipStream_t s);
+int delta_scan_num_chunks(int n);
+void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
+                       int units, int n, int d, float theta, hipStream_t s);
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
                          uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if

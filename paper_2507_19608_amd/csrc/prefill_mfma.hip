@@ -44,7 +44,7 @@ struct MfmaArgs {
     const bf16_t *__restrict__ Q;
     const bf16_t *__restrict__ K;
     const bf16_t *__restrict__ Khat;
-    const bf16_t *__restrict__ Vt;      // [unit][D][n_pad]
+    const bf16_t *__restrict__ Vt;      // per unit: V in matrix-core operand order, D * n_pad elements
     bf16_t *__restrict__ O;
     const EntryChunk *__restrict__ ents;
     const uint8_t *__restrict__ nch8;
@@ -162,22 +162,12 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
     __syncthreads();   // Q tile staged
 
-    // V^T operands of one block: vreg[ka * MT + mt] for k-step ka, channel tile mt
+    // V^T operands of one block: vreg[ka * MT + mt] for k-step ka, channel tile mt.  V was rearranged
+    // into matrix-core operand order, so each operand is one fully coalesced 16-byte load per lane.
     auto load_v = [&](u32x4 (&vreg)[2 * MT], int jb) {
+        const u32x4 *vp = (const u32x4 *)Vtp + (size_t)(jb / kTB) * (2 * MT * 64) + lane;
 #pragma unroll
-        for (int ka = 0; ka < 2; ++ka)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const bf16_t *vrow = Vtp + (size_t)(mt * 32 + li) * a.n_pad + (jb + 16 * ka + 4 * half);
-                const u32x2 v0 = *(const u32x2 *)(vrow);
-                const u32x2 v1 = *(const u32x2 *)(vrow + 8);
-                u32x4 va;
-                va[0] = v0[0];
-                va[1] = v0[1];
-                va[2] = v1[0];
-                va[3] = v1[1];
-                vreg[ka * MT + mt] = va;
-            }
+        for (int k = 0; k < 2 * MT; ++k) vreg[k] = vp[k * 64];
     };
 
     // Online softmax + PV for one block; s[16] are this lane's scaled scores (-inf where masked).
@@ -469,29 +459,41 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     }
 }
 
-// V [unit][n][D] -> Vt [unit][D][n_pad], zero beyond n
+// V [unit][n][D] -> matrix-core operand order [unit][block of 32 keys][k-step ka][channel tile mt][lane][8]:
+// lane l of operand (ka, mt) holds channel 32 mt + l % 32 at keys 16 ka + 4 (l / 32) + {0..3} and
+// 16 ka + 8 + 4 (l / 32) + {0..3} of the block (the key order of the score tile's D registers).
+// Keys beyond n are zero.
 template <int D>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
                                                           int n, int n_pad) {
-    __shared__ bf16_t tile[64][D + 2];
-    const int unit = blockIdx.y, t0 = blockIdx.x * 64, tid = threadIdx.x;
+    __shared__ bf16_t tile[kTB][D + 2];
+    constexpr int MT = D / 32;
+    const int unit = blockIdx.y, blk = blockIdx.x, t0 = blk * kTB, tid = threadIdx.x;
     const bf16_t *Vp = V + (size_t)unit * n * D;
-    for (int idx = tid; idx < 64 * D; idx += 256) {
+    for (int idx = tid; idx < kTB * D; idx += 256) {
         const int r = idx / D, c = idx % D;
         tile[r][c] = (t0 + r < n) ? Vp[(size_t)(t0 + r) * D + c] : (bf16_t)0;
     }
     __syncthreads();
-    bf16_t *Op = Vt + (size_t)unit * D * n_pad;
-    for (int idx = tid; idx < 64 * D; idx += 256) {
-        const int c = idx / 64, r = idx % 64;
-        if (t0 + r < n_pad) Op[(size_t)c * n_pad + t0 + r] = tile[r][c];
+    u32x4 *Op = (u32x4 *)(Vt + (size_t)unit * D * n_pad) + (size_t)blk * (2 * MT * 64);
+    for (int idx = tid; idx < 2 * MT * 64; idx += 256) {
+        const int l = idx % 64, k = idx / 64, ka = k / MT, mt = k % MT;
+        const int ch = mt * 32 + (l & 31), hf = l >> 5;
+        u32x4 w;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const int e = 2 * e2;
+            const int key0 = 16 * ka + (e < 4 ? 4 * hf + e : 8 + 4 * hf + (e - 4));
+            w[e2] = (uint32_t)tile[key0][ch] | ((uint32_t)tile[key0 + 1][ch] << 16);
+        }
+        Op[idx] = w;
     }
 }
 
 template <int D>
 static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const int units = p.B * p.Hkv;
-    hipLaunchKernelGGL((transpose_v_kernel<D>), dim3((n_pad + 63) / 64, units), dim3(256), 0, s,
+    hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(n_pad / kTB, units), dim3(256), 0, s,
                        (const bf16_t *)p.V, (bf16_t *)vt, p.n, n_pad);
     MfmaArgs a;
     a.Q = (const bf16_t *)p.Q;

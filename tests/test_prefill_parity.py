@@ -128,6 +128,29 @@ def test_c5_sweep_masks_and_sparsity():
         assert (khat.double().cpu().numpy()[0, 0] == Kh).all()
 
 
+@pytest.mark.parametrize("n,d", [(5000, 96), (4097, 64), (130, 32), (63, 128), (1, 64)])
+def test_delta_scan_time_chunks_adversarial(n, d):
+    """The scan is cut into time chunks that start from a guessed state and are repaired afterwards;
+    these inputs make the repair walk long: keys that never fire, a slow drift that fires every few
+    rows at different phases per channel, and a mix with isolated jumps."""
+    rng = np.random.default_rng(n + d)
+    const = np.tile(rng.standard_normal((1, 1, 1, d)), (1, 1, n, 1))
+    drift = const + 0.03125 * np.arange(n)[None, None, :, None] * (1 + (np.arange(d) % 5))[None, None, None, :] / 4
+    jumps = const + np.cumsum((rng.random((1, 1, n, d)) < 0.01) * rng.standard_normal((1, 1, n, d)), axis=2)
+    saw = const + 0.01 * (np.arange(n)[None, None, :, None] % 97)
+    for name, K, dtype, theta in [("const", const, "bf16", 0.1), ("drift", drift, "f32", 0.1),
+                                  ("jumps", jumps, "bf16", 0.3), ("saw", saw, "f32", 0.25),
+                                  ("drift_bf16", drift, "bf16", 0.1)]:
+        K = wl.round_to_dtype(K, dtype)
+        maskg, nnzg, khat = da.delta_attn_delta_scan(to_dev(K, dtype), theta, want_khat=True)
+        m, _, Kh, knife = orc.delta_scan(K[0, 0], theta)
+        # (fp32 inputs may sit on a binary32 rounding edge; the decision is defined in binary32)
+        assert knife == 0 or dtype == "f32", name
+        assert (unpack_mask(maskg, d)[0, 0] == m).all(), name
+        assert int(nnzg[0, 0]) == int(m.sum()), name
+        assert (khat.double().cpu().numpy()[0, 0] == Kh).all(), name
+
+
 def test_binding_rejects_bad_arguments():
     Q = torch.zeros(1, 4, 64, 64, dtype=torch.bfloat16, device="cuda")
     K = torch.zeros(1, 2, 64, 64, dtype=torch.bfloat16, device="cuda")
