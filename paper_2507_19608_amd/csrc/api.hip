@@ -44,7 +44,7 @@ WsLayout layout(const da_prefill_params *p) {
     w.khat = off;
     off += align_up(rows * p->head_dim * elt_size(p->dtype));
     w.chunk_out = off;
-    off += align_up(units * (size_t)delta_scan_num_chunks(p->seq_len) * p->head_dim * elt_size(p->dtype));
+    off += align_up(2 * units * (size_t)delta_scan_num_chunks(p->seq_len) * p->head_dim * elt_size(p->dtype));
     w.ents = off;
     off += align_up(rows * p->head_dim * 8);   // EntryChunk storage: 8 bytes per possible entry
     w.counts = off;

@@ -14,6 +14,7 @@ struct da_cache {
     int device;
     int nck;              // checkpoints per unit: max_seq / kChunk + 1
     int max_chunks;       // (max_seq + kChunk - 1) / kChunk
+    int vmax8;            // max_seq rounded up to a multiple of 8 (row capacity of V)
     // per (batch, KV head) unit, all device memory:
     uint32_t *mask;       // [units][max_seq][d/32]   delta mask bits
     void *surv;           // [units][max_seq * d]     surviving key values, row after row, channel order
@@ -21,7 +22,7 @@ struct da_cache {
     void *ck;             // [units][nck][d]          ck[m] = reference key after row m*kChunk - 1 (m >= 1)
     void *khat;           // [units][d]               current reference key
     void *ring;           // [units][Wd][d]           raw key of position p at slot p % Wd
-    void *V;              // [units][max_seq][d]
+    void *V;              // [units][vmax8 / 8][d][8]: 8 rows interleaved per channel
     uint64_t *nnz;        // [units]
     float *part;          // [B*Hq][max_chunks][d + 2] per-chunk (o, m, l) partials of one decode step
 };

@@ -14,6 +14,13 @@ namespace {
 
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
+// V cache layout: 8 rows interleaved per channel, [unit][t / 8][channel][t % 8], so that eight
+// consecutive rows of one channel are contiguous (the k-contiguous operand order of the matrix
+// cores).  vmax8 = max_seq rounded up to 8.
+__device__ __forceinline__ size_t v_index(int unit, int vmax8, int d, int t, int ch) {
+    return ((size_t)unit * (vmax8 >> 3) + (t >> 3)) * ((size_t)d * 8) + (size_t)ch * 8 + (t & 7);
+}
+
 // ---------------------------------------------------------------------------------- cache fill
 __global__ __launch_bounds__(256) void row_offsets_kernel(const uint32_t *__restrict__ counts,
                                                           uint32_t *__restrict__ roff, const uint64_t *nnz_in,
@@ -67,7 +74,7 @@ __global__ __launch_bounds__(256) void cache_fill_kernel(const T *__restrict__ K
         if (act) {
             const T k = K[src + ch];
             if (bit) surv[off + lanes_below(b)] = k;
-            ((T *)c.V)[((size_t)unit * c.max_seq + row) * d + ch] = V[src + ch];
+            ((T *)c.V)[v_index(unit, c.vmax8, d, row, ch)] = V[src + ch];
             if (row >= n - c.Wd) ((T *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = k;
             if (row > 0 && row % kChunk == 0)
                 ((T *)c.ck)[((size_t)unit * c.nck + row / kChunk) * d + ch] = Khat[src - d + ch];
@@ -108,7 +115,7 @@ __global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *
             }
             if (fire) *hp = kraw;
             ((T *)c.ring)[((size_t)unit * c.Wd + t % c.Wd) * d + ch] = kraw;
-            ((T *)c.V)[((size_t)unit * c.max_seq + t) * d + ch] = v_new[(size_t)unit * d + ch];
+            ((T *)c.V)[v_index(unit, c.vmax8, d, t, ch)] = v_new[(size_t)unit * d + ch];
         }
         const uint64_t b = __ballot(fire);
         if (fire) surv[off + lanes_below(b)] = kraw;
@@ -145,7 +152,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <typename T>
 __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *__restrict__ q_new, int t,
                                                           float scale_log2) {
-    extern __shared__ float lds[];
+    extern __shared__ float lds_f[];
+    float *lds = lds_f;
     const int d = c.d, wpr = d >> 5;
     const int ldk = d + 1;
     float *kh = lds;                    // [kChunk][d + 1]
@@ -206,12 +214,13 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
         pb[lane] = p;
         __syncthreads();
         float *out = c.part + (((size_t)b * c.Hq + h) * c.max_chunks + chunk) * (d + 2);
-        const T *Vp = (const T *)c.V + ((size_t)unit * c.max_seq + r0) * d;
+        const T *Vp = (const T *)c.V;
         for (int w = 0; w * kWave < d; ++w) {
             const int ch = w * kWave + lane;
             if (ch < d) {
                 float acc = 0.f;
-                for (int r = 0; r < r1 - r0; ++r) acc = fmaf(pb[r], load_f32(Vp, (size_t)r * d + ch), acc);
+                for (int r = 0; r < r1 - r0; ++r)
+                    acc = fmaf(pb[r], load_f32(Vp, v_index(unit, c.vmax8, d, r0 + r, ch)), acc);
                 out[ch] = acc;
             }
         }
@@ -220,6 +229,184 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
             out[d + 1] = l;
         }
     }
+}
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// D2-D4 for bf16 caches: one wave per chunk of kChunk cached rows of one unit, all query heads of the
+// unit's group.
+//   1. the chunk's surviving key values (one contiguous run of the compact cache) are copied to LDS;
+//   2. lanes = channels walk the chunk's history rows in order: the mask word of a row, broadcast
+//      from the lane that holds it, selects which lanes take their next surviving value, the rest
+//      keep the held one (Eq. 3); each reference row k_hat(j) goes to an LDS tile (Eq. 4 telescoped:
+//      the history score of row j is q . k_hat(j)); rows inside the decode window are copied from
+//      the raw-key ring instead;
+//   3. scores of 64 rows x up to 16 heads on the matrix cores (16x16x32: A lane l = tile row l % 16,
+//      k = 8 (l / 16)..+7; B lane l = column l % 16, same k; D lane l = column l % 16, rows
+//      4 (l / 16) + r);
+//   4. per-head chunk softmax with lanes = rows; P V on the matrix cores against the 8-row
+//      interleaved V cache, partial (o, m, l) to the per-chunk scratch.
+__global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const bf16_t *__restrict__ q_new, int t,
+                                                               float scale_log2) {
+    extern __shared__ float lds_f[];
+    char *lds = (char *)lds_f;
+    const int d = c.d, wpr = d >> 5;
+    const int nw = (d + kWave - 1) / kWave;
+    const int ldk = d + 8;
+    bf16_t *ktile = (bf16_t *)lds;                           // [kChunk][d + 8]
+    bf16_t *sv = ktile + kChunk * ldk;                       // staged surviving values, <= kChunk * d + 8
+    float *sc = (float *)(sv + kChunk * d + 16);             // [16][kChunk] scores, heads x rows
+    bf16_t *pt = (bf16_t *)(sc + 16 * kChunk);               // [16][kChunk + 8] probabilities, heads x rows
+    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
+    const int r0 = chunk * kChunk;
+    const int r1 = min(r0 + kChunk, t + 1);
+    const int nrows = r1 - r0;
+    const int g = c.Hq / c.Hkv;
+    const int b = unit / c.Hkv, hk = unit % c.Hkv;
+    const int win_begin = t + 1 - c.Wd;                      // rows >= win_begin use raw keys
+    const int hist_rows = min(max(win_begin - r0, 0), nrows);
+    const bf16_t *surv = (const bf16_t *)c.surv + (size_t)unit * c.max_seq * d;
+    const uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
+    const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    if (hist_rows > 0) {
+        // 1. stage the chunk's survivors: rows r0 .. r0 + hist_rows - 1 occupy [rp[r0], rp[r0 + hist_rows])
+        const uint32_t roffv = rp[r0 + min(lane, hist_rows)];
+        const uint32_t s_begin = __builtin_amdgcn_readfirstlane(roffv);
+        const uint32_t s_end = rp[r0 + hist_rows];
+        const uint32_t base = s_begin & ~7u;
+        for (uint32_t i = base + lane * 8; i < s_end; i += kWave * 8)
+            *(u32x4 *)(sv + (i - base)) = *(const u32x4 *)(surv + i);
+        uint32_t mk[8];
+#pragma unroll
+        for (int w2 = 0; w2 < 8; ++w2) mk[w2] = (w2 < wpr && lane < hist_rows) ? Mp[(size_t)lane * wpr + w2] : 0u;
+        uint32_t held[4] = {0u, 0u, 0u, 0u};
+        if (r0 > 0) {
+            const bf16_t *ckp = (const bf16_t *)c.ck + ((size_t)unit * c.nck + chunk) * d;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                if (w < nw && w * kWave + lane < d) held[w] = ckp[w * kWave + lane];
+        }
+        __syncthreads();
+        // 2. reference keys of the history rows
+        for (int r = 0; r < hist_rows; ++r) {
+            uint32_t off = __builtin_amdgcn_readlane(roffv, r) - base;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                if (w < nw) {
+                    const uint32_t lo = __builtin_amdgcn_readlane(mk[2 * w], r);
+                    const uint32_t hi = __builtin_amdgcn_readlane(mk[2 * w + 1], r);
+                    const uint64_t m64 = (uint64_t)lo | ((uint64_t)hi << 32);
+                    const bool bit = (m64 >> lane) & 1ull;
+                    const uint32_t val = sv[off + lanes_below(m64)];
+                    held[w] = bit ? val : held[w];
+                    if (w * kWave + lane < d) ktile[r * ldk + w * kWave + lane] = (bf16_t)held[w];
+                    off += __popcll(m64);
+                }
+            }
+        }
+    }
+    // window rows come from the raw-key ring; rows past the newest key are zero
+    for (int r = hist_rows; r < kChunk; ++r) {
+        const int row = r0 + r;
+        const bf16_t *ringrow = (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * d;
+        for (int w = 0; w < nw; ++w) {
+            const int ch = w * kWave + lane;
+            if (ch < d) ktile[r * ldk + ch] = (r < nrows) ? ringrow[ch] : (bf16_t)0;
+        }
+    }
+    for (int i = lane; i < 16 * (kChunk + 8); i += kWave) pt[i] = 0;
+    __syncthreads();
+
+    for (int hbase = 0; hbase < g; hbase += 16) {
+        const int gh = min(16, g - hbase);
+        // 3. scores
+        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + hbase + min(l16, gh - 1)) * d;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < (d >> 5); ++ks) {
+                const u32x4 av = *(const u32x4 *)(ktile + (16 * rt + l16) * ldk + 32 * ks + 8 * lg);
+                u32x4 bv = *(const u32x4 *)(qrow + 32 * ks + 8 * lg);
+                if (l16 >= gh) bv = u32x4{0u, 0u, 0u, 0u};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                              __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sc[l16 * kChunk + 16 * rt + 4 * lg + r] = acc[r];
+        }
+        __syncthreads();
+        // 4. chunk softmax per head, lanes = rows
+        const bool valid = lane < nrows;
+        for (int h = 0; h < gh; ++h) {
+            const float sv_ = valid ? sc[h * kChunk + lane] * scale_log2 : -INFINITY;
+            const float m = wave_max(sv_);                   // row r0 is always valid, so m is finite
+            const float p = valid ? exp2f(sv_ - m) : 0.f;
+            const float l = wave_sum(p);
+            pt[h * (kChunk + 8) + lane] = f32_to_bf16(p);
+            if (lane == 0) {
+                float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (d + 2);
+                out[d] = m;
+                out[d + 1] = l;
+            }
+        }
+        __syncthreads();
+        // P V: heads x channels, contraction over the chunk's 64 rows
+        for (int ct = 0; ct < (d >> 4); ++ct) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const u32x4 av = *(const u32x4 *)(pt + l16 * (kChunk + 8) + 32 * ks + 8 * lg);
+                const u32x4 bv = *(const u32x4 *)((const bf16_t *)c.V +
+                                                  v_index(unit, c.vmax8, d, r0 + 32 * ks + 8 * lg, 16 * ct + l16));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                              __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int h = 4 * lg + r;
+                if (h < gh)
+                    c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (d + 2) + 16 * ct + l16] =
+                        acc[r];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Merge of the per-chunk partials of one (batch, query head): lanes = chunks for the weights,
+// lanes = channels for the output.
+template <typename T>
+__global__ __launch_bounds__(64) void decode_combine2_kernel(da_cache c, T *__restrict__ o, int nchunks) {
+    const int bh = blockIdx.x, lane = threadIdx.x;
+    const int d = c.d;
+    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
+    float M = -INFINITY;
+    for (int k = lane; k < nchunks; k += kWave) M = fmaxf(M, part[(size_t)k * (d + 2) + d]);
+    M = wave_max(M);
+    float L = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < nchunks; k0 += kWave) {
+        const int k = k0 + lane;
+        const float wk = k < nchunks ? exp2f(part[(size_t)k * (d + 2) + d] - M) : 0.f;
+        L += k < nchunks ? wk * part[(size_t)k * (d + 2) + d + 1] : 0.f;
+        const int cnt = min(kWave, nchunks - k0);
+        for (int kk = 0; kk < cnt; ++kk) {
+            const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
+            const float *row = part + (size_t)(k0 + kk) * (d + 2);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i * kWave + lane < d) acc[i] = fmaf(w, row[i * kWave + lane], acc[i]);
+        }
+    }
+    L = wave_sum(L);
+    const float inv = 1.f / L;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (i * kWave + lane < d) store_from_f32(o + (size_t)bh * d, i * kWave + lane, acc[i] * inv);
 }
 
 template <typename T>
@@ -252,18 +439,32 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
                        mask_row, t);
     stage_end(kStageAppend, s);
     const int nchunks = t / kChunk + 1;
-    const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
-    static bool attr_done = false;   // per instantiation; d = 256 needs slightly more than 64 KiB
-    if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)decode_chunk_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)));
-        attr_done = true;
-    }
     stage_begin(kStageChunk, s);
-    hipLaunchKernelGGL(decode_chunk_kernel<T>, dim3(nchunks, units), dim3(64), lds, s, *c, (const T *)q, t, sc);
+    if (c->dtype == DA_BF16) {
+        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * kChunk * 4 +
+                           16 * (kChunk + 8) * 2;
+        static bool attr16_done = false;   // d = 256 needs more than 64 KiB
+        if (!attr16_done) {
+            (void)hipFuncSetAttribute((const void *)decode_chunk_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 + 16 * kChunk * 4 +
+                                            16 * (kChunk + 8) * 2));
+            attr16_done = true;
+        }
+        hipLaunchKernelGGL(decode_chunk_bf16_kernel, dim3(nchunks, units), dim3(64), lds, s, *c, (const bf16_t *)q, t,
+                           sc);
+    } else {
+        const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
+        static bool attr_done = false;   // d = 256 needs slightly more than 64 KiB
+        if (!attr_done) {
+            (void)hipFuncSetAttribute((const void *)decode_chunk_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)));
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(decode_chunk_kernel<T>, dim3(nchunks, units), dim3(64), lds, s, *c, (const T *)q, t, sc);
+    }
     stage_end(kStageChunk, s);
     stage_begin(kStageCombine, s);
-    hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+    hipLaunchKernelGGL(decode_combine2_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
     stage_end(kStageCombine, s);
 }
 
@@ -332,6 +533,7 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     c->len = 0;
     c->nck = max_seq / kChunk + 1;
     c->max_chunks = (max_seq + kChunk - 1) / kChunk;
+    c->vmax8 = (max_seq + kChunk - 1) / kChunk * kChunk;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;
         return DA_ERR_HIP;
@@ -344,7 +546,8 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     ok = ok && hipMalloc(&c->ck, units * c->nck * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->khat, units * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->ring, units * c->Wd * d * es) == hipSuccess;
-    ok = ok && hipMalloc(&c->V, units * max_seq * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->V, units * (size_t)c->vmax8 * d * es) == hipSuccess;
+    if (ok) ok = hipMemset(c->V, 0, units * (size_t)c->vmax8 * d * es) == hipSuccess;   // rows never written must be finite
     ok = ok && hipMalloc((void **)&c->nnz, units * 8) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->part, (size_t)batch * n_q_heads * c->max_chunks * (d + 2) * 4) == hipSuccess;
     if (ok) ok = hipMemset(c->nnz, 0, units * 8) == hipSuccess;

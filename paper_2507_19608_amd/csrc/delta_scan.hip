@@ -77,25 +77,25 @@ int timing_collect(double *ms_per_stage, int *calls_per_stage) {
 
 // The recurrence of Eq. 2-3 is sequential in t and is not an associative scan, but it forgets its
 // past every time a channel fires: from then on the held value is k(t) whatever it was before.
-// So time is cut into chunks that are scanned in parallel from a guessed state, and a short serial
-// pass repairs the start of each chunk:
+// So time is cut into chunks that are scanned in parallel from a guessed incoming state:
 //
-//   pass A  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row and is
-//           exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and writes mask words, held
-//           keys and its final held value as if the guess were true.
-//   pass B  (one wave per (unit, 64 channels), chunks in order): carries the true held value into
-//           each chunk and re-runs rows from the chunk start only while some channel's true held value
-//           still differs from the guessed chain's; after the first row where they agree (both fired, or
-//           the values coincide) the guessed results are the true ones.  Rows walked get their mask word,
-//           held keys and the nnz count corrected.  Exact for any input; the walk is a handful of rows
-//           per chunk when channels fire often and the whole chunk when nothing ever fires.
+//   pass 1  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row and is
+//           exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and records only its final
+//           held value.  That final value is already the true one for every channel that fired at
+//           least once inside the chunk at a row where the true chain fired too - nearly all.
+//   pass 2  same scan, but chunk c starts from pass 1's final value of chunk c - 1, and writes mask
+//           words, held keys, nnz and its own final values.
+//   pass 3  (one wave per (unit, 64 channels), chunks in order): carries the true held value along.
+//           Where it equals the value pass 2 started a chunk from, pass 2's results for the chunk
+//           are the true ones and nothing is touched; otherwise the chunk's rows are re-run from the
+//           true state until it meets pass 2's chain (both hold the same value), correcting mask
+//           words, held keys and nnz on the way.  Exact for any input.
 //
 // One lane per channel; the wave ballot of the threshold decision is the mask word itself.
-constexpr int kScanPrefetch = 16;   // rows of the next chunk that pass B holds in registers
-
-template <typename T>
+template <typename T, bool kFinal>
 __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restrict__ K, T *__restrict__ Khat,
                                                                uint32_t *__restrict__ mask_bits,
+                                                               const T *__restrict__ guess_out,
                                                                T *__restrict__ chunk_out,
                                                                unsigned long long *__restrict__ nnz, int n, int d,
                                                                int L, int nchunks, float theta) {
@@ -111,17 +111,20 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
     const int word = c >> 5;
     const int t0 = chunk * L, t1 = min(n, t0 + L);
 
-    float held;
+    float held = 0.f;
     unsigned long long cnt = 0;
     int t = t0;
     if (chunk == 0) {   // row 0 is the basis: kept whole
-        held = active ? load_f32(Kp, c) : 0.f;
-        if (active) Hp[c] = Kp[c];
-        if (writer) Mp[word] = 0xffffffffu;
-        cnt = __popcll(__ballot(active));
+        if (active) held = load_f32(Kp, c);
+        if (kFinal) {
+            if (active) Hp[c] = Kp[c];
+            if (writer) Mp[word] = 0xffffffffu;
+            cnt = __popcll(__ballot(active));
+        }
         t = 1;
-    } else {
-        held = active ? load_f32(Kp, (size_t)(t0 - 1) * d + c) : 0.f;
+    } else if (active) {
+        held = kFinal ? load_f32(guess_out, ((size_t)unit * nchunks + chunk - 1) * d + c)
+                      : load_f32(Kp, (size_t)(t0 - 1) * d + c);
     }
     constexpr int U = 16;
     for (; t + U <= t1; t += U) {
@@ -133,29 +136,34 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
             const float diff = k[u] - held;                  // Eq. 2 condition in binary32
             const bool fire = active && (fabsf(diff) > theta);
             held = fire ? k[u] : held;                        // Eq. 3
-            const uint64_t b = __ballot(fire);
-            if (writer) Mp[(size_t)(t + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
-            if (active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
-            cnt += __popcll(b);
+            if (kFinal) {
+                const uint64_t b = __ballot(fire);
+                if (writer) Mp[(size_t)(t + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
+                if (active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
+                cnt += __popcll(b);
+            }
         }
     }
     for (; t < t1; ++t) {
         const float k = active ? load_f32(Kp, (size_t)t * d + c) : 0.f;
         const bool fire = active && (fabsf(k - held) > theta);
         held = fire ? k : held;
-        const uint64_t b = __ballot(fire);
-        if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(b >> (lane & 32));
-        if (active) store_from_f32(Hp, (size_t)t * d + c, held);
-        cnt += __popcll(b);
+        if (kFinal) {
+            const uint64_t b = __ballot(fire);
+            if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(b >> (lane & 32));
+            if (active) store_from_f32(Hp, (size_t)t * d + c, held);
+            cnt += __popcll(b);
+        }
     }
     if (active) store_from_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + c, held);
-    if (lane == 0) atomicAdd(nnz + unit, cnt);
+    if (kFinal && lane == 0) atomicAdd(nnz + unit, cnt);
 }
 
 template <typename T>
 __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restrict__ K, T *__restrict__ Khat,
                                                               uint32_t *__restrict__ mask_bits,
-                                                              const T *__restrict__ chunk_out,
+                                                              const T *__restrict__ out1,   // pass 1 final values
+                                                              const T *__restrict__ out2,   // pass 2 final values
                                                               unsigned long long *__restrict__ nnz, int n, int d,
                                                               int L, int nchunks, float theta) {
     const int unit = blockIdx.y;
@@ -169,70 +177,48 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
     uint32_t *Mp = mask_bits + (size_t)unit * n * wpr;
     const bool writer = active && ((lane & 31) == 0);
     const int word = c >> 5;
-    constexpr int P = kScanPrefetch;
+    const T *o1 = out1 + (size_t)unit * nchunks * d + cs;
+    const T *o2 = out2 + (size_t)unit * nchunks * d + cs;
 
-    float held = load_f32(chunk_out, ((size_t)unit * nchunks) * d + cs);   // true state after chunk 0
+    float held = load_f32(o2, 0);   // chunk 0 is exact
     long long adjust = 0;
-    // rows t0-1 .. t0+P-1 of the next chunk, loaded one chunk ahead (addresses do not depend on the state)
-    float kn[P + 1];
-    auto prefetch = [&](int chunk) {
-        const int t0 = chunk * L;
+    constexpr int G = 16;           // chunks whose boundary values are fetched together
+    for (int cb = 1; cb < nchunks; cb += G) {
+        float g1[G], g2[G];
 #pragma unroll
-        for (int u = 0; u <= P; ++u) {
-            const int t = min(t0 - 1 + u, n - 1);
-            kn[u] = load_f32(Kp, (size_t)t * d + cs);
+        for (int u = 0; u < G; ++u) {
+            const int ch = min(cb + u, nchunks - 1);
+            g1[u] = load_f32(o1, (size_t)(ch - 1) * d);   // the value pass 2 started chunk ch from
+            g2[u] = load_f32(o2, (size_t)ch * d);         // the value pass 2 ended chunk ch with
         }
-    };
-    if (nchunks > 1) prefetch(1);
-    for (int chunk = 1; chunk < nchunks; ++chunk) {
-        const int t0 = chunk * L, t1 = min(n, t0 + L);
-        float kc[P + 1];
 #pragma unroll
-        for (int u = 0; u <= P; ++u) kc[u] = kn[u];
-        const float spec_out = load_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + cs);
-        if (chunk + 1 < nchunks) prefetch(chunk + 1);
-        float spec = kc[0];                       // the guess pass A started from: k(t0 - 1)
-        bool synced = !active || (__float_as_uint(held) == __float_as_uint(spec));
-        int t = t0;
-        // rows held in registers
-#pragma unroll
-        for (int u = 1; u <= P; ++u) {
-            if (t < t1 && __any(!synced)) {
-                const float k = kc[u];
-                const bool fs = fabsf(k - spec) > theta;
-                const bool ft = fabsf(k - held) > theta;
-                spec = fs ? k : spec;
-                if (!synced) {
-                    held = ft ? k : held;
-                    store_from_f32(Hp, (size_t)t * d + c, held);
+        for (int u = 0; u < G; ++u) {
+            const int chunk = cb + u;
+            if (chunk < nchunks) {
+                float spec = g1[u];
+                bool synced = !active || (__float_as_uint(held) == __float_as_uint(spec));
+                if (__any(!synced)) {
+                    const int t1 = min(n, chunk * L + L);
+                    for (int t = chunk * L; t < t1 && __any(!synced); ++t) {
+                        const float k = load_f32(Kp, (size_t)t * d + cs);
+                        const bool fs = fabsf(k - spec) > theta;
+                        const bool ft = fabsf(k - held) > theta;
+                        spec = fs ? k : spec;
+                        if (!synced) {
+                            held = ft ? k : held;
+                            store_from_f32(Hp, (size_t)t * d + c, held);
+                        }
+                        const uint64_t bt = __ballot(synced ? fs : ft);
+                        const uint64_t bs = __ballot(fs);
+                        if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
+                        adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
+                        synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
+                    }
                 }
-                const uint64_t bt = __ballot(synced ? fs : ft);
-                const uint64_t bs = __ballot(fs);
-                if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
-                adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
-                synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
-                ++t;
+                // a synced channel ends the chunk where pass 2's chain ended; an unsynced one walked all of it
+                held = synced ? g2[u] : held;
             }
         }
-        // rare: still not synced after the prefetched rows
-        while (t < t1 && __any(!synced)) {
-            const float k = load_f32(Kp, (size_t)t * d + cs);
-            const bool fs = fabsf(k - spec) > theta;
-            const bool ft = fabsf(k - held) > theta;
-            spec = fs ? k : spec;
-            if (!synced) {
-                held = ft ? k : held;
-                store_from_f32(Hp, (size_t)t * d + c, held);
-            }
-            const uint64_t bt = __ballot(synced ? fs : ft);
-            const uint64_t bs = __ballot(fs);
-            if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
-            adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
-            synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
-            ++t;
-        }
-        // a synced channel ends the chunk where the guessed chain ended; an unsynced one walked to t1
-        held = synced ? spec_out : held;
     }
     if (lane == 0 && adjust != 0) atomicAdd(nnz + unit, (unsigned long long)adjust);
 }
@@ -307,14 +293,22 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
                        int n, int d, float theta, hipStream_t s) {
     const int L = delta_scan_chunk_len(n), nchunks = delta_scan_num_chunks(n);
     const int cw = (d + kWave - 1) / kWave;
-    hipLaunchKernelGGL(delta_scan_chunks_kernel<T>, dim3(cw, nchunks, units), dim3(kWave), 0, s, (const T *)K,
-                       (T *)Khat, mask_bits, (T *)chunk_out, (unsigned long long *)nnz, n, d, L, nchunks, theta);
+    T *out1 = (T *)chunk_out;
+    T *out2 = out1 + (size_t)units * nchunks * d;
+    if (nchunks > 1)
+        hipLaunchKernelGGL((delta_scan_chunks_kernel<T, false>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
+                           (const T *)K, (T *)Khat, mask_bits, (const T *)nullptr, out1,
+                           (unsigned long long *)nnz, n, d, L, nchunks, theta);
+    hipLaunchKernelGGL((delta_scan_chunks_kernel<T, true>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
+                       (const T *)K, (T *)Khat, mask_bits, (const T *)out1, out2, (unsigned long long *)nnz, n, d, L,
+                       nchunks, theta);
     if (nchunks > 1)
         hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw, units), dim3(kWave), 0, s, (const T *)K, (T *)Khat,
-                           mask_bits, (const T *)chunk_out, (unsigned long long *)nnz, n, d, L, nchunks, theta);
+                           mask_bits, (const T *)out1, (const T *)out2, (unsigned long long *)nnz, n, d, L, nchunks,
+                           theta);
 }
 
-// Khat [units][n][d] and chunk_out [units][delta_scan_num_chunks(n)][d] are required scratch/outputs.
+// Khat [units][n][d] and chunk_out [2][units][delta_scan_num_chunks(n)][d] are required scratch/outputs.
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s) {
     launch_fill_u64(nnz, 0, units, s);
