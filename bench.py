@@ -111,23 +111,19 @@ def prefill_bench(args, da, wl, torch, np):
 
 
 def cpu_baseline(w, x, theta, np):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload: blocks of 32 query
-    rows spread evenly over the sequence, every query head of batch entry 0."""
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: every query row and
+    every query head of batch entry 0 (one of w.batch entries)."""
     from oracle import delta_oracle as orc
-    n, d, g = w.seq_len, w.head_dim, w.n_q_heads // w.n_kv_heads
-    nblocks, blk = 64, 32
-    starts = [int((k + 0.5) * n / nblocks) - blk // 2 for k in range(nblocks)]
+    n, g = w.seq_len, w.n_q_heads // w.n_kv_heads
     t0 = time.perf_counter()
     for hk in range(w.n_kv_heads):
         _, dK, _, _ = orc.delta_scan(x["K"][0, hk], theta)
         for h in range(hk * g, (hk + 1) * g):
-            for s in starts:
-                orc.hybrid_rows(x["Q"][0, h], x["K"][0, hk], x["V"][0, hk], dK, w.window, 0, None, 0, (s, s + blk))
+            orc.hybrid_rows(x["Q"][0, h], x["K"][0, hk], x["V"][0, hk], dK, w.window, 0, None, 0, (0, n))
     dt = time.perf_counter() - t0
-    rows = nblocks * blk
-    return {"value": rows / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{rows} query rows ({nblocks} blocks of {blk}, evenly spread) x all {w.n_q_heads} query heads "
-                      f"of batch entry 0 of the same workload, fp64, {dt:.1f} s"}
+    return {"value": n / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"batch entry 0 of {w.batch}: all {n} query rows x all {w.n_q_heads} query heads of the same "
+                      f"workload, fp64, {dt:.1f} s"}
 
 
 def decode_bench(args, da, wl, torch, np):

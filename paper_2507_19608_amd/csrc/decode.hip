@@ -248,17 +248,17 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 //      4 (l / 16) + r);
 //   4. per-head chunk softmax with lanes = rows; P V on the matrix cores against the 8-row
 //      interleaved V cache, partial (o, m, l) to the per-chunk scratch.
+template <int DT>   // head_dim known at compile time (64, 128), or 0 for any multiple of 32
 __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const bf16_t *__restrict__ q_new, int t,
                                                                float scale_log2) {
     extern __shared__ float lds_f[];
     char *lds = (char *)lds_f;
-    const int d = c.d, wpr = d >> 5;
+    const int d = DT ? DT : c.d, wpr = d >> 5;
     const int nw = (d + kWave - 1) / kWave;
     const int ldk = d + 8;
     bf16_t *ktile = (bf16_t *)lds;                           // [kChunk][d + 8]
     bf16_t *sv = ktile + kChunk * ldk;                       // staged surviving values, <= kChunk * d + 8
-    float *sc = (float *)(sv + kChunk * d + 16);             // [16][kChunk] scores, heads x rows
-    bf16_t *pt = (bf16_t *)(sc + 16 * kChunk);               // [16][kChunk + 8] probabilities, heads x rows
+    bf16_t *pt = sv + kChunk * d + 16;                       // [16][kChunk + 8] probabilities, heads x rows
     const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
     const int r0 = chunk * kChunk;
     const int r1 = min(r0 + kChunk, t + 1);
@@ -271,106 +271,176 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
     const uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
     const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
     const int l16 = lane & 15, lg = lane >> 4;
+    const int ks_n = d >> 5, ct_n = d >> 4;
 
+    // everything whose address does not depend on loaded data is requested up front
+    uint32_t roffv = 0, s_end = 0;
+    uint32_t mk[8];
+    uint32_t held[4] = {0u, 0u, 0u, 0u};
     if (hist_rows > 0) {
-        // 1. stage the chunk's survivors: rows r0 .. r0 + hist_rows - 1 occupy [rp[r0], rp[r0 + hist_rows])
-        const uint32_t roffv = rp[r0 + min(lane, hist_rows)];
-        const uint32_t s_begin = __builtin_amdgcn_readfirstlane(roffv);
-        const uint32_t s_end = rp[r0 + hist_rows];
-        const uint32_t base = s_begin & ~7u;
-        for (uint32_t i = base + lane * 8; i < s_end; i += kWave * 8)
-            *(u32x4 *)(sv + (i - base)) = *(const u32x4 *)(surv + i);
-        uint32_t mk[8];
+        roffv = rp[r0 + min(lane, hist_rows)];
+        s_end = rp[r0 + hist_rows];
 #pragma unroll
         for (int w2 = 0; w2 < 8; ++w2) mk[w2] = (w2 < wpr && lane < hist_rows) ? Mp[(size_t)lane * wpr + w2] : 0u;
-        uint32_t held[4] = {0u, 0u, 0u, 0u};
         if (r0 > 0) {
             const bf16_t *ckp = (const bf16_t *)c.ck + ((size_t)unit * c.nck + chunk) * d;
 #pragma unroll
             for (int w = 0; w < 4; ++w)
                 if (w < nw && w * kWave + lane < d) held[w] = ckp[w * kWave + lane];
         }
-        __syncthreads();
-        // 2. reference keys of the history rows
-        for (int r = 0; r < hist_rows; ++r) {
-            uint32_t off = __builtin_amdgcn_readlane(roffv, r) - base;
+    }
+    // raw keys of the window rows (16 bytes per lane per copy) straight into the tile; zero past the newest key
+    {
+        const int segs = d >> 3;
+        const int first = hist_rows * segs, last = kChunk * segs;
+        const bf16_t *ringu = (const bf16_t *)c.ring + (size_t)unit * c.Wd * d;
+        for (int i0 = first + lane; i0 < last; i0 += 4 * kWave) {
+            u32x4 v[4];
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                if (w < nw) {
-                    const uint32_t lo = __builtin_amdgcn_readlane(mk[2 * w], r);
-                    const uint32_t hi = __builtin_amdgcn_readlane(mk[2 * w + 1], r);
-                    const uint64_t m64 = (uint64_t)lo | ((uint64_t)hi << 32);
-                    const bool bit = (m64 >> lane) & 1ull;
-                    const uint32_t val = sv[off + lanes_below(m64)];
-                    held[w] = bit ? val : held[w];
-                    if (w * kWave + lane < d) ktile[r * ldk + w * kWave + lane] = (bf16_t)held[w];
-                    off += __popcll(m64);
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kWave;
+                const int r = min(i, last - 1) / segs, seg = min(i, last - 1) % segs;
+                v[u] = u32x4{0u, 0u, 0u, 0u};
+                if (i < last && r < nrows) v[u] = *(const u32x4 *)(ringu + (size_t)((r0 + r) % c.Wd) * d + seg * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kWave;
+                if (i < last) *(u32x4 *)(ktile + (i / segs) * ldk + (i % segs) * 8) = v[u];
+            }
+        }
+    }
+    for (int i = lane; i < 16 * (kChunk + 8); i += kWave) pt[i] = 0;
+    // V operands of the whole chunk (needed last, requested first)
+    constexpr int kVregs = DT ? 2 * (DT / 16) : 1;
+    u32x4 vop[kVregs];
+    if (DT) {
+#pragma unroll
+        for (int i = 0; i < kVregs; ++i)
+            vop[i] = *(const u32x4 *)((const bf16_t *)c.V +
+                                      v_index(unit, c.vmax8, d, r0 + 32 * (i & 1) + 8 * lg, 16 * (i >> 1) + l16));
+    }
+
+    if (hist_rows > 0) {
+        // 1. stage the chunk's survivors: rows r0 .. r0 + hist_rows - 1 occupy [rp[r0], rp[r0 + hist_rows])
+        const uint32_t s_begin = __builtin_amdgcn_readfirstlane(roffv);
+        const uint32_t base = s_begin & ~7u;
+        for (uint32_t i = base + lane * 8; i < s_end; i += kWave * 8)
+            *(u32x4 *)(sv + (i - base)) = *(const u32x4 *)(surv + i);
+        __syncthreads();
+        // 2. reference keys of the history rows, 8 rows per batch so that the LDS reads of a batch are
+        //    in flight together (their addresses depend on the masks only, not on the held values)
+        for (int rb = 0; rb < hist_rows; rb += 8) {
+            uint32_t val[8][4];
+            bool bit[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = min(rb + u, hist_rows - 1);
+                uint32_t off = __builtin_amdgcn_readlane(roffv, r) - base;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    if (w < nw) {
+                        const uint32_t lo = __builtin_amdgcn_readlane(mk[2 * w], r);
+                        const uint32_t hi = __builtin_amdgcn_readlane(mk[2 * w + 1], r);
+                        const uint64_t m64 = (uint64_t)lo | ((uint64_t)hi << 32);
+                        bit[u][w] = (m64 >> lane) & 1ull;
+                        val[u][w] = sv[off + lanes_below(m64)];
+                        off += __popcll(m64);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (rb + u < hist_rows) {
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        if (w < nw) {
+                            held[w] = bit[u][w] ? val[u][w] : held[w];
+                            if (w * kWave + lane < d) ktile[(rb + u) * ldk + w * kWave + lane] = (bf16_t)held[w];
+                        }
+                    }
                 }
             }
         }
     }
-    // window rows come from the raw-key ring; rows past the newest key are zero
-    for (int r = hist_rows; r < kChunk; ++r) {
-        const int row = r0 + r;
-        const bf16_t *ringrow = (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * d;
-        for (int w = 0; w < nw; ++w) {
-            const int ch = w * kWave + lane;
-            if (ch < d) ktile[r * ldk + ch] = (r < nrows) ? ringrow[ch] : (bf16_t)0;
-        }
-    }
-    for (int i = lane; i < 16 * (kChunk + 8); i += kWave) pt[i] = 0;
     __syncthreads();
 
     for (int hbase = 0; hbase < g; hbase += 16) {
         const int gh = min(16, g - hbase);
-        // 3. scores
+        // 3. scores: lane l ends up with head l % 16 at rows 16 rt + 4 (l / 16) + r
         const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + hbase + min(l16, gh - 1)) * d;
+        f32x4 acc[4];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < ks_n; ++ks) {
+            u32x4 bv = *(const u32x4 *)(qrow + 32 * ks + 8 * lg);
+            if (l16 >= gh) bv = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) {
+                const u32x4 av = *(const u32x4 *)(ktile + (16 * rt + l16) * ldk + 32 * ks + 8 * lg);
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                  __builtin_bit_cast(bf16x8, bv), acc[rt], 0, 0, 0);
+            }
+        }
+        // 4. chunk softmax per head: 16 values in registers, then the 4 lane groups that share the head
+        float m = -INFINITY;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool valid = 16 * rt + 4 * lg + r < nrows;
+                acc[rt][r] = valid ? acc[rt][r] * scale_log2 : -INFINITY;
+                m = fmaxf(m, acc[rt][r]);
+            }
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));                     // row r0 is always valid, so m is finite
+        float l = 0.f;
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int ks = 0; ks < (d >> 5); ++ks) {
-                const u32x4 av = *(const u32x4 *)(ktile + (16 * rt + l16) * ldk + 32 * ks + 8 * lg);
-                u32x4 bv = *(const u32x4 *)(qrow + 32 * ks + 8 * lg);
-                if (l16 >= gh) bv = u32x4{0u, 0u, 0u, 0u};
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
-                                                              __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
-            }
+            float p[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) sc[l16 * kChunk + 16 * rt + 4 * lg + r] = acc[r];
-        }
-        __syncthreads();
-        // 4. chunk softmax per head, lanes = rows
-        const bool valid = lane < nrows;
-        for (int h = 0; h < gh; ++h) {
-            const float sv_ = valid ? sc[h * kChunk + lane] * scale_log2 : -INFINITY;
-            const float m = wave_max(sv_);                   // row r0 is always valid, so m is finite
-            const float p = valid ? exp2f(sv_ - m) : 0.f;
-            const float l = wave_sum(p);
-            pt[h * (kChunk + 8) + lane] = f32_to_bf16(p);
-            if (lane == 0) {
-                float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (d + 2);
-                out[d] = m;
-                out[d + 1] = l;
+            for (int r = 0; r < 4; ++r) {
+                p[r] = exp2f(acc[rt][r] - m);
+                l += p[r];
             }
+            uint2 pk;
+            pk.x = (uint32_t)f32_to_bf16(p[0]) | ((uint32_t)f32_to_bf16(p[1]) << 16);
+            pk.y = (uint32_t)f32_to_bf16(p[2]) | ((uint32_t)f32_to_bf16(p[3]) << 16);
+            *(uint2 *)(pt + l16 * (kChunk + 8) + 16 * rt + 4 * lg) = pk;
+        }
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (lane < gh) {
+            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * (d + 2);
+            out[d] = m;
+            out[d + 1] = l;
         }
         __syncthreads();
         // P V: heads x channels, contraction over the chunk's 64 rows
-        for (int ct = 0; ct < (d >> 4); ++ct) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        u32x4 pa[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) pa[ks] = *(const u32x4 *)(pt + l16 * (kChunk + 8) + 32 * ks + 8 * lg);
+#pragma unroll
+        for (int ct = 0; ct < (DT ? DT / 16 : 16); ++ct) {
+            if (!DT && ct >= ct_n) break;
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const u32x4 av = *(const u32x4 *)(pt + l16 * (kChunk + 8) + 32 * ks + 8 * lg);
-                const u32x4 bv = *(const u32x4 *)((const bf16_t *)c.V +
-                                                  v_index(unit, c.vmax8, d, r0 + 32 * ks + 8 * lg, 16 * ct + l16));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
-                                                              __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+                u32x4 bv;
+                if (DT)
+                    bv = vop[2 * ct + ks];
+                else
+                    bv = *(const u32x4 *)((const bf16_t *)c.V +
+                                          v_index(unit, c.vmax8, d, r0 + 32 * ks + 8 * lg, 16 * ct + l16));
+                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa[ks]),
+                                                            __builtin_bit_cast(bf16x8, bv), o, 0, 0, 0);
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int h = 4 * lg + r;
                 if (h < gh)
                     c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (d + 2) + 16 * ct + l16] =
-                        acc[r];
+                        o[r];
             }
         }
         __syncthreads();
@@ -394,12 +464,21 @@ __global__ __launch_bounds__(64) void decode_combine2_kernel(da_cache c, T *__re
         const float wk = k < nchunks ? exp2f(part[(size_t)k * (d + 2) + d] - M) : 0.f;
         L += k < nchunks ? wk * part[(size_t)k * (d + 2) + d + 1] : 0.f;
         const int cnt = min(kWave, nchunks - k0);
-        for (int kk = 0; kk < cnt; ++kk) {
-            const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
-            const float *row = part + (size_t)(k0 + kk) * (d + 2);
+        for (int kb = 0; kb < cnt; kb += 8) {
+            float w[8], x[8][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (i * kWave + lane < d) acc[i] = fmaf(w, row[i * kWave + lane], acc[i]);
+            for (int u = 0; u < 8; ++u) {
+                const int kk = min(kb + u, cnt - 1);
+                w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
+                if (kb + u >= cnt) w[u] = 0.f;
+                const float *row = part + (size_t)(k0 + kk) * (d + 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[u][i] = (i * kWave + lane < d) ? row[i * kWave + lane] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(w[u], x[u][i], acc[i]);
         }
     }
     L = wave_sum(L);
@@ -441,17 +520,23 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const int nchunks = t / kChunk + 1;
     stage_begin(kStageChunk, s);
     if (c->dtype == DA_BF16) {
-        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * kChunk * 4 +
-                           16 * (kChunk + 8) * 2;
+        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
         static bool attr16_done = false;   // d = 256 needs more than 64 KiB
         if (!attr16_done) {
-            (void)hipFuncSetAttribute((const void *)decode_chunk_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 + 16 * kChunk * 4 +
+            (void)hipFuncSetAttribute((const void *)decode_chunk_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 +
                                             16 * (kChunk + 8) * 2));
             attr16_done = true;
         }
-        hipLaunchKernelGGL(decode_chunk_bf16_kernel, dim3(nchunks, units), dim3(64), lds, s, *c, (const bf16_t *)q, t,
-                           sc);
+        if (c->d == 64)
+            hipLaunchKernelGGL(decode_chunk_bf16_kernel<64>, dim3(nchunks, units), dim3(64), lds, s, *c,
+                               (const bf16_t *)q, t, sc);
+        else if (c->d == 128)
+            hipLaunchKernelGGL(decode_chunk_bf16_kernel<128>, dim3(nchunks, units), dim3(64), lds, s, *c,
+                               (const bf16_t *)q, t, sc);
+        else
+            hipLaunchKernelGGL(decode_chunk_bf16_kernel<0>, dim3(nchunks, units), dim3(64), lds, s, *c,
+                               (const bf16_t *)q, t, sc);
     } else {
         const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
         static bool attr_done = false;   // d = 256 needs slightly more than 64 KiB
