@@ -33,7 +33,7 @@ def outside_rows(n, W):
 
 
 def prefill_bench(args, da, wl, torch, np):
-    w = {"C5": wl.C5, "C3": wl.C3, "C2": wl.C2}[args.workload]
+    w = {"C5": wl.c5(args.sparsity, args.p_jump), "C3": wl.C3, "C2": wl.C2}[args.workload]
     mode = da.DA_SCORE_GATHER if args.mode == "gather" else da.DA_SCORE_REBASE
     theta = wl.theta_for(w)
     x = wl.generate(w)
@@ -185,6 +185,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C5", choices=["C5", "C3", "C2"])
     ap.add_argument("--mode", default="gather", choices=["gather", "rebase"])
+    ap.add_argument("--sparsity", type=float, default=0.60, help="C5 only: 0, 0.4, 0.6 or 0.8 (tuned theta)")
+    ap.add_argument("--p-jump", type=float, default=0.05, help="C5 only: 0.01, 0.05 or 0.20")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     if (far_blocks > 0) {
         const char *qtb = (const char *)qt;
         const uint32_t lane_off = (uint32_t)lane * 8u;
-        constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 2 * 64;
+        constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 4 * 64;
         char *ring = lds_raw + (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
         for (int o = lane * 16; o < kRingBytes; o += 64 * 16) *(u32x4 *)(ring + o) = u32x4{0u, 0u, 0u, 0u};
 
@@ -279,17 +279,20 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             uint32_t cend = pk & 0xffu;
             int cc = 0;
             float u[4] = {0.f, 0.f, 0.f, 0.f};
-            Set A, B;
-            rd_ch(A, 0);
-            rd_d(A, 0);
-            rd_ch(B, 1);
-            issue_q(A);
-            // consume chunk t (set x) while the q reads of chunk t+1 (set y) and the entry reads of
-            // chunks t+1 / t+2 are in flight
+            Set S0, S1, S2;
+            rd_ch(S0, 0);
+            rd_ch(S1, 1);
+            rd_ch(S2, 2);
+            issue_q(S0);
+            rd_d(S0, 0);
+            issue_q(S1);
+            rd_d(S1, 1);
+            // consume chunk t (set x) while the q / delta reads of chunks t+1 (in flight since the previous
+            // step) and t+2 (set y, issued here) and the channel reads of chunk t+3 are in flight
             auto step = [&](Set &x, Set &y, uint32_t t) {
+                rd_ch(x, t + 3);
                 issue_q(y);
-                rd_d(y, t + 1);
-                rd_ch(x, t + 2);
+                rd_d(y, t + 2);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float dl = x.d[i >> 2][i & 3];
@@ -306,57 +309,56 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 }
             };
             uint32_t t = 0;
-            for (; t + 1 < total; t += 2) {
-                step(A, B, t);
-                step(B, A, t + 1);
+            for (; t + 2 < total; t += 3) {
+                step(S0, S2, t);
+                step(S1, S0, t + 1);
+                step(S2, S1, t + 2);
             }
-            if (t < total) step(A, B, t);
+            if (t < total) step(S0, S2, t);
+            if (t + 1 < total) step(S1, S0, t + 1);
         };
 
-        for (int blk = 0; blk <= far_blocks; ++blk) {
+        // per block: gather -> (all waves) -> owners read the updates -> (all waves) -> softmax and PV
+        for (int blk = 0; blk < far_blocks; ++blk) {
+            w_store(st, pk_cur);                                 // this block's chunks into the ring
+            const uint32_t pk = pk_cur;
+            pk_cur = pk_nxt;
+            g_issue(st, blk + 1, pk_cur);                        // next block's chunks into registers
+            pk_nxt = pack_of(blk + 2);
+            gather_block(pk);
             u32x4 vreg[2 * MT];
+            load_v(vreg, blk * kTB);
+            __syncthreads();                                     // u of this block complete
+            // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1
+            // (the matrix-core D layout).  A lane sums inside its own groups and gets the other
+            // half's group totals from its partner lane, so the running Eq. 4 score advances in
+            // column order.
+            const float *up = ubuf + (4 * half) * kRows + my_sr;
+            float w[16], t_own[4], t_oth[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float run = 0.f;
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    run += up[(8 * q + bb) * kRows];
+                    w[4 * q + bb] = run;
+                }
+                t_own[q] = run;
+            }
+            __syncthreads();                                     // u buffer free for the next block
+#pragma unroll
+            for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
             float s[16];
-            if (blk > 0) {
-                __syncthreads();                                 // u of block blk-1 complete
-                // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1
-                // (the matrix-core D layout).  A lane sums inside its own groups and gets the other
-                // half's group totals from its partner lane, so the running Eq. 4 score advances in
-                // column order.
-                const float *up = ubuf + (4 * half) * kRows + my_sr;
-                float w[16], t_own[4], t_oth[4];
+            float base = r_run;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float run = 0.f;
+            for (int q = 0; q < 4; ++q) {
+                const float mine = half ? base + t_oth[q] : base;
 #pragma unroll
-                    for (int bb = 0; bb < 4; ++bb) {
-                        run += up[(8 * q + bb) * kRows];
-                        w[4 * q + bb] = run;
-                    }
-                    t_own[q] = run;
-                }
-                __syncthreads();                                 // u buffer free for the next block
-#pragma unroll
-                for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
-                float base = r_run;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float mine = half ? base + t_oth[q] : base;
-#pragma unroll
-                    for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = (mine + w[4 * q + bb]) * far_scale;
-                    base += t_own[q] + t_oth[q];
-                }
-                r_run = base;
-                load_v(vreg, (blk - 1) * kTB);                   // in flight during the next gather
+                for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = (mine + w[4 * q + bb]) * far_scale;
+                base += t_own[q] + t_oth[q];
             }
-            if (blk < far_blocks) {
-                w_store(st, pk_cur);                             // this block's chunks into the ring
-                const uint32_t pk = pk_cur;
-                pk_cur = pk_nxt;
-                g_issue(st, blk + 1, pk_cur);                    // next block's chunks into registers
-                pk_nxt = pack_of(blk + 2);
-                gather_block(pk);
-            }
-            if (blk > 0) softmax_pv(s, vreg);
+            r_run = base;
+            softmax_pv(s, vreg);
         }
     }
 
@@ -515,7 +517,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.n + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
-    const size_t lds = (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 2 * 64);
+    const size_t lds = (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
