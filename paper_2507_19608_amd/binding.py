@@ -9,7 +9,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libdelta_attn.so")
+LIB_PATH = os.environ.get("DELTA_ATTN_LIB", os.path.join(HERE, "libdelta_attn.so"))   # override: load another build
 
 DA_OK = 0
 DA_F32, DA_BF16 = 0, 1
