@@ -363,84 +363,93 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     }
 
     // ---------------------------------------------------------------- near blocks (and all blocks in rebase mode)
+    // Exact scores K Q^T (and K_hat Q^T where needed) on the matrix cores.  The K / K_hat / V tiles of a
+    // block are fetched once per work group, one 16-byte piece per thread, a block ahead into registers,
+    // then parked in LDS in operand order (lane-contiguous 16-byte slots, conflict free) where all 8 waves
+    // read them.  Two LDS buffers alternate; one barrier per block.
     if (far_blocks < nblocks) {
         u32x4 qreg[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
-        auto load_x = [&](u32x4 (&xr)[KS], const bf16_t *X, int jb) {
-            const bf16_t *xrow = X + (size_t)min(jb + li, n - 1) * D + half * 8;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) xr[ks] = *(const u32x4 *)(xrow + ks * 16);
+        constexpr int kTileBytes = D * 64;                       // 32 keys x D channels, bf16
+        constexpr int kPieces = kTileBytes / 16;                 // 16-byte pieces per tile (256 or 512)
+        char *tiles = lds_raw + (size_t)D * kRows * 2;           // [2 buffers][K, K_hat, V]
+        const bool has_piece = tid < kPieces;
+        const int pr = tid / (D / 8), pseg = tid % (D / 8);      // K piece: key row, 8-channel segment
+        const int kslot = ((pseg >> 1) * 64 + (pseg & 1) * 32 + pr) * 16;   // its operand-order slot
+        // operand X of a block: K_hat while every row has the block outside its window (rebase mode), else K
+        auto first_src = [&](int jb) -> const bf16_t * { return (jb + kTB <= win_first) ? Hp : Kp; };
+        struct Pieces {
+            u32x4 k, h, v;
         };
-        // transposed score tile S^T[key][score row] = X[jb + key] . q
-        auto score_tile = [&](const u32x4 (&xr)[KS]) -> f32x16 {
+        auto load_tiles = [&](Pieces &pc, int blk) {
+            const int jb = blk * kTB;
+            if (has_piece) {
+                const size_t roff = (size_t)min(jb + pr, n - 1) * D + pseg * 8;
+                pc.k = *(const u32x4 *)(first_src(jb) + roff);
+                if (!aligned) pc.h = *(const u32x4 *)(Hp + roff);
+                pc.v = *((const u32x4 *)Vtp + (size_t)blk * kPieces + tid);
+            }
+        };
+        auto store_tiles = [&](const Pieces &pc, int buf) {
+            char *base = tiles + buf * (3 * kTileBytes);
+            if (has_piece) {
+                *(u32x4 *)(base + kslot) = pc.k;
+                if (!aligned) *(u32x4 *)(base + kTileBytes + kslot) = pc.h;
+                *(u32x4 *)(base + 2 * kTileBytes + tid * 16) = pc.v;
+            }
+        };
+        // transposed score tile S^T[key][score row] = X[jb + key] . q, X tile in operand order at xt
+        auto score_tile = [&](const char *xt) -> f32x16 {
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xr[ks]), as_bf16x8(qreg[ks]), acc, 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 xa = *(const u32x4 *)(xt + (ks * 64 + lane) * 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xa), as_bf16x8(qreg[ks]), acc, 0, 0, 0);
+            }
             return acc;
         };
-        // operand X of a block: K_hat while every row has the block outside its window (rebase mode), else K
-        auto first_src = [&](int jb) -> const bf16_t * { return (jb + kTB <= win_first) ? Hp : Kp; };
-        if (aligned) {
-            // every row of the tile has the same window: blocks left of it use K_hat (rebase mode), the
-            // window itself uses K with the causal mask
-            for (int blk = far_blocks; blk < nblocks; ++blk) {
-                const int jb = blk * kTB;
-                float s[16];
-                {
-                    u32x4 xk[KS];
-                    load_x(xk, first_src(jb), jb);
-                    const f32x16 sk = score_tile(xk);
-                    if (jb + kTB <= i0 + 1) {   // no masked entry for any row of the tile
+        Pieces pc;
+        load_tiles(pc, far_blocks);
+        __syncthreads();                                         // the far loop's LDS use is over
+        for (int blk = far_blocks; blk < nblocks; ++blk) {
+            const int jb = blk * kTB;
+            const char *base = tiles + (blk & 1) * (3 * kTileBytes);
+            store_tiles(pc, blk & 1);
+            __syncthreads();
+            if (blk + 1 < nblocks) load_tiles(pc, blk + 1);      // in flight while this block is computed
+            float s[16];
+            {
+                const f32x16 sk = score_tile(base);
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) s[r] = sk[r] * a.scale_log2;
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                            s[r] = (j <= my_i) ? sk[r] * a.scale_log2 : -INFINITY;
-                        }
-                    }
-                }
-                u32x4 vreg[2 * MT];
-                load_v(vreg, jb);
-                softmax_pv(s, vreg);
+                for (int r = 0; r < 16; ++r) s[r] = sk[r];
             }
-        } else {
-            // the tile straddles window squares: per element, exact score inside the row's own window,
-            // K_hat score (telescoped Eq. 4) left of it
-            for (int blk = far_blocks; blk < nblocks; ++blk) {
-                const int jb = blk * kTB;
-                float s[16];
-                {
-                    u32x4 xk[KS];
-                    load_x(xk, first_src(jb), jb);
-                    const f32x16 sk = score_tile(xk);
+            if (!aligned && first_src(jb) == Kp) {
+                // the tile straddles window squares: exact score inside the row's own window, K_hat score
+                // (telescoped Eq. 4) left of it
+                const f32x16 sh = score_tile(base + kTileBytes);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[r] = sk[r];
+                for (int r = 0; r < 16; ++r) {
+                    const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
+                    s[r] = (j >= my_win) ? s[r] : sh[r];
                 }
-                if (first_src(jb) == Kp) {
-                    u32x4 xh[KS];
-                    load_x(xh, Hp, jb);
-                    const f32x16 sh = score_tile(xh);
+            }
+            if (jb + kTB <= i0 + 1) {   // no masked entry for any row of the tile
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                        s[r] = (j >= my_win) ? s[r] : sh[r];
-                    }
-                }
+                for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
+            } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
                     s[r] = (j <= my_i) ? s[r] * a.scale_log2 : -INFINITY;
                 }
-                u32x4 vreg[2 * MT];
-                load_v(vreg, jb);
-                softmax_pv(s, vreg);
             }
+            u32x4 vreg[2 * MT];
+#pragma unroll
+            for (int k = 0; k < 2 * MT; ++k) vreg[k] = *(const u32x4 *)(base + 2 * kTileBytes + (k * 64 + lane) * 16);
+            softmax_pv(s, vreg);
         }
     }
 
@@ -517,7 +526,9 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.n + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
-    const size_t lds = (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
+    const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
+    const size_t lds_near = (size_t)6 * D * 64;
+    const size_t lds = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
