@@ -32,13 +32,16 @@ def outside_rows(n, W):
     return np.maximum(0, n - np.minimum(n, (j // W + 1) * W))
 
 
-def prefill_bench(args, da, wl, torch, np):
+def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
     w = {"C5": wl.c5(args.sparsity, args.p_jump), "C3": wl.C3, "C2": wl.C2}[args.workload]
-    mode = da.DA_SCORE_GATHER if args.mode == "gather" else da.DA_SCORE_REBASE
+    mode = da.DA_SCORE_GATHER if mode_name == "gather" else da.DA_SCORE_REBASE
     theta = wl.theta_for(w)
-    x = wl.generate(w)
     tdt = torch.bfloat16
-    Q, K, V = (torch.from_numpy(x[k]).to(tdt).cuda().contiguous() for k in "QKV")
+    if data is None:
+        x = wl.generate(w)
+        Q, K, V = (torch.from_numpy(x[k]).to(tdt).cuda().contiguous() for k in "QKV")
+    else:
+        x, (Q, K, V) = data
     B, Hq, n, d = Q.shape
     Hkv = K.shape[1]
     g = Hq // Hkv
@@ -50,6 +53,12 @@ def prefill_bench(args, da, wl, torch, np):
     def step():
         da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out)
 
+    if args.calibrate_copy:   # a plain copy of known size, to scale the profiler's byte counters
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -103,11 +112,11 @@ def prefill_bench(args, da, wl, torch, np):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.key()}: prefill B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} W{w.window} theta={theta:.6g} "
-                               f"p_jump={w.p_jump}", "score_mode": args.mode, "s_m": s_m, "s_c": s_c},
+                               f"p_jump={w.p_jump}", "score_mode": mode_name, "s_m": s_m, "s_c": s_c},
         "stage_ms": {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items() if v[1]},
         "roofline": roof,
     }
-    return res, (w, x, theta)
+    return res, (w, x, theta, (Q, K, V))
 
 
 def cpu_baseline(w, x, theta, np):
@@ -188,6 +197,9 @@ def main():
     ap.add_argument("--sparsity", type=float, default=0.60, help="C5 only: 0, 0.4, 0.6 or 0.8 (tuned theta)")
     ap.add_argument("--p-jump", type=float, default=0.05, help="C5 only: 0.01, 0.05 or 0.20")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-other-mode", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (profiling aid for scaling FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -201,7 +213,14 @@ def main():
         sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
         sys.exit(1)
     da.lib()
-    res, (w, x, theta) = prefill_bench(args, da, wl, torch, np)
+    res, (w, x, theta, dev) = prefill_bench(args, da, wl, torch, np, args.mode)
+    if not args.no_other_mode:
+        # the same workload through the other score mode (same results; see include/delta_attn.h)
+        other = "rebase" if args.mode == "gather" else "gather"
+        r2, _ = prefill_bench(args, da, wl, torch, np, other, data=(x, dev))
+        res["other_score_mode"] = {k: r2[k] for k in ("value", "unit", "ms_per_step", "stage_ms", "roofline")}
+        res["other_score_mode"]["score_mode"] = other
+    del dev
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(w, x, theta, np)
     del x
