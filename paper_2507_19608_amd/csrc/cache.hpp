@@ -14,15 +14,15 @@ struct da_cache {
     int device;
     int nck;              // checkpoints per unit: max_seq / kChunk + 1
     int max_chunks;       // (max_seq + kChunk - 1) / kChunk
-    int vmax8;            // max_seq rounded up to a multiple of 8 (row capacity of V)
+    int vrows;            // max_seq rounded up to a whole chunk (row capacity of V)
     // per (batch, KV head) unit, all device memory:
     uint32_t *mask;       // [units][max_seq][d/32]   delta mask bits
-    void *surv;           // [units][max_seq * d]     surviving key values, row after row, channel order
-    uint32_t *roff;       // [units][max_seq + 1]     start of each row in surv
+    void *surv;           // [units][max_chunks][kChunk * d] surviving key values of a chunk: row after row, channel order
+    uint32_t *ccnt;       // [units][max_chunks]      survivors stored in each chunk
     void *ck;             // [units][nck][d]          ck[m] = reference key after row m*kChunk - 1 (m >= 1)
     void *khat;           // [units][d]               current reference key
     void *ring;           // [units][Wd][d]           raw key of position p at slot p % Wd
-    void *V;              // [units][vmax8 / 8][d][8]: 8 rows interleaved per channel
+    void *V;              // [units][vrows / 8][d][8]: 8 rows interleaved per channel
     uint64_t *nnz;        // [units]
     float *part;          // [B*Hq][max_chunks][d + 2] per-chunk (o, m, l) partials of one decode step
 };

@@ -12,90 +12,122 @@ using namespace da;
 
 namespace {
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 // V cache layout: 8 rows interleaved per channel, [unit][t / 8][channel][t % 8], so that eight
 // consecutive rows of one channel are contiguous (the k-contiguous operand order of the matrix
-// cores).  vmax8 = max_seq rounded up to 8.
-__device__ __forceinline__ size_t v_index(int unit, int vmax8, int d, int t, int ch) {
-    return ((size_t)unit * (vmax8 >> 3) + (t >> 3)) * ((size_t)d * 8) + (size_t)ch * 8 + (t & 7);
+// cores).  vrows = row capacity (max_seq rounded up to a whole chunk).
+__device__ __forceinline__ size_t v_index(int unit, int vrows, int d, int t, int ch) {
+    return ((size_t)unit * (vrows >> 3) + (t >> 3)) * ((size_t)d * 8) + (size_t)ch * 8 + (t & 7);
+}
+
+// surviving key values of one chunk of kChunk rows: row after row, channel order, fixed room of kChunk * d
+template <typename T>
+__device__ __forceinline__ T *surv_chunk(const da_cache &c, int unit, int chunk) {
+    return (T *)c.surv + ((size_t)unit * c.max_chunks + chunk) * ((size_t)kChunk * c.d);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s);
+    return v;
+}
+// exclusive prefix sum over the 64 lanes; *total receives the wave sum
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, uint32_t *total) {
+    const int lane = threadIdx.x & 63;
+    uint32_t inc = v;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const uint32_t o = __shfl_up(inc, s);
+        if (lane >= s) inc += o;
+    }
+    *total = __shfl(inc, 63);
+    return inc - v;
 }
 
 // ---------------------------------------------------------------------------------- cache fill
-__global__ __launch_bounds__(256) void row_offsets_kernel(const uint32_t *__restrict__ counts,
-                                                          uint32_t *__restrict__ roff, const uint64_t *nnz_in,
-                                                          uint64_t *nnz_out, int n, int max_seq) {
-    __shared__ uint32_t buf[256];
-    const int unit = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *cp = counts + (size_t)unit * n;
-    uint32_t *rp = roff + (size_t)unit * (max_seq + 1);
-    uint32_t carry = 0;
-    for (int base = 0; base < n; base += 256) {
-        const uint32_t v = (base + tid < n) ? cp[base + tid] : 0u;
-        buf[tid] = v;
-        __syncthreads();
-        for (int s = 1; s < 256; s <<= 1) {
-            const uint32_t add = (tid >= s) ? buf[tid - s] : 0u;
-            __syncthreads();
-            buf[tid] += add;
-            __syncthreads();
-        }
-        if (base + tid < n) rp[base + tid] = carry + buf[tid] - v;   // exclusive
-        carry += buf[255];
-        __syncthreads();
-    }
-    if (tid == 0) {
-        rp[n] = carry;
-        nnz_out[unit] = nnz_in[unit];
-    }
-}
-
-// one wave per cached row
+// Prefill hand-off (Sec. III-C): one wave per (chunk of kChunk rows, unit) turns the prefill's mask rows,
+// keys, reference keys and values into the cache layout.
 template <typename T>
-__global__ __launch_bounds__(256) void cache_fill_kernel(const T *__restrict__ K, const T *__restrict__ V,
-                                                         const T *__restrict__ Khat,
-                                                         const uint32_t *__restrict__ mask_bits, da_cache c, int n) {
-    const int unit = blockIdx.y;
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n) return;
+__global__ __launch_bounds__(64) void cache_fill_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                        const T *__restrict__ Khat,
+                                                        const uint32_t *__restrict__ mask_bits,
+                                                        const uint64_t *__restrict__ nnz_in, da_cache c, int n) {
+    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
     const int d = c.d, wpr = d >> 5;
-    const size_t src = ((size_t)unit * n + row) * d;
-    const uint32_t *Mp = mask_bits + ((size_t)unit * n + row) * wpr;
-    uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + row) * wpr;
-    T *surv = (T *)c.surv + (size_t)unit * c.max_seq * d;
-    uint32_t off = c.roff[(size_t)unit * (c.max_seq + 1) + row];
-    for (int c0 = 0; c0 < d; c0 += kWave) {
-        const int ch = c0 + lane;
-        const bool act = ch < d;
-        bool bit = false;
-        if (act) bit = (Mp[ch >> 5] >> (ch & 31)) & 1u;
-        const uint64_t b = __ballot(bit);
-        if (act) {
-            const T k = K[src + ch];
-            if (bit) surv[off + lanes_below(b)] = k;
-            ((T *)c.V)[v_index(unit, c.vmax8, d, row, ch)] = V[src + ch];
-            if (row >= n - c.Wd) ((T *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = k;
-            if (row > 0 && row % kChunk == 0)
-                ((T *)c.ck)[((size_t)unit * c.nck + row / kChunk) * d + ch] = Khat[src - d + ch];
-            if (row == n - 1) ((T *)c.khat)[(size_t)unit * d + ch] = Khat[src + ch];
+    const int r0 = chunk * kChunk, rows = min(kChunk, n - r0);
+    const uint32_t *Mp = mask_bits + ((size_t)unit * n + r0) * wpr;
+    uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
+    // lane = row: mask copy, number of survivors of the row, start of the row inside the chunk
+    uint32_t cnt = 0;
+    if (lane < rows)
+        for (int w = 0; w < wpr; ++w) {
+            const uint32_t m = Mp[(size_t)lane * wpr + w];
+            Mc[(size_t)lane * wpr + w] = m;
+            cnt += __popc(m);
         }
-        off += __popcll(b);
+    uint32_t total;
+    const uint32_t offv = wave_exclusive_scan(cnt, &total);
+    if (lane == 0) {
+        c.ccnt[(size_t)unit * c.max_chunks + chunk] = total;
+        if (chunk == 0) c.nnz[unit] = nnz_in[unit];
     }
-    if (lane < wpr) Mc[lane] = Mp[lane];
+    // lane = channel
+    T *surv = surv_chunk<T>(c, unit, chunk);
+    const T *Kp = K + ((size_t)unit * n + r0) * d;
+    const T *Hp = Khat + ((size_t)unit * n + r0) * d;
+    const T *Vp = V + ((size_t)unit * n + r0) * d;
+    for (int r = 0; r < rows; ++r) {
+        uint32_t off = __builtin_amdgcn_readlane(offv, r);
+        const int row = r0 + r;
+        for (int c0 = 0; c0 < d; c0 += kWave) {
+            const int ch = c0 + lane;
+            const bool act = ch < d;
+            bool bit = false;
+            if (act) bit = (Mp[(size_t)r * wpr + (ch >> 5)] >> (ch & 31)) & 1u;
+            const uint64_t b = __ballot(bit);
+            if (act) {
+                const T k = Kp[(size_t)r * d + ch];
+                if (bit) surv[off + lanes_below(b)] = k;
+                if (row >= n - c.Wd) ((T *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = k;
+                if (r == 0 && chunk > 0) ((T *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = Hp[ch - d];
+                if (row == n - 1) ((T *)c.khat)[(size_t)unit * d + ch] = Hp[(size_t)r * d + ch];
+            }
+            off += __popcll(b);
+        }
+    }
+    // V: 8 rows of one channel are contiguous in the cache
+    for (int g8 = 0; g8 * 8 < rows; ++g8)
+        for (int ch = lane; ch < d; ch += kWave) {
+            T v8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] = (g8 * 8 + e < rows) ? Vp[(size_t)(g8 * 8 + e) * d + ch] : (T)0;
+            T *dst = (T *)c.V + v_index(unit, c.vrows, d, r0 + g8 * 8, ch);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e] = v8[e];
+        }
 }
 
 // ---------------------------------------------------------------------------------- decode step
-// D1: delta of the new key against the carried reference key, append to the compact cache.
+// D1: delta of the new key against the carried reference key (Eq. 2-3), appended to the compact cache.
+// Executed by one wave per unit.
 template <typename T>
-__global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *__restrict__ k_new,
-                                                           const T *__restrict__ v_new,
-                                                           uint32_t *__restrict__ mask_row, int t) {
-    const int unit = blockIdx.x, lane = threadIdx.x;
+__device__ void append_row(const da_cache &c, int unit, int lane, const T *__restrict__ k_new,
+                           const T *__restrict__ v_new, uint32_t *__restrict__ mask_row, int t) {
     const int d = c.d, wpr = d >> 5;
-    T *surv = (T *)c.surv + (size_t)unit * c.max_seq * d;
-    uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
-    const uint32_t start = (t == 0) ? 0u : rp[t];
+    const int chunk = t / kChunk;
+    T *surv = surv_chunk<T>(c, unit, chunk);
+    uint32_t *cc = c.ccnt + (size_t)unit * c.max_chunks + chunk;
+    const uint32_t start = (t % kChunk == 0) ? 0u : *cc;
     uint32_t off = start;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int ch = c0 + lane;
@@ -111,11 +143,11 @@ __global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *
                 const T hraw = *hp;
                 const float diff = load_f32(&kraw, 0) - load_f32(&hraw, 0);
                 fire = fabsf(diff) > c.theta;
-                if (t % kChunk == 0) ((T *)c.ck)[((size_t)unit * c.nck + t / kChunk) * d + ch] = hraw;
+                if (t % kChunk == 0) ((T *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = hraw;
             }
             if (fire) *hp = kraw;
             ((T *)c.ring)[((size_t)unit * c.Wd + t % c.Wd) * d + ch] = kraw;
-            ((T *)c.V)[v_index(unit, c.vmax8, d, t, ch)] = v_new[(size_t)unit * d + ch];
+            ((T *)c.V)[v_index(unit, c.vrows, d, t, ch)] = v_new[(size_t)unit * d + ch];
         }
         const uint64_t b = __ballot(fire);
         if (fire) surv[off + lanes_below(b)] = kraw;
@@ -127,24 +159,19 @@ __global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *
         off += __popcll(b);
     }
     if (lane == 0) {
-        if (t == 0) rp[0] = 0;
-        rp[t + 1] = off;
+        *cc = off;
         c.nnz[unit] = (t == 0 ? 0ull : c.nnz[unit]) + (off - start);
     }
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s);
-    return v;
+template <typename T>
+__global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *__restrict__ k_new,
+                                                           const T *__restrict__ v_new,
+                                                           uint32_t *__restrict__ mask_row, int t) {
+    append_row<T>(c, blockIdx.x, threadIdx.x, k_new, v_new, mask_row, t);
 }
 
-// D2-D4 for one chunk of kChunk cached rows of one unit, all query heads of the unit's group.
+// D2-D4, generic (fp32 caches): one wave per chunk of kChunk cached rows of one unit, vector ALU only.
 // Phase A (lanes = channels): rebuild the reference keys k_hat(j) of the chunk from the chunk's
 // checkpoint, the mask bits and the surviving values; by telescoping Eq. 4 the history score of
 // row j is q . k_hat(j).  Phase B (lanes = rows): scores (raw-key ring inside the window), chunk
@@ -164,8 +191,7 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
     const int g = c.Hq / c.Hkv;
     const int b = unit / c.Hkv, hk = unit % c.Hkv;
     const int win_begin = t + 1 - c.Wd;   // rows >= win_begin use raw keys (may be negative)
-    const T *surv = (const T *)c.surv + (size_t)unit * c.max_seq * d;
-    const uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
+    const T *surv = surv_chunk<T>(c, unit, chunk);
     const uint32_t *Mp = c.mask + (size_t)unit * c.max_seq * wpr;
 
     if (r0 < win_begin) {   // some row of the chunk is history
@@ -176,8 +202,8 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
                 if (w * kWave + lane < d) held[w] = load_f32(ckp, w * kWave + lane);
         }
         const int hist_end = min(r1, win_begin);
+        uint32_t off = 0;
         for (int row = r0; row < hist_end; ++row) {
-            uint32_t off = rp[row];
             for (int w = 0; w * kWave < d; ++w) {
                 const int ch = w * kWave + lane;
                 bool bit = false;
@@ -220,7 +246,7 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
             if (ch < d) {
                 float acc = 0.f;
                 for (int r = 0; r < r1 - r0; ++r)
-                    acc = fmaf(pb[r], load_f32(Vp, v_index(unit, c.vmax8, d, r0 + r, ch)), acc);
+                    acc = fmaf(pb[r], load_f32(Vp, v_index(unit, c.vrows, d, r0 + r, ch)), acc);
                 out[ch] = acc;
             }
         }
@@ -231,35 +257,87 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
     }
 }
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+// Merge of the per-chunk partials (o, m, l) of one (batch, query head): lanes = chunks for the weights,
+// lanes = channels for the output.
+template <typename T>
+__device__ void combine_head(const da_cache &c, int bh, int lane, T *__restrict__ o, int nchunks) {
+    const int d = c.d;
+    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
+    auto ld = [&](const float *p) -> float { return *p; };
+    float M = -INFINITY;
+    for (int k = lane; k < nchunks; k += kWave) M = fmaxf(M, ld(part + (size_t)k * (d + 2) + d));
+    M = wave_max(M);
+    float L = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < nchunks; k0 += kWave) {
+        const int k = k0 + lane;
+        const float wk = k < nchunks ? exp2f(ld(part + (size_t)k * (d + 2) + d) - M) : 0.f;
+        L += k < nchunks ? wk * ld(part + (size_t)k * (d + 2) + d + 1) : 0.f;
+        const int cnt = min(kWave, nchunks - k0);
+        for (int kb = 0; kb < cnt; kb += 8) {
+            float w[8], x[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int kk = min(kb + u, cnt - 1);
+                w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
+                if (kb + u >= cnt) w[u] = 0.f;
+                const float *row = part + (size_t)(k0 + kk) * (d + 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[u][i] = (i * kWave + lane < d) ? ld(row + i * kWave + lane) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(w[u], x[u][i], acc[i]);
+        }
+    }
+    L = wave_sum(L);
+    const float inv = 1.f / L;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (i * kWave + lane < d) store_from_f32(o + (size_t)bh * d, i * kWave + lane, acc[i] * inv);
+}
 
-// D2-D4 for bf16 caches: one wave per chunk of kChunk cached rows of one unit, all query heads of the
-// unit's group.
-//   1. the chunk's surviving key values (one contiguous run of the compact cache) are copied to LDS;
+template <typename T>
+__global__ __launch_bounds__(64) void decode_combine_kernel(da_cache c, T *__restrict__ o, int nchunks) {
+    combine_head<T>(c, blockIdx.x, threadIdx.x, o, nchunks);
+}
+
+// The decode step for bf16 caches: one wave per chunk of kChunk cached rows of one
+// unit, all query heads of the unit's group.
+//   0. the wave that owns the newest row appends it (D1);
+//   1. mask rows (lane = row) give the survivor count of every row, hence each row's start inside the
+//      chunk's survivor run (a wave prefix sum) - no offset table is read; the run itself is copied to
+//      LDS, its first 4 KiB requested before the masks have arrived;
 //   2. lanes = channels walk the chunk's history rows in order: the mask word of a row, broadcast
 //      from the lane that holds it, selects which lanes take their next surviving value, the rest
 //      keep the held one (Eq. 3); each reference row k_hat(j) goes to an LDS tile (Eq. 4 telescoped:
 //      the history score of row j is q . k_hat(j)); rows inside the decode window are copied from
-//      the raw-key ring instead;
+//      the raw-key ring instead, the newest one from the call's k_new;
 //   3. scores of 64 rows x up to 16 heads on the matrix cores (16x16x32: A lane l = tile row l % 16,
 //      k = 8 (l / 16)..+7; B lane l = column l % 16, same k; D lane l = column l % 16, rows
-//      4 (l / 16) + r);
-//   4. per-head chunk softmax with lanes = rows; P V on the matrix cores against the 8-row
-//      interleaved V cache, partial (o, m, l) to the per-chunk scratch.
+//      4 (l / 16) + r); chunk softmax in that register layout;
+//   4. P V on the matrix cores against the 8-row interleaved V cache; partial (o, m, l) to scratch.
+// The partials are merged by a second launch: on this chip every XCD has its own L2, so handing them
+// to a "last wave" inside the same launch needs device-scope fences that write the L2 back, which
+// measured six times slower than the extra launch.
 template <int DT>   // head_dim known at compile time (64, 128), or 0 for any multiple of 32
-__global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const bf16_t *__restrict__ q_new, int t,
-                                                               float scale_log2) {
+__global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const bf16_t *__restrict__ q_new,
+                                                              const bf16_t *__restrict__ k_new,
+                                                              const bf16_t *__restrict__ v_new,
+                                                              uint32_t *__restrict__ mask_row, int t,
+                                                              float scale_log2) {
     extern __shared__ float lds_f[];
     char *lds = (char *)lds_f;
     const int d = DT ? DT : c.d, wpr = d >> 5;
     const int nw = (d + kWave - 1) / kWave;
     const int ldk = d + 8;
     bf16_t *ktile = (bf16_t *)lds;                           // [kChunk][d + 8]
-    bf16_t *sv = ktile + kChunk * ldk;                       // staged surviving values, <= kChunk * d + 8
+    bf16_t *sv = ktile + kChunk * ldk;                       // staged surviving values, <= kChunk * d
     bf16_t *pt = sv + kChunk * d + 16;                       // [16][kChunk + 8] probabilities, heads x rows
     const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
+    const int nchunks = t / kChunk + 1;
+    const bool newest = chunk == nchunks - 1;                // this wave owns row t
     const int r0 = chunk * kChunk;
     const int r1 = min(r0 + kChunk, t + 1);
     const int nrows = r1 - r0;
@@ -267,19 +345,17 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
     const int b = unit / c.Hkv, hk = unit % c.Hkv;
     const int win_begin = t + 1 - c.Wd;                      // rows >= win_begin use raw keys
     const int hist_rows = min(max(win_begin - r0, 0), nrows);
-    const bf16_t *surv = (const bf16_t *)c.surv + (size_t)unit * c.max_seq * d;
-    const uint32_t *rp = c.roff + (size_t)unit * (c.max_seq + 1);
+    const bf16_t *surv = surv_chunk<bf16_t>(c, unit, chunk);
     const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
     const int l16 = lane & 15, lg = lane >> 4;
     const int ks_n = d >> 5, ct_n = d >> 4;
+    const int pieces = (kChunk * d) >> 9;                    // 16-byte-per-lane copies that cover the chunk's room
 
-    // everything whose address does not depend on loaded data is requested up front
-    uint32_t roffv = 0, s_end = 0;
+    // ---- everything whose address does not depend on loaded data is requested up front
     uint32_t mk[8];
     uint32_t held[4] = {0u, 0u, 0u, 0u};
+    u32x4 sp[4];                                             // first 4 KiB of the survivor run
     if (hist_rows > 0) {
-        roffv = rp[r0 + min(lane, hist_rows)];
-        s_end = rp[r0 + hist_rows];
 #pragma unroll
         for (int w2 = 0; w2 < 8; ++w2) mk[w2] = (w2 < wpr && lane < hist_rows) ? Mp[(size_t)lane * wpr + w2] : 0u;
         if (r0 > 0) {
@@ -288,8 +364,12 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
             for (int w = 0; w < 4; ++w)
                 if (w < nw && w * kWave + lane < d) held[w] = ckp[w * kWave + lane];
         }
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (p < pieces) sp[p] = *(const u32x4 *)(surv + p * 512 + lane * 8);
     }
-    // raw keys of the window rows (16 bytes per lane per copy) straight into the tile; zero past the newest key
+    // raw keys of the window rows (16 bytes per lane per copy) straight into the tile; the newest row comes
+    // from the call's argument, rows past it are zero
     {
         const int segs = d >> 3;
         const int first = hist_rows * segs, last = kChunk * segs;
@@ -301,7 +381,12 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
                 const int i = i0 + u * kWave;
                 const int r = min(i, last - 1) / segs, seg = min(i, last - 1) % segs;
                 v[u] = u32x4{0u, 0u, 0u, 0u};
-                if (i < last && r < nrows) v[u] = *(const u32x4 *)(ringu + (size_t)((r0 + r) % c.Wd) * d + seg * 8);
+                if (i < last && r < nrows) {
+                    if (r0 + r == t)
+                        v[u] = *(const u32x4 *)(k_new + (size_t)unit * d + seg * 8);
+                    else
+                        v[u] = *(const u32x4 *)(ringu + (size_t)((r0 + r) % c.Wd) * d + seg * 8);
+                }
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -311,22 +396,37 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
         }
     }
     for (int i = lane; i < 16 * (kChunk + 8); i += kWave) pt[i] = 0;
-    // V operands of the whole chunk (needed last, requested first)
+    // V operands of the whole chunk (needed last, requested first); the newest row is patched in from v_new
     constexpr int kVregs = DT ? 2 * (DT / 16) : 1;
     u32x4 vop[kVregs];
     if (DT) {
 #pragma unroll
-        for (int i = 0; i < kVregs; ++i)
-            vop[i] = *(const u32x4 *)((const bf16_t *)c.V +
-                                      v_index(unit, c.vmax8, d, r0 + 32 * (i & 1) + 8 * lg, 16 * (i >> 1) + l16));
+        for (int i = 0; i < kVregs; ++i) {
+            const int row8 = r0 + 32 * (i & 1) + 8 * lg, ch = 16 * (i >> 1) + l16;
+            vop[i] = *(const u32x4 *)((const bf16_t *)c.V + v_index(unit, c.vrows, d, row8, ch));
+            if (newest && (t & ~7) == row8) {
+                const uint32_t vn = v_new[(size_t)unit * d + ch];
+                const int e = t & 7;
+                const uint32_t old = vop[i][e >> 1];
+                vop[i][e >> 1] = (e & 1) ? ((old & 0xffffu) | (vn << 16)) : ((old & 0xffff0000u) | vn);
+            }
+        }
     }
+    // 0. the new row goes into the cache (other waves of this launch never read what is written here)
+    if (newest) append_row<bf16_t>(c, unit, lane, k_new, v_new, mask_row, t);
 
     if (hist_rows > 0) {
-        // 1. stage the chunk's survivors: rows r0 .. r0 + hist_rows - 1 occupy [rp[r0], rp[r0 + hist_rows])
-        const uint32_t s_begin = __builtin_amdgcn_readfirstlane(roffv);
-        const uint32_t base = s_begin & ~7u;
-        for (uint32_t i = base + lane * 8; i < s_end; i += kWave * 8)
-            *(u32x4 *)(sv + (i - base)) = *(const u32x4 *)(surv + i);
+        // 1. row starts inside the chunk's survivor run, from the mask rows
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < 8; ++w2) cnt += __popc(mk[w2]);
+        uint32_t need;
+        const uint32_t roffv = wave_exclusive_scan(cnt, &need);
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (p < pieces) *(u32x4 *)(sv + p * 512 + lane * 8) = sp[p];
+        for (int p = 4; p < pieces && (uint32_t)p * 512u < need; ++p)
+            *(u32x4 *)(sv + p * 512 + lane * 8) = *(const u32x4 *)(surv + p * 512 + lane * 8);
         __syncthreads();
         // 2. reference keys of the history rows, 8 rows per batch so that the LDS reads of a batch are
         //    in flight together (their addresses depend on the masks only, not on the held values)
@@ -336,7 +436,7 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int r = min(rb + u, hist_rows - 1);
-                uint32_t off = __builtin_amdgcn_readlane(roffv, r) - base;
+                uint32_t off = __builtin_amdgcn_readlane(roffv, r);
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     if (w < nw) {
@@ -382,7 +482,7 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
                                                                   __builtin_bit_cast(bf16x8, bv), acc[rt], 0, 0, 0);
             }
         }
-        // 4. chunk softmax per head: 16 values in registers, then the 4 lane groups that share the head
+        // chunk softmax per head: 16 values in registers, then the 4 lane groups that share the head
         float m = -INFINITY;
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
@@ -416,7 +516,7 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
             out[d + 1] = l;
         }
         __syncthreads();
-        // P V: heads x channels, contraction over the chunk's 64 rows
+        // 4. P V: heads x channels, contraction over the chunk's 64 rows
         u32x4 pa[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) pa[ks] = *(const u32x4 *)(pt + l16 * (kChunk + 8) + 32 * ks + 8 * lg);
@@ -427,11 +527,18 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 u32x4 bv;
-                if (DT)
+                if (DT) {
                     bv = vop[2 * ct + ks];
-                else
-                    bv = *(const u32x4 *)((const bf16_t *)c.V +
-                                          v_index(unit, c.vmax8, d, r0 + 32 * ks + 8 * lg, 16 * ct + l16));
+                } else {
+                    const int row8 = r0 + 32 * ks + 8 * lg, ch = 16 * ct + l16;
+                    bv = *(const u32x4 *)((const bf16_t *)c.V + v_index(unit, c.vrows, d, row8, ch));
+                    if (newest && (t & ~7) == row8) {
+                        const uint32_t vn = v_new[(size_t)unit * d + ch];
+                        const int e = t & 7;
+                        const uint32_t old = bv[e >> 1];
+                        bv[e >> 1] = (e & 1) ? ((old & 0xffffu) | (vn << 16)) : ((old & 0xffff0000u) | vn);
+                    }
+                }
                 o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa[ks]),
                                                             __builtin_bit_cast(bf16x8, bv), o, 0, 0, 0);
             }
@@ -445,66 +552,7 @@ __global__ __launch_bounds__(64) void decode_chunk_bf16_kernel(da_cache c, const
         }
         __syncthreads();
     }
-}
 
-// Merge of the per-chunk partials of one (batch, query head): lanes = chunks for the weights,
-// lanes = channels for the output.
-template <typename T>
-__global__ __launch_bounds__(64) void decode_combine2_kernel(da_cache c, T *__restrict__ o, int nchunks) {
-    const int bh = blockIdx.x, lane = threadIdx.x;
-    const int d = c.d;
-    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
-    float M = -INFINITY;
-    for (int k = lane; k < nchunks; k += kWave) M = fmaxf(M, part[(size_t)k * (d + 2) + d]);
-    M = wave_max(M);
-    float L = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < nchunks; k0 += kWave) {
-        const int k = k0 + lane;
-        const float wk = k < nchunks ? exp2f(part[(size_t)k * (d + 2) + d] - M) : 0.f;
-        L += k < nchunks ? wk * part[(size_t)k * (d + 2) + d + 1] : 0.f;
-        const int cnt = min(kWave, nchunks - k0);
-        for (int kb = 0; kb < cnt; kb += 8) {
-            float w[8], x[8][4];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int kk = min(kb + u, cnt - 1);
-                w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
-                if (kb + u >= cnt) w[u] = 0.f;
-                const float *row = part + (size_t)(k0 + kk) * (d + 2);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) x[u][i] = (i * kWave + lane < d) ? row[i * kWave + lane] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[i] = fmaf(w[u], x[u][i], acc[i]);
-        }
-    }
-    L = wave_sum(L);
-    const float inv = 1.f / L;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (i * kWave + lane < d) store_from_f32(o + (size_t)bh * d, i * kWave + lane, acc[i] * inv);
-}
-
-template <typename T>
-__global__ __launch_bounds__(64) void decode_combine_kernel(da_cache c, T *__restrict__ o, int nchunks) {
-    const int bh = blockIdx.x, lane = threadIdx.x;
-    const int d = c.d;
-    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
-    float M = -INFINITY;
-    for (int k = 0; k < nchunks; ++k) M = fmaxf(M, part[(size_t)k * (d + 2) + d]);
-    float L = 0.f;
-    for (int k = 0; k < nchunks; ++k)
-        L += part[(size_t)k * (d + 2) + d + 1] * exp2f(part[(size_t)k * (d + 2) + d] - M);
-    const float inv = 1.f / L;
-    for (int ch = lane; ch < d; ch += kWave) {
-        float acc = 0.f;
-        for (int k = 0; k < nchunks; ++k)
-            acc = fmaf(part[(size_t)k * (d + 2) + ch], exp2f(part[(size_t)k * (d + 2) + d] - M), acc);
-        store_from_f32(o + (size_t)bh * d, ch, acc * inv);
-    }
 }
 
 template <typename T>
@@ -513,31 +561,40 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const int t = (int)c->len;
     const int units = c->B * c->Hkv;
     const float sc = (c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d)) * 1.4426950408889634f;
+    const int nchunks = t / kChunk + 1;
+    if (c->dtype == DA_BF16) {
+        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
+        static bool attr_done = false;   // d = 256 needs more than 64 KiB
+        if (!attr_done) {
+            (void)hipFuncSetAttribute((const void *)decode_step_bf16_kernel<0>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 +
+                                            16 * (kChunk + 8) * 2));
+            attr_done = true;
+        }
+        stage_begin(kStageChunk, s);
+        const dim3 grid(nchunks, units), block(64);
+        if (c->d == 64)
+            hipLaunchKernelGGL(decode_step_bf16_kernel<64>, grid, block, lds, s, *c, (const bf16_t *)q,
+                               (const bf16_t *)k, (const bf16_t *)v, mask_row, t, sc);
+        else if (c->d == 128)
+            hipLaunchKernelGGL(decode_step_bf16_kernel<128>, grid, block, lds, s, *c, (const bf16_t *)q,
+                               (const bf16_t *)k, (const bf16_t *)v, mask_row, t, sc);
+        else
+            hipLaunchKernelGGL(decode_step_bf16_kernel<0>, grid, block, lds, s, *c, (const bf16_t *)q,
+                               (const bf16_t *)k, (const bf16_t *)v, mask_row, t, sc);
+        stage_end(kStageChunk, s);
+        stage_begin(kStageCombine, s);
+        hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+        stage_end(kStageCombine, s);
+        return;
+    }
     stage_begin(kStageAppend, s);
     hipLaunchKernelGGL(decode_append_kernel<T>, dim3(units), dim3(64), 0, s, *c, (const T *)k, (const T *)v,
                        mask_row, t);
     stage_end(kStageAppend, s);
-    const int nchunks = t / kChunk + 1;
     stage_begin(kStageChunk, s);
-    if (c->dtype == DA_BF16) {
-        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
-        static bool attr16_done = false;   // d = 256 needs more than 64 KiB
-        if (!attr16_done) {
-            (void)hipFuncSetAttribute((const void *)decode_chunk_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 +
-                                            16 * (kChunk + 8) * 2));
-            attr16_done = true;
-        }
-        if (c->d == 64)
-            hipLaunchKernelGGL(decode_chunk_bf16_kernel<64>, dim3(nchunks, units), dim3(64), lds, s, *c,
-                               (const bf16_t *)q, t, sc);
-        else if (c->d == 128)
-            hipLaunchKernelGGL(decode_chunk_bf16_kernel<128>, dim3(nchunks, units), dim3(64), lds, s, *c,
-                               (const bf16_t *)q, t, sc);
-        else
-            hipLaunchKernelGGL(decode_chunk_bf16_kernel<0>, dim3(nchunks, units), dim3(64), lds, s, *c,
-                               (const bf16_t *)q, t, sc);
-    } else {
+    {
         const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
         static bool attr_done = false;   // d = 256 needs slightly more than 64 KiB
         if (!attr_done) {
@@ -549,12 +606,12 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     }
     stage_end(kStageChunk, s);
     stage_begin(kStageCombine, s);
-    hipLaunchKernelGGL(decode_combine2_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+    hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
     stage_end(kStageCombine, s);
 }
 
 void free_all(da_cache *c) {
-    void *ptrs[] = {c->mask, c->surv, c->roff, c->ck, c->khat, c->ring, c->V, c->nnz, c->part};
+    void *ptrs[] = {c->mask, c->surv, c->ccnt, c->ck, c->khat, c->ring, c->V, c->nnz, c->part};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -574,16 +631,15 @@ da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p)
 void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void *K, const void *V,
                              const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,
                              const uint64_t *nnz, hipStream_t s) {
+    (void)counts;
     const int units = c->B * c->Hkv, n = p->seq_len;
-    hipLaunchKernelGGL(row_offsets_kernel, dim3(units), dim3(256), 0, s, counts, c->roff, nnz, c->nnz, n,
-                       c->max_seq);
-    dim3 grid((n + 3) / 4, units), block(256);
+    dim3 grid((n + kChunk - 1) / kChunk, units), block(64);
     if (c->dtype == DA_F32)
         hipLaunchKernelGGL(cache_fill_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)V,
-                           (const float *)Khat, mask_bits, *c, n);
+                           (const float *)Khat, mask_bits, nnz, *c, n);
     else
         hipLaunchKernelGGL(cache_fill_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K, (const bf16_t *)V,
-                           (const bf16_t *)Khat, mask_bits, *c, n);
+                           (const bf16_t *)Khat, mask_bits, nnz, *c, n);
     c->len = n;
 }
 
@@ -618,7 +674,7 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     c->len = 0;
     c->nck = max_seq / kChunk + 1;
     c->max_chunks = (max_seq + kChunk - 1) / kChunk;
-    c->vmax8 = (max_seq + kChunk - 1) / kChunk * kChunk;
+    c->vrows = (max_seq + kChunk - 1) / kChunk * kChunk;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;
         return DA_ERR_HIP;
@@ -626,13 +682,13 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     const size_t units = (size_t)batch * n_kv_heads, es = elt_size(dtype), d = head_dim;
     bool ok = true;
     ok = ok && hipMalloc((void **)&c->mask, units * max_seq * (d / 32) * 4) == hipSuccess;
-    ok = ok && hipMalloc(&c->surv, units * max_seq * d * es) == hipSuccess;
-    ok = ok && hipMalloc((void **)&c->roff, units * ((size_t)max_seq + 1) * 4) == hipSuccess;
+    ok = ok && hipMalloc(&c->surv, units * (size_t)c->max_chunks * kChunk * d * es) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->ccnt, units * (size_t)c->max_chunks * 4) == hipSuccess;
     ok = ok && hipMalloc(&c->ck, units * c->nck * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->khat, units * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->ring, units * c->Wd * d * es) == hipSuccess;
-    ok = ok && hipMalloc(&c->V, units * (size_t)c->vmax8 * d * es) == hipSuccess;
-    if (ok) ok = hipMemset(c->V, 0, units * (size_t)c->vmax8 * d * es) == hipSuccess;   // rows never written must be finite
+    ok = ok && hipMalloc(&c->V, units * (size_t)c->vrows * d * es) == hipSuccess;
+    if (ok) ok = hipMemset(c->V, 0, units * (size_t)c->vrows * d * es) == hipSuccess;   // rows never written must be finite
     ok = ok && hipMalloc((void **)&c->nnz, units * 8) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->part, (size_t)batch * n_q_heads * c->max_chunks * (d + 2) * 4) == hipSuccess;
     if (ok) ok = hipMemset(c->nnz, 0, units * 8) == hipSuccess;
