@@ -332,9 +332,10 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
     const int d = DT ? DT : c.d, wpr = d >> 5;
     const int nw = (d + kWave - 1) / kWave;
     const int ldk = d + 8;
-    bf16_t *ktile = (bf16_t *)lds;                           // [kChunk][d + 8]
-    bf16_t *sv = ktile + kChunk * ldk;                       // staged surviving values, <= kChunk * d
-    bf16_t *pt = sv + kChunk * d + 16;                       // [16][kChunk + 8] probabilities, heads x rows
+    constexpr int kSlab = 16;                                // rows rebuilt and scored at a time
+    bf16_t *__restrict__ ktile = (bf16_t *)lds;              // [kSlab][d + 8]
+    bf16_t *__restrict__ sv = ktile + kSlab * ldk;           // staged surviving values, <= kChunk * d
+    bf16_t *__restrict__ pt = sv + kChunk * d + 16;          // [16][kChunk + 8] probabilities, heads x rows
     const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
     const int nchunks = t / kChunk + 1;
     const bool newest = chunk == nchunks - 1;                // this wave owns row t
@@ -368,33 +369,6 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
         for (int p = 0; p < 4; ++p)
             if (p < pieces) sp[p] = *(const u32x4 *)(surv + p * 512 + lane * 8);
     }
-    // raw keys of the window rows (16 bytes per lane per copy) straight into the tile; the newest row comes
-    // from the call's argument, rows past it are zero
-    {
-        const int segs = d >> 3;
-        const int first = hist_rows * segs, last = kChunk * segs;
-        const bf16_t *ringu = (const bf16_t *)c.ring + (size_t)unit * c.Wd * d;
-        for (int i0 = first + lane; i0 < last; i0 += 4 * kWave) {
-            u32x4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * kWave;
-                const int r = min(i, last - 1) / segs, seg = min(i, last - 1) % segs;
-                v[u] = u32x4{0u, 0u, 0u, 0u};
-                if (i < last && r < nrows) {
-                    if (r0 + r == t)
-                        v[u] = *(const u32x4 *)(k_new + (size_t)unit * d + seg * 8);
-                    else
-                        v[u] = *(const u32x4 *)(ringu + (size_t)((r0 + r) % c.Wd) * d + seg * 8);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * kWave;
-                if (i < last) *(u32x4 *)(ktile + (i / segs) * ldk + (i % segs) * 8) = v[u];
-            }
-        }
-    }
     for (int i = lane; i < 16 * (kChunk + 8); i += kWave) pt[i] = 0;
     // V operands of the whole chunk (needed last, requested first); the newest row is patched in from v_new
     constexpr int kVregs = DT ? 2 * (DT / 16) : 1;
@@ -412,74 +386,120 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
             }
         }
     }
+    // q operand of the first 16 heads (B operand of the score MFMA), also requested early
+    constexpr int kQregs = DT ? DT / 32 : 1;
+    u32x4 qop[kQregs];
+    if (DT) {
+        const int gh0 = min(16, g);
+        const bf16_t *qrow0 = q_new + ((size_t)b * c.Hq + hk * g + min(l16, gh0 - 1)) * d;
+#pragma unroll
+        for (int ks = 0; ks < kQregs; ++ks) {
+            qop[ks] = *(const u32x4 *)(qrow0 + 32 * ks + 8 * lg);
+            if (l16 >= gh0) qop[ks] = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
     // 0. the new row goes into the cache (other waves of this launch never read what is written here)
     if (newest) append_row<bf16_t>(c, unit, lane, k_new, v_new, mask_row, t);
 
+    uint32_t roffv = 0;
     if (hist_rows > 0) {
         // 1. row starts inside the chunk's survivor run, from the mask rows
         uint32_t cnt = 0;
 #pragma unroll
         for (int w2 = 0; w2 < 8; ++w2) cnt += __popc(mk[w2]);
         uint32_t need;
-        const uint32_t roffv = wave_exclusive_scan(cnt, &need);
+        roffv = wave_exclusive_scan(cnt, &need);
 #pragma unroll
         for (int p = 0; p < 4; ++p)
             if (p < pieces) *(u32x4 *)(sv + p * 512 + lane * 8) = sp[p];
         for (int p = 4; p < pieces && (uint32_t)p * 512u < need; ++p)
             *(u32x4 *)(sv + p * 512 + lane * 8) = *(const u32x4 *)(surv + p * 512 + lane * 8);
-        __syncthreads();
-        // 2. reference keys of the history rows, 8 rows per batch so that the LDS reads of a batch are
-        //    in flight together (their addresses depend on the masks only, not on the held values)
-        for (int rb = 0; rb < hist_rows; rb += 8) {
-            uint32_t val[8][4];
-            bool bit[8][4];
+    }
+
+    const int segs = d >> 3;
+    const bf16_t *ringu = (const bf16_t *)c.ring + (size_t)unit * c.Wd * d;
+    for (int hbase = 0; hbase < g; hbase += 16) {
+        const int gh = min(16, g - hbase);
+        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + hbase + min(l16, gh - 1)) * d;
+        f32x4 acc[4];
+        uint32_t hcur[4] = {held[0], held[1], held[2], held[3]};
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int r = min(rb + u, hist_rows - 1);
-                uint32_t off = __builtin_amdgcn_readlane(roffv, r);
+        for (int slab = 0; slab < kChunk / kSlab; ++slab) {
+            const int s0 = slab * kSlab;
+            __syncthreads();                                 // survivors staged / previous slab's tile consumed
+            // 2. reference keys of the slab's history rows, 8 rows per batch so that the LDS reads of a batch
+            //    are in flight together (their addresses depend on the masks only, not on the held values)
+            const int hist_here = min(max(hist_rows - s0, 0), kSlab);
+            uint32_t off = hist_here > 0 ? __builtin_amdgcn_readlane(roffv, s0) : 0u;   // uniform, advanced per row
+            for (int rb = 0; rb < hist_here; rb += 8) {
+                uint32_t val[8][4];
+                uint64_t msk[8][4];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if (w < nw) {
-                        const uint32_t lo = __builtin_amdgcn_readlane(mk[2 * w], r);
-                        const uint32_t hi = __builtin_amdgcn_readlane(mk[2 * w + 1], r);
-                        const uint64_t m64 = (uint64_t)lo | ((uint64_t)hi << 32);
-                        bit[u][w] = (m64 >> lane) & 1ull;
-                        val[u][w] = sv[off + lanes_below(m64)];
-                        off += __popcll(m64);
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (rb + u < hist_rows) {
+                for (int u = 0; u < 8; ++u) {
+                    const int r = s0 + min(rb + u, hist_here - 1);
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
                         if (w < nw) {
-                            held[w] = bit[u][w] ? val[u][w] : held[w];
-                            if (w * kWave + lane < d) ktile[(rb + u) * ldk + w * kWave + lane] = (bf16_t)held[w];
+                            const uint32_t lo = __builtin_amdgcn_readlane(mk[2 * w], r);
+                            const uint32_t hi = __builtin_amdgcn_readlane(mk[2 * w + 1], r);
+                            const uint64_t m64 = (rb + u < hist_here) ? ((uint64_t)lo | ((uint64_t)hi << 32)) : 0ull;
+                            msk[u][w] = m64;
+                            val[u][w] = sv[off + lanes_below(m64)];
+                            off += __popcll(m64);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (rb + u < hist_here) {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            if (w < nw) {
+                                hcur[w] = __builtin_amdgcn_inverse_ballot_w64(msk[u][w]) ? val[u][w] : hcur[w];
+                                if (w * kWave + lane < d) ktile[(rb + u) * ldk + w * kWave + lane] = (bf16_t)hcur[w];
+                            }
                         }
                     }
                 }
             }
-        }
-    }
-    __syncthreads();
-
-    for (int hbase = 0; hbase < g; hbase += 16) {
-        const int gh = min(16, g - hbase);
-        // 3. scores: lane l ends up with head l % 16 at rows 16 rt + 4 (l / 16) + r
-        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + hbase + min(l16, gh - 1)) * d;
-        f32x4 acc[4];
+            // window rows of the slab: raw keys from the ring (the newest one from the call's argument),
+            // zero past the newest key
+            for (int i0 = hist_here * segs + lane; i0 < kSlab * segs; i0 += 2 * kWave) {
+                u32x4 v[2];
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int ks = 0; ks < ks_n; ++ks) {
-            u32x4 bv = *(const u32x4 *)(qrow + 32 * ks + 8 * lg);
-            if (l16 >= gh) bv = u32x4{0u, 0u, 0u, 0u};
+                for (int u = 0; u < 2; ++u) {
+                    const int i = min(i0 + u * kWave, kSlab * segs - 1);
+                    const int r = s0 + i / segs, seg = i % segs;
+                    v[u] = u32x4{0u, 0u, 0u, 0u};
+                    if (r < nrows) {
+                        if (r0 + r == t)
+                            v[u] = *(const u32x4 *)(k_new + (size_t)unit * d + seg * 8);
+                        else
+                            v[u] = *(const u32x4 *)(ringu + (size_t)((r0 + r) % c.Wd) * d + seg * 8);
+                    }
+                }
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt) {
-                const u32x4 av = *(const u32x4 *)(ktile + (16 * rt + l16) * ldk + 32 * ks + 8 * lg);
-                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
-                                                                  __builtin_bit_cast(bf16x8, bv), acc[rt], 0, 0, 0);
+                for (int u = 0; u < 2; ++u) {
+                    const int i = i0 + u * kWave;
+                    if (i < kSlab * segs) *(u32x4 *)(ktile + (i / segs) * ldk + (i % segs) * 8) = v[u];
+                }
+            }
+            __syncthreads();
+            // 3. scores of the slab: lane l ends up with head l % 16 at rows s0 + 4 (l / 16) + r
+            acc[slab] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < (DT ? DT / 32 : 8); ++ks) {
+                if (!DT && ks >= ks_n) break;
+                u32x4 bv;
+                if (DT && hbase == 0) {
+                    bv = qop[ks];
+                } else {
+                    bv = *(const u32x4 *)(qrow + 32 * ks + 8 * lg);
+                    if (l16 >= gh) bv = u32x4{0u, 0u, 0u, 0u};
+                }
+                const u32x4 av = *(const u32x4 *)(ktile + l16 * ldk + 32 * ks + 8 * lg);
+                acc[slab] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                    __builtin_bit_cast(bf16x8, bv), acc[slab], 0, 0, 0);
             }
         }
         // chunk softmax per head: 16 values in registers, then the 4 lane groups that share the head
@@ -503,9 +523,11 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
                 p[r] = exp2f(acc[rt][r] - m);
                 l += p[r];
             }
+            typedef __attribute__((ext_vector_type(2))) float f32x2;
+            typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
             uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16(p[0]) | ((uint32_t)f32_to_bf16(p[1]) << 16);
-            pk.y = (uint32_t)f32_to_bf16(p[2]) | ((uint32_t)f32_to_bf16(p[3]) << 16);
+            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p[0], p[1]}, bf16x2));
+            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p[2], p[3]}, bf16x2));
             *(uint2 *)(pt + l16 * (kChunk + 8) + 16 * rt + 4 * lg) = pk;
         }
         l += __shfl_xor(l, 16);
@@ -563,13 +585,12 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const float sc = (c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d)) * 1.4426950408889634f;
     const int nchunks = t / kChunk + 1;
     if (c->dtype == DA_BF16) {
-        const size_t lds = ((size_t)kChunk * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
+        const size_t lds = ((size_t)16 * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
         static bool attr_done = false;   // d = 256 needs more than 64 KiB
         if (!attr_done) {
             (void)hipFuncSetAttribute((const void *)decode_step_bf16_kernel<0>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)(((size_t)kChunk * 264 + (size_t)kChunk * 256 + 16) * 2 +
-                                            16 * (kChunk + 8) * 2));
+                                      (int)(((size_t)16 * 264 + (size_t)kChunk * 256 + 16) * 2 + 16 * (kChunk + 8) * 2));
             attr_done = true;
         }
         stage_begin(kStageChunk, s);
