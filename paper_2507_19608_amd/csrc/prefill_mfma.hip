@@ -170,14 +170,15 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         for (int k = 0; k < 2 * MT; ++k) vreg[k] = vp[k * 64];
     };
 
-    // Online softmax + PV for one block; s[16] are this lane's scaled scores (-inf where masked).
-    // The running maximum is only raised when the block maximum exceeds it by more than 2^8 in the
-    // exponent, so probabilities stay <= 256 and the accumulator is rarely rescaled.
-    auto softmax_pv = [&](float (&s)[16], const u32x4 (&vreg)[2 * MT]) {
+    // Online softmax + PV for one block; s[16] are this lane's raw scores (-inf where masked), sc the
+    // positive factor that turns them into log2 units.  The running maximum is only raised when the
+    // block maximum exceeds it by more than 2^8 in the exponent, so probabilities stay <= 256 and the
+    // accumulator is rarely rescaled.
+    auto softmax_pv = [&](float (&s)[16], float sc, const u32x4 (&vreg)[2 * MT]) {
         float bm = s[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) bm = fmaxf(bm, s[r]);
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        bm = fmaxf(bm, __shfl_xor(bm, 32)) * sc;
         if (__any(bm > m_run + 8.f)) {
             const float m_new = fmaxf(m_run, bm);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -189,12 +190,12 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
         }
-        const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
         float psum = 0.f;
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            p[r] = exp2f(s[r] - m_use);
+            p[r] = exp2f(fmaf(s[r], sc, neg_m));
             psum += p[r];
         }
         l_run += psum;
@@ -354,11 +355,11 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             for (int q = 0; q < 4; ++q) {
                 const float mine = half ? base + t_oth[q] : base;
 #pragma unroll
-                for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = (mine + w[4 * q + bb]) * far_scale;
+                for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = mine + w[4 * q + bb];
                 base += t_own[q] + t_oth[q];
             }
             r_run = base;
-            softmax_pv(s, vreg);
+            softmax_pv(s, far_scale, vreg);
         }
     }
 
@@ -366,14 +367,14 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // Exact scores K Q^T (and K_hat Q^T where needed) on the matrix cores.  The K / K_hat / V tiles of a
     // block are fetched once per work group, one 16-byte piece per thread, a block ahead into registers,
     // then parked in LDS in operand order (lane-contiguous 16-byte slots, conflict free) where all 8 waves
-    // read them.  Two LDS buffers alternate; one barrier per block.
+    // read them.  Three LDS buffers rotate (tiles are requested two blocks ahead); one barrier per block.
     if (far_blocks < nblocks) {
         u32x4 qreg[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
         constexpr int kTileBytes = D * 64;                       // 32 keys x D channels, bf16
         constexpr int kPieces = kTileBytes / 16;                 // 16-byte pieces per tile (256 or 512)
-        char *tiles = lds_raw + (size_t)D * kRows * 2;           // [2 buffers][K, K_hat, V]
+        char *tiles = lds_raw + (size_t)D * kRows * 2;           // [3 buffers][K, K_hat, V]
         const bool has_piece = tid < kPieces;
         const int pr = tid / (D / 8), pseg = tid % (D / 8);      // K piece: key row, 8-channel segment
         const int kslot = ((pseg >> 1) * 64 + (pseg & 1) * 32 + pr) * 16;   // its operand-order slot
@@ -411,16 +412,8 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             }
             return acc;
         };
-        Pieces pc;
-        load_tiles(pc, far_blocks);
-        __syncthreads();                                         // the far loop's LDS use is over
-        for (int blk = far_blocks; blk < nblocks; ++blk) {
-            const int jb = blk * kTB;
-            const char *base = tiles + (blk & 1) * (3 * kTileBytes);
-            store_tiles(pc, blk & 1);
-            __syncthreads();
-            if (blk + 1 < nblocks) load_tiles(pc, blk + 1);      // in flight while this block is computed
-            float s[16];
+        // raw score registers of a block: exact / K_hat scores picked per element, causal mask applied
+        auto block_scores = [&](float (&s)[16], const char *base, int jb) {
             {
                 const f32x16 sk = score_tile(base);
 #pragma unroll
@@ -436,20 +429,49 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                     s[r] = (j >= my_win) ? s[r] : sh[r];
                 }
             }
-            if (jb + kTB <= i0 + 1) {   // no masked entry for any row of the tile
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
-            } else {
+            if (jb + kTB > i0 + 1) {   // some entry is masked for some row of the tile
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int j = jb + 8 * (r >> 2) + 4 * half + (r & 3);
-                    s[r] = (j <= my_i) ? s[r] * a.scale_log2 : -INFINITY;
+                    s[r] = (j <= my_i) ? s[r] : -INFINITY;
                 }
             }
+        };
+        // Software pipeline over blocks: the score MFMAs of block b+1 are issued before the softmax of
+        // block b, so matrix-core and vector-ALU work of one wave overlap.  Buffer b % 3 holds the tiles of
+        // block b; its K tile is read one iteration before its V tile.
+        Pieces p0, p1;
+        load_tiles(p0, far_blocks);
+        if (far_blocks + 1 < nblocks) load_tiles(p1, far_blocks + 1);
+        __syncthreads();                                         // the far loop's LDS use is over
+        store_tiles(p0, 0);
+        p0 = p1;
+        if (far_blocks + 2 < nblocks) load_tiles(p1, far_blocks + 2);
+        __syncthreads();
+        float s_cur[16];
+        block_scores(s_cur, tiles, far_blocks * kTB);
+        int buf = 0;
+        for (int blk = far_blocks; blk < nblocks; ++blk) {
+            const char *base = tiles + buf * (3 * kTileBytes);
+            const int nbuf = buf == 2 ? 0 : buf + 1;
+            const bool more = blk + 1 < nblocks;
+            if (more) {
+                store_tiles(p0, nbuf);
+                p0 = p1;
+                if (blk + 3 < nblocks) load_tiles(p1, blk + 3);  // in flight for two iterations
+            }
+            __syncthreads();
+            float s_next[16];
+            if (more) block_scores(s_next, tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
             u32x4 vreg[2 * MT];
 #pragma unroll
             for (int k = 0; k < 2 * MT; ++k) vreg[k] = *(const u32x4 *)(base + 2 * kTileBytes + (k * 64 + lane) * 16);
-            softmax_pv(s, vreg);
+            softmax_pv(s_cur, a.scale_log2, vreg);
+            if (more) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_cur[r] = s_next[r];
+            }
+            buf = nbuf;
         }
     }
 
@@ -527,7 +549,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
-    const size_t lds_near = (size_t)6 * D * 64;
+    const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
     static bool attr_done = false;
     if (!attr_done) {
