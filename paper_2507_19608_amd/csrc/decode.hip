@@ -520,7 +520,7 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
             float p[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                p[r] = exp2f(acc[rt][r] - m);
+                p[r] = __builtin_amdgcn_exp2f(acc[rt][r] - m);
                 l += p[r];
             }
             typedef __attribute__((ext_vector_type(2))) float f32x2;

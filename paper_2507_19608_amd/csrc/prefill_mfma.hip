@@ -182,7 +182,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         if (__any(bm > m_run + 8.f)) {
             const float m_new = fmaxf(m_run, bm);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m_run - m_use);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            p[r] = exp2f(fmaf(s[r], sc, neg_m));
+            p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], sc, neg_m));   // bare v_exp_f32: tiny results may flush to 0
             psum += p[r];
         }
         l_run += psum;
@@ -376,8 +376,11 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         constexpr int kPieces = kTileBytes / 16;                 // 16-byte pieces per tile (256 or 512)
         char *tiles = lds_raw + (size_t)D * kRows * 2;           // [3 buffers][K, K_hat, V]
         const bool has_piece = tid < kPieces;
-        const int pr = tid / (D / 8), pseg = tid % (D / 8);      // K piece: key row, 8-channel segment
-        const int kslot = ((pseg >> 1) * 64 + (pseg & 1) * 32 + pr) * 16;   // its operand-order slot
+        // K piece of thread tid: key row tid % 32, 8-channel segment tid / 32.  Its operand-order slot is then
+        // tid itself, so a wave's 64 LDS stores are contiguous (a row-major thread-to-piece map made 16 lanes
+        // hit the same banks)
+        const int pr = tid & 31, pseg = tid >> 5;
+        const int kslot = ((pseg >> 1) * 64 + (pseg & 1) * 32 + pr) * 16;
         // operand X of a block: K_hat while every row has the block outside its window (rebase mode), else K
         auto first_src = [&](int jb) -> const bf16_t * { return (jb + kTB <= win_first) ? Hp : Kp; };
         struct Pieces {
