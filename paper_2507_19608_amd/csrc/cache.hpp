@@ -15,14 +15,25 @@ struct da_cache {
     int nck;              // checkpoints per unit: max_seq / kChunk + 1
     int max_chunks;       // (max_seq + kChunk - 1) / kChunk
     int vrows;            // max_seq rounded up to a whole chunk (row capacity of V)
+    int fast;             // 1: bf16, head_dim 64 or 128, decode window >= kChunk, <= 32 query heads per KV
+                          //    head: the column-run layout below
     // per (batch, KV head) unit, all device memory:
     uint32_t *mask;       // [units][max_seq][d/32]   delta mask bits
-    void *surv;           // [units][max_chunks][kChunk * d] surviving key values of a chunk: row after row, channel order
-    uint32_t *ccnt;       // [units][max_chunks]      survivors stored in each chunk
+    // Surviving key values (the new reference values at the positions the mask marks), (kChunk + 1) * d
+    // elements of room per chunk.
+    //   row layout (fast == 0): row after row, channels ascending inside a row, appended one row per step.
+    //   column-run layout (fast == 1): written once per chunk, when its last row has arrived ("sealed"):
+    //     for every channel in ascending order one run = the reference value held when the chunk starts,
+    //     then the channel's surviving values in row order.  Rows of an unsealed chunk are always inside
+    //     the decode window (window >= kChunk), where raw keys are used, so they need no run.
+    void *surv;           // [units][max_chunks][(kChunk + 1) * d]
+    uint32_t *ccnt;       // [units][max_chunks]      elements stored in each chunk's room
     void *ck;             // [units][nck][d]          ck[m] = reference key after row m*kChunk - 1 (m >= 1)
     void *khat;           // [units][d]               current reference key
     void *ring;           // [units][Wd][d]           raw key of position p at slot p % Wd
-    void *V;              // [units][vrows / 8][d][8]: 8 rows interleaved per channel
+    void *V;              // fast == 0: [units][vrows / 8][d][8], 8 rows interleaved per channel;
+                          // fast == 1: [units][vrows / 16][d][16], 16 rows per channel in matrix-core
+                          //            accumulator order (slot 8 k + i holds row 8 (i / 4) + 4 k + i % 4)
     uint64_t *nnz;        // [units]
     float *part;          // [B*Hq][max_chunks][d + 2] per-chunk (o, m, l) partials of one decode step
 };
@@ -32,4 +43,10 @@ da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p)
 void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void *K, const void *V,
                              const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,
                              const uint64_t *nnz, hipStream_t s);
+// column-run layout (fast == 1)
+void cache_fill_runs(da_cache *c, int n, const void *K, const void *V, const void *Khat, const uint32_t *mask_bits,
+                     const uint64_t *nnz, hipStream_t s);
+void decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, uint32_t *mask_row, int t,
+                      float scale_log2, hipStream_t s);
+void seal_chunk_runs(da_cache *c, int chunk, hipStream_t s);
 }  // namespace da

@@ -38,4 +38,17 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
+// exclusive prefix sum over the 64 lanes; *total receives the wave sum
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, uint32_t *total) {
+    const int lane = threadIdx.x & 63;
+    uint32_t inc = v;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const uint32_t o = __shfl_up(inc, s);
+        if (lane >= s) inc += o;
+    }
+    *total = __shfl(inc, 63);
+    return inc - v;
+}
+
 }  // namespace da

@@ -25,10 +25,10 @@ __device__ __forceinline__ size_t v_index(int unit, int vrows, int d, int t, int
     return ((size_t)unit * (vrows >> 3) + (t >> 3)) * ((size_t)d * 8) + (size_t)ch * 8 + (t & 7);
 }
 
-// surviving key values of one chunk of kChunk rows: row after row, channel order, fixed room of kChunk * d
+// surviving key values of one chunk of kChunk rows: row after row, channel order, room of (kChunk + 1) * d
 template <typename T>
 __device__ __forceinline__ T *surv_chunk(const da_cache &c, int unit, int chunk) {
-    return (T *)c.surv + ((size_t)unit * c.max_chunks + chunk) * ((size_t)kChunk * c.d);
+    return (T *)c.surv + ((size_t)unit * c.max_chunks + chunk) * ((size_t)(kChunk + 1) * c.d);
 }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -41,19 +41,6 @@ __device__ __forceinline__ float wave_sum(float v) {
     for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s);
     return v;
 }
-// exclusive prefix sum over the 64 lanes; *total receives the wave sum
-__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, uint32_t *total) {
-    const int lane = threadIdx.x & 63;
-    uint32_t inc = v;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-        const uint32_t o = __shfl_up(inc, s);
-        if (lane >= s) inc += o;
-    }
-    *total = __shfl(inc, 63);
-    return inc - v;
-}
-
 // ---------------------------------------------------------------------------------- cache fill
 // Prefill hand-off (Sec. III-C): one wave per (chunk of kChunk rows, unit) turns the prefill's mask rows,
 // keys, reference keys and values into the cache layout.
@@ -584,6 +571,16 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const int units = c->B * c->Hkv;
     const float sc = (c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d)) * 1.4426950408889634f;
     const int nchunks = t / kChunk + 1;
+    if (c->fast) {
+        stage_begin(kStageChunk, s);
+        da::decode_step_runs(c, q, k, v, mask_row, t, sc, s);
+        stage_end(kStageChunk, s);
+        stage_begin(kStageCombine, s);
+        hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+        stage_end(kStageCombine, s);
+        if ((t + 1) % kChunk == 0) da::seal_chunk_runs(c, t / kChunk, s);
+        return;
+    }
     if (c->dtype == DA_BF16) {
         const size_t lds = ((size_t)16 * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
         static bool attr_done = false;   // d = 256 needs more than 64 KiB
@@ -654,6 +651,11 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
                              const uint64_t *nnz, hipStream_t s) {
     (void)counts;
     const int units = c->B * c->Hkv, n = p->seq_len;
+    if (c->fast) {
+        da::cache_fill_runs(c, n, K, V, Khat, mask_bits, nnz, s);
+        c->len = n;
+        return;
+    }
     dim3 grid((n + kChunk - 1) / kChunk, units), block(64);
     if (c->dtype == DA_F32)
         hipLaunchKernelGGL(cache_fill_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)V,
@@ -696,6 +698,8 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     c->nck = max_seq / kChunk + 1;
     c->max_chunks = (max_seq + kChunk - 1) / kChunk;
     c->vrows = (max_seq + kChunk - 1) / kChunk * kChunk;
+    c->fast = dtype == DA_BF16 && (head_dim == 64 || head_dim == 128) && c->Wd >= kChunk &&
+              n_q_heads / n_kv_heads <= 32;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;
         return DA_ERR_HIP;
@@ -703,7 +707,7 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     const size_t units = (size_t)batch * n_kv_heads, es = elt_size(dtype), d = head_dim;
     bool ok = true;
     ok = ok && hipMalloc((void **)&c->mask, units * max_seq * (d / 32) * 4) == hipSuccess;
-    ok = ok && hipMalloc(&c->surv, units * (size_t)c->max_chunks * kChunk * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->surv, units * (size_t)c->max_chunks * (kChunk + 1) * d * es) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->ccnt, units * (size_t)c->max_chunks * 4) == hipSuccess;
     ok = ok && hipMalloc(&c->ck, units * c->nck * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->khat, units * d * es) == hipSuccess;

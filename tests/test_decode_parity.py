@@ -64,6 +64,21 @@ def test_decode_small(n, steps, d, Wd, B, Hq, Hkv, theta, dtype):
     run_decode(Q, K, V, n, steps, theta, Wd, dtype, scale=0.0 if dtype == "bf16" else 0.15)
 
 
+@pytest.mark.parametrize("n,steps,d,Wd,B,Hq,Hkv,theta", [
+    (70, 130, 64, 64, 2, 4, 2, 0.2),      # window = one chunk: a chunk is sealed one step before its first row leaves
+    (200, 70, 128, 70, 1, 8, 1, 0.15),    # head_dim 128, 8 query heads per KV head
+    (0, 140, 64, 64, 1, 2, 1, 0.25),      # from an empty cache through two seals
+    (128, 65, 64, 100, 1, 32, 1, 0.1),    # prefill ends on a chunk boundary; 32 heads share the KV head
+    (191, 3, 128, 128, 1, 2, 2, 0.3),     # the prefill leaves an unsealed chunk one row short of full
+])
+def test_decode_column_run_layout(n, steps, d, Wd, B, Hq, Hkv, theta):
+    """bf16 caches with head_dim 64 / 128 and a decode window of at least one chunk keep the compact
+    cache as per-channel runs sealed chunk by chunk; same oracle, same tolerances."""
+    L = n + steps
+    Q, K, V = rand_walk(31, B, Hq, L, d), rand_walk(32, B, Hkv, L, d), rand_walk(33, B, Hkv, L, d, clip=3.5)
+    run_decode(Q, K, V, n, steps, theta, Wd, "bf16")
+
+
 def test_decode_from_empty_cache_and_dense_limits():
     B, Hq, Hkv, L, d = 1, 2, 1, 40, 64
     Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d, clip=3.5)
@@ -71,6 +86,10 @@ def test_decode_from_empty_cache_and_dense_limits():
     run_decode(Q, K, V, 10, 30, 0.0, 3, "bf16")           # theta = 0: dense attention
     run_decode(Q, K, V, 10, 30, 0.4, 1000, "bf16")        # window covers everything
     run_decode(Q, K, V, 10, 30, float("inf"), 3, "bf16")  # history frozen at the basis key
+    L = 200
+    Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d, clip=3.5)
+    run_decode(Q, K, V, 100, 100, 0.0, 64, "bf16")           # the same limits in the column-run layout
+    run_decode(Q, K, V, 100, 100, float("inf"), 64, "bf16")
 
 
 def test_cache_state_errors():
