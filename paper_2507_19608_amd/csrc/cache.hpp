@@ -35,8 +35,11 @@ struct da_cache {
                           // fast == 1: [units][vrows / 16][d][16], 16 rows per channel in matrix-core
                           //            accumulator order (slot 8 k + i holds row 8 (i / 4) + 4 k + i % 4)
     uint64_t *nnz;        // [units]
-    float *part;          // [B*Hq][max_chunks][d + 2] per-chunk (o, m, l) partials of one decode step
+    float *part;          // [B*Hq][max_chunks][d + 4] partial (o[d], m, l, 2 unused) rows of one decode step
 };
+
+// floats per partial row: o[d], running maximum, running sum, padded to a 16-byte multiple
+__host__ __device__ inline int part_stride(int d) { return d + 4; }
 
 namespace da {
 da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p);

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
         __syncthreads();
         pb[lane] = p;
         __syncthreads();
-        float *out = c.part + (((size_t)b * c.Hq + h) * c.max_chunks + chunk) * (d + 2);
+        float *out = c.part + (((size_t)b * c.Hq + h) * c.max_chunks + chunk) * part_stride(d);
         const T *Vp = (const T *)c.V;
         for (int w = 0; w * kWave < d; ++w) {
             const int ch = w * kWave + lane;
@@ -244,50 +244,68 @@ __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *_
     }
 }
 
-// Merge of the per-chunk partials (o, m, l) of one (batch, query head): lanes = chunks for the weights,
-// lanes = channels for the output.
+// Merge of the partials (o, m, l) of one (batch, query head).  A partial row is read by G = d / 4 lanes
+// (rounded up to a power of two) as 128-bit loads, so 64 / G partials are in flight side by side and kB
+// per lane: all loads of a batch are independent.  Every lane keeps a running (max, sum, 4 channels);
+// the lane groups are merged with two or three shuffle steps at the end.
 template <typename T>
-__device__ void combine_head(const da_cache &c, int bh, int lane, T *__restrict__ o, int nchunks) {
-    const int d = c.d;
-    const float *part = c.part + (size_t)bh * c.max_chunks * (d + 2);
-    auto ld = [&](const float *p) -> float { return *p; };
-    float M = -INFINITY;
-    for (int k = lane; k < nchunks; k += kWave) M = fmaxf(M, ld(part + (size_t)k * (d + 2) + d));
-    M = wave_max(M);
-    float L = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < nchunks; k0 += kWave) {
-        const int k = k0 + lane;
-        const float wk = k < nchunks ? exp2f(ld(part + (size_t)k * (d + 2) + d) - M) : 0.f;
-        L += k < nchunks ? wk * ld(part + (size_t)k * (d + 2) + d + 1) : 0.f;
-        const int cnt = min(kWave, nchunks - k0);
-        for (int kb = 0; kb < cnt; kb += 8) {
-            float w[8], x[8][4];
+__global__ __launch_bounds__(64) void decode_combine_kernel(da_cache c, T *__restrict__ o, int nparts) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    constexpr int kB = 4;
+    const int bh = blockIdx.x, lane = threadIdx.x, d = c.d, ps = part_stride(d);
+    int G = 8;
+    while (G * 4 < d) G <<= 1;
+    const int li = lane & (G - 1), slot = lane / G, slots = kWave / G;
+    const bool act = li * 4 < d;
+    const float *part = c.part + (size_t)bh * c.max_chunks * ps;
+    float M = -INFINITY, L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < nparts; k0 += slots * kB) {
+        f32x4 x[kB];
+        f32x2 ml[kB];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int kk = min(kb + u, cnt - 1);
-                w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wk), kk));
-                if (kb + u >= cnt) w[u] = 0.f;
-                const float *row = part + (size_t)(k0 + kk) * (d + 2);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) x[u][i] = (i * kWave + lane < d) ? ld(row + i * kWave + lane) : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[i] = fmaf(w[u], x[u][i], acc[i]);
+        for (int u = 0; u < kB; ++u) {
+            const float *row = part + (size_t)min(k0 + u * slots + slot, nparts - 1) * ps;
+            x[u] = act ? *(const f32x4 *)(row + 4 * li) : f32x4{0.f, 0.f, 0.f, 0.f};
+            ml[u] = *(const f32x2 *)(row + d);
         }
-    }
-    L = wave_sum(L);
-    const float inv = 1.f / L;
+        float mb = M;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (i * kWave + lane < d) store_from_f32(o + (size_t)bh * d, i * kWave + lane, acc[i] * inv);
+        for (int u = 0; u < kB; ++u)
+            if (k0 + u * slots + slot < nparts) mb = fmaxf(mb, ml[u][0]);
+        const float f = mb == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - mb);
+        L *= f;
+        acc *= f;
+#pragma unroll
+        for (int u = 0; u < kB; ++u) {
+            const float w = (k0 + u * slots + slot < nparts) ? __builtin_amdgcn_exp2f(ml[u][0] - mb) : 0.f;
+            L = fmaf(w, ml[u][1], L);
+            acc += w * x[u];
+        }
+        M = mb;
+    }
+    for (int s = G; s < kWave; s <<= 1) {
+        const float m2 = __shfl_xor(M, s), l2 = __shfl_xor(L, s);
+        f32x4 a2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a2[i] = __shfl_xor(acc[i], s);
+        const float mn = fmaxf(M, m2);
+        const float f1 = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - mn);
+        const float f2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+        L = L * f1 + l2 * f2;
+        acc = acc * f1 + a2 * f2;
+        M = mn;
+    }
+    if (slot == 0 && act) {
+        const float inv = 1.f / L;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) store_from_f32(o + (size_t)bh * d, 4 * li + i, acc[i] * inv);
+    }
 }
 
 template <typename T>
-__global__ __launch_bounds__(64) void decode_combine_kernel(da_cache c, T *__restrict__ o, int nchunks) {
-    combine_head<T>(c, blockIdx.x, threadIdx.x, o, nchunks);
+void launch_combine(da_cache *c, T *o, int nparts, hipStream_t s) {
+    hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, o, nparts);
 }
 
 // The decode step for bf16 caches: one wave per chunk of kChunk cached rows of one
@@ -520,7 +538,7 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         if (lane < gh) {
-            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * (d + 2);
+            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * part_stride(d);
             out[d] = m;
             out[d + 1] = l;
         }
@@ -555,7 +573,7 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
             for (int r = 0; r < 4; ++r) {
                 const int h = 4 * lg + r;
                 if (h < gh)
-                    c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (d + 2) + 16 * ct + l16] =
+                    c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * part_stride(d) + 16 * ct + l16] =
                         o[r];
             }
         }
@@ -576,7 +594,7 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
         da::decode_step_runs(c, q, k, v, mask_row, t, sc, s);
         stage_end(kStageChunk, s);
         stage_begin(kStageCombine, s);
-        hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+        launch_combine<T>(c, (T *)o, nchunks, s);
         stage_end(kStageCombine, s);
         if ((t + 1) % kChunk == 0) da::seal_chunk_runs(c, t / kChunk, s);
         return;
@@ -603,7 +621,7 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
                                (const bf16_t *)k, (const bf16_t *)v, mask_row, t, sc);
         stage_end(kStageChunk, s);
         stage_begin(kStageCombine, s);
-        hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+        launch_combine<T>(c, (T *)o, nchunks, s);
         stage_end(kStageCombine, s);
         return;
     }
@@ -624,7 +642,7 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     }
     stage_end(kStageChunk, s);
     stage_begin(kStageCombine, s);
-    hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, (T *)o, nchunks);
+    launch_combine<T>(c, (T *)o, nchunks, s);
     stage_end(kStageCombine, s);
 }
 
@@ -715,7 +733,7 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     ok = ok && hipMalloc(&c->V, units * (size_t)c->vrows * d * es) == hipSuccess;
     if (ok) ok = hipMemset(c->V, 0, units * (size_t)c->vrows * d * es) == hipSuccess;   // rows never written must be finite
     ok = ok && hipMalloc((void **)&c->nnz, units * 8) == hipSuccess;
-    ok = ok && hipMalloc((void **)&c->part, (size_t)batch * n_q_heads * c->max_chunks * (d + 2) * 4) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->part, (size_t)batch * n_q_heads * c->max_chunks * part_stride(d) * 4) == hipSuccess;
     if (ok) ok = hipMemset(c->nnz, 0, units * 8) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();

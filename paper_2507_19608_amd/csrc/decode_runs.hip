@@ -337,7 +337,7 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
             }
         l += __shfl_xor(l, 32);
         if (lane < gh) {
-            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * (D + 2);
+            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * part_stride(D);
             out[D] = m;
             out[D + 1] = l;
         }
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int h = 8 * rq + 4 * kap + r4;
                     if (h < gh)
-                        c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * (D + 2) + ch] =
+                        c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * part_stride(D) + ch] =
                             o[4 * rq + r4];
                 }
             }
