@@ -20,7 +20,7 @@ EXPORTS = [
     "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
     "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
-    "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
+    "delta_attn_cache_set_launch_plan", "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
     "delta_attn_sparsity",
 ]
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_cache_destroy.argtypes = [vp]
         L.delta_attn_cache_reset.restype = ctypes.c_int
         L.delta_attn_cache_reset.argtypes = [vp, vp]
+        L.delta_attn_cache_set_launch_plan.restype = ctypes.c_int
+        L.delta_attn_cache_set_launch_plan.argtypes = [vp, i32, i32]
         L.delta_attn_cache_length.restype = i64
         L.delta_attn_cache_length.argtypes = [vp]
         L.delta_attn_cache_nnz.restype = vp
@@ -179,6 +181,10 @@ class Cache:
 
     def reset(self):
         _check(lib().delta_attn_cache_reset(self.handle, _stream()), "delta_attn_cache_reset")
+
+    def set_launch_plan(self, merge_in_kernel: int = -1, wave_slots: int = 0):
+        _check(lib().delta_attn_cache_set_launch_plan(self.handle, int(merge_in_kernel), int(wave_slots)),
+               "delta_attn_cache_set_launch_plan")
 
     def nnz(self):
         """[B, Hkv] int64 copy of the per-unit nnz counters."""

@@ -15,6 +15,8 @@ struct da_cache {
     int nck;              // checkpoints per unit: max_seq / kChunk + 1
     int max_chunks;       // (max_seq + kChunk - 1) / kChunk
     int vrows;            // max_seq rounded up to a whole chunk (row capacity of V)
+    int plan_merge;       // launch plan of the column-run layout: -1 auto, 0 second launch, 1 merge in the kernel
+    int plan_slots;       // wave slots a launch is sized for, 0 = from the device
     int fast;             // 1: bf16, head_dim 64 or 128, decode window >= kChunk, <= 32 query heads per KV
                           //    head: the column-run layout below
     // per (batch, KV head) unit, all device memory:
@@ -49,7 +51,8 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
 // column-run layout (fast == 1)
 void cache_fill_runs(da_cache *c, int n, const void *K, const void *V, const void *Khat, const uint32_t *mask_bits,
                      const uint64_t *nnz, hipStream_t s);
-void decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, uint32_t *mask_row, int t,
-                      float scale_log2, hipStream_t s);
+// returns the number of partial rows written per head, 0 if the launch wrote the output itself
+int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,
+                     float scale_log2, hipStream_t s);
 void seal_chunk_runs(da_cache *c, int chunk, hipStream_t s);
 }  // namespace da

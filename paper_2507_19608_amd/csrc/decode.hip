@@ -591,11 +591,13 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     const int nchunks = t / kChunk + 1;
     if (c->fast) {
         stage_begin(kStageChunk, s);
-        da::decode_step_runs(c, q, k, v, mask_row, t, sc, s);
+        const int nparts = da::decode_step_runs(c, q, k, v, o, mask_row, t, sc, s);
         stage_end(kStageChunk, s);
-        stage_begin(kStageCombine, s);
-        launch_combine<T>(c, (T *)o, nchunks, s);
-        stage_end(kStageCombine, s);
+        if (nparts > 0) {
+            stage_begin(kStageCombine, s);
+            launch_combine<T>(c, (T *)o, nparts, s);
+            stage_end(kStageCombine, s);
+        }
         if ((t + 1) % kChunk == 0) da::seal_chunk_runs(c, t / kChunk, s);
         return;
     }
@@ -716,6 +718,8 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     c->nck = max_seq / kChunk + 1;
     c->max_chunks = (max_seq + kChunk - 1) / kChunk;
     c->vrows = (max_seq + kChunk - 1) / kChunk * kChunk;
+    c->plan_merge = -1;
+    c->plan_slots = 0;
     c->fast = dtype == DA_BF16 && (head_dim == 64 || head_dim == 128) && c->Wd >= kChunk &&
               n_q_heads / n_kv_heads <= 32;
     if (hipGetDevice(&c->device) != hipSuccess) {
@@ -757,6 +761,13 @@ da_status delta_attn_cache_reset(da_cache *c, void *hip_stream) {
     launch_fill_u64(c->nnz, 0, c->B * c->Hkv, (hipStream_t)hip_stream);
     c->len = 0;
     return launch_ok("cache_reset") ? DA_OK : DA_ERR_HIP;
+}
+
+da_status delta_attn_cache_set_launch_plan(da_cache *c, int32_t merge_in_kernel, int32_t wave_slots) {
+    if (!c || merge_in_kernel < -1 || merge_in_kernel > 1 || wave_slots < 0) return DA_ERR_INVALID_ARG;
+    c->plan_merge = merge_in_kernel;
+    c->plan_slots = wave_slots;
+    return DA_OK;
 }
 
 int64_t delta_attn_cache_length(const da_cache *c) { return c ? c->len : -1; }

@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // V cache, column-run layout: 16 rows per channel, [unit][t / 16][channel][16].  Inside a group of 16 the
 // slot of row p is 8 k + i with k = (p / 4) % 2 and i = 4 (p / 8) + p % 4: the order in which the 32x32
@@ -143,7 +144,11 @@ __device__ void append_row_runs(const da_cache &c, int unit, int lane, const bf1
     if (lane == 0) c.nnz[unit] = (t == 0 ? 0ull : c.nnz[unit]) + fired;
 }
 
-// One decode step: one wave per (chunk of kChunk cached rows, unit), all query heads of the unit's group.
+// One decode step: one wave per (run of `nc` consecutive chunks, unit), all query heads of the unit's group.
+// A wave walks its chunks in order with flash-style running (max, sum, output) in registers, and asks for
+// the next chunk's mask rows and runs while it works on the current one; a launch is sized so that all of
+// its waves are resident at once (work-group dispatch, not memory, bounds a launch of one chunk per wave).
+// Per chunk:
 //   0. the wave that owns the newest row appends it (D1);
 //   1. history chunks (rows left of the decode window): the chunk's runs are copied to LDS; lane = row j
 //      takes, for every channel c, element B_c + #{marked rows <= j of channel c} of the staged runs,
@@ -154,62 +159,103 @@ __device__ void append_row_runs(const da_cache &c, int unit, int lane, const bf1
 //      Window rows (lane = row again) are 128-bit loads from the raw-key ring, the newest from k_new.
 //   2. a lane now holds a whole key row; one permlane32 swap per register pair turns that into the
 //      32x32x16 operand order (lane l: row l % 32, channels 16 s + 8 (l / 32)..+7 of contraction step s);
-//   3. scores S[row][head] on the matrix cores (heads padded to 32 columns), softmax of the chunk in the
+//   3. scores S[row][head] on the matrix cores (heads padded to 32 columns); softmax update in the
 //      accumulator registers (lane = head, 32 rows per lane, the other 32 in lane + 32);
-//   4. the accumulator registers, rounded to bf16, are the A operand of P V as they stand, because the V
-//      cache stores each group of 16 rows in exactly that order; partial (o, m, l) of the chunk to scratch.
-template <int D>
-__global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(da_cache c, const bf16_t *__restrict__ q_new,
-                                                              const bf16_t *__restrict__ k_new,
-                                                              const bf16_t *__restrict__ v_new,
-                                                              uint32_t *__restrict__ mask_row, int t,
-                                                              float scale_log2) {
-    extern __shared__ float lds_f[];
-    bf16_t *__restrict__ sv = (bf16_t *)lds_f;               // staged runs, <= (kChunk + 1) * D elements
+//   4. the accumulator registers, rounded to bf16, are the B operand of O^T += V^T P^T as they stand, because
+//      the V cache stores each group of 16 rows in exactly that order; O^T keeps lane = head, so the
+//      running rescale needs no cross-lane traffic.
+// The wave's (o, m, l) goes to scratch; a second launch merges the partials of a head.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, const bf16_t *__restrict__ q_new,
+                                                                    const bf16_t *__restrict__ k_new,
+                                                                    const bf16_t *__restrict__ v_new,
+                                                                    bf16_t *__restrict__ o_out,
+                                                                    uint32_t *__restrict__ mask_row, int t,
+                                                                    float scale_log2, int nc) {
     constexpr int WPR = D / 32, KS = D / 16, CT = D / 32, NK = D / 2;
     constexpr int kRoom = (kChunk + 1) * D;                  // elements
     constexpr int kPieces = (kRoom + 511) / 512;             // 1 KiB copies (16 bytes per lane) that cover the room
-    constexpr int kEager = D / 16;                           // copies requested before the element count is known
-    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
+    // two staging areas for the runs of a chunk, used in turn: separate arrays, so that reads of one are known
+    // not to touch the other while its copy is still in flight
+    __shared__ __attribute__((aligned(16))) bf16_t stage_a_all[NW][kPieces * 512];
+    __shared__ __attribute__((aligned(16))) bf16_t stage_b_all[NW][kPieces * 512];
+    __shared__ float ml_all[NW][32][2];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    bf16_t *stage_a = stage_a_all[wave], *stage_b = stage_b_all[wave];
+    const int part_i = blockIdx.x * NW + wave, unit = blockIdx.y, lane = threadIdx.x & 63;
     const int nchunks = t / kChunk + 1;
-    const bool newest = chunk == nchunks - 1;
-    const int r0 = chunk * kChunk;
-    const int nrows = min(kChunk, t + 1 - r0);
-    const int g = c.Hq / c.Hkv;
+    const int c_begin = part_i * nc, c_end = min(c_begin + nc, nchunks);
+    const int g = c.Hq / c.Hkv;                              // <= 32 in this layout
     const int b = unit / c.Hkv, hk = unit % c.Hkv;
-    const int hist_rows = min(max(t + 1 - c.Wd - r0, 0), nrows);   // > 0 only for sealed chunks (Wd >= kChunk)
     const int n32 = lane & 31, kap = lane >> 5;
+    const int win_begin = t + 1 - c.Wd;
+    // rows of chunk ch left of the decode window (> 0 only for sealed chunks, because Wd >= kChunk)
+    auto hist_of = [&](int ch) { return min(max(win_begin - ch * kChunk, 0), min(kChunk, t + 1 - ch * kChunk)); };
 
-    // ---- requests whose addresses depend on nothing loaded
-    uint32_t mk[WPR];
-    u32x4 sp[kEager];
-    uint32_t total = 0;
-    const bf16_t *runs = run_room(c, unit, chunk);
-    if (hist_rows > 0) {
-        const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0 + lane) * WPR;
-#pragma unroll
-        for (int w = 0; w < WPR; ++w) mk[w] = Mp[w];
-        total = c.ccnt[(size_t)unit * c.max_chunks + chunk];
-#pragma unroll
-        for (int p = 0; p < kEager; ++p) sp[p] = *(const u32x4 *)(runs + p * 512 + lane * 8);
-    }
-    // q operands of the first 32 heads (B operand of the score contraction)
+    // q operands (B operand of the score contraction): lane l = head l % 32, channels 16 s + 8 (l / 32)..+7
     u32x4 qop[KS];
     {
-        const int gh0 = g;
-        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + min(n32, gh0 - 1)) * D;
+        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + min(n32, g - 1)) * D;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             qop[s] = *(const u32x4 *)(qrow + 16 * s + 8 * kap);
-            if (n32 >= gh0) qop[s] = u32x4{0u, 0u, 0u, 0u};
+            if (n32 >= g) qop[s] = u32x4{0u, 0u, 0u, 0u};
         }
     }
-    // V operands of the whole chunk (needed last): B operand of P V, lane l = channel 32 ct + l % 32, rows of
-    // lane half l / 32 of the 16-row group; the newest row is patched in from v_new
-    u32x4 vop[CT][2][2];
-    auto load_v = [&]() {
-        const int pt = t & 15;
-        const int kap_t = (pt >> 2) & 1, i_t = 4 * (pt >> 3) + (pt & 3);
+    // History chunk ch: its runs go straight from global memory to the LDS staging area (128-bit LDS-direct
+    // loads: lane i of a copy lands at base + 16 i), `total` elements of them; its mask rows, lane = row.
+    auto copy_runs = [&](int ch, uint32_t total, bf16_t *sv) {
+        const bf16_t *runs = run_room(c, unit, ch);
+#pragma unroll
+        for (int p = 0; p < kPieces; ++p)
+            if ((uint32_t)p * 512u < total && p * 512 + lane * 8 + 8 <= kRoom)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(runs + p * 512 + lane * 8),
+                                                 (__attribute__((address_space(3))) void *)(sv + p * 512), 16, 0, 0);
+    };
+    auto total_of = [&](int ch) -> uint32_t {
+        return hist_of(ch) > 0 ? __builtin_amdgcn_readfirstlane(c.ccnt[(size_t)unit * c.max_chunks + ch]) : 0u;
+    };
+    uint32_t mk_n[WPR];
+    auto request_masks = [&](int ch) {
+        if (hist_of(ch) > 0) {
+            const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + ch * kChunk + lane) * WPR;
+#pragma unroll
+            for (int w = 0; w < WPR; ++w) mk_n[w] = Mp[w];
+        }
+    };
+    if (c_begin < c_end) {
+        copy_runs(c_begin, total_of(c_begin), stage_a);
+        request_masks(c_begin);
+    }
+    uint32_t tot_v = 0;                                      // element count of the chunk after the next one's copy
+    if (c_begin + 1 < c_end && hist_of(c_begin + 1) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + c_begin + 1];
+
+    f32x16 o[CT];                                            // O^T: lane = head, register r of tile ct =
+#pragma unroll                                               // channel 32 ct + 8 (r / 4) + 4 (l / 32) + r % 4
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;                    // l_run: this lane half's share of the sum
+
+    auto do_chunk = [&](int chunk, const bf16_t *sv, bf16_t *sv_next) {
+        const bool newest = chunk == nchunks - 1;            // this wave owns row t
+        const int r0 = chunk * kChunk;
+        const int nrows = min(kChunk, t + 1 - r0);
+        const int hist_rows = hist_of(chunk);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this chunk's runs have landed in LDS
+        // the next chunk's runs and mask rows, and the element count of the one after it, fly in meanwhile
+        uint32_t mk[WPR];
+#pragma unroll
+        for (int w = 0; w < WPR; ++w) mk[w] = mk_n[w];
+        if (chunk + 1 < c_end) {
+            copy_runs(chunk + 1, __builtin_amdgcn_readfirstlane(tot_v), sv_next);
+            request_masks(chunk + 1);
+            tot_v = 0;
+            if (chunk + 2 < c_end && hist_of(chunk + 2) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + chunk + 2];
+        }
+        // V operands of the chunk (needed last, requested first): lane l = channel 32 ct + l % 32, rows of lane
+        // half l / 32 of each 16-row group; the newest row is patched in from v_new
+        u32x4 vop[CT][2][2];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -221,7 +267,9 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
                                                       (((size_t)unit * (c.vrows >> 4) + (row16 >> 4)) * D + ch) * 16 + 8 * kap);
                 }
         if (newest) {
-            const int T = (t >> 5) & 1, s2 = (t >> 4) & 1;
+            const int pt = t & 15;
+            const int kap_t = (pt >> 2) & 1, i_t = 4 * (pt >> 3) + (pt & 3);
+            const int Tn = (t >> 5) & 1, sn = (t >> 4) & 1;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 const uint32_t vn = v_new[(size_t)unit * D + 32 * ct + n32];
@@ -231,78 +279,69 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
                     for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
                         for (int w = 0; w < 4; ++w) {
-                            const bool hit = TT == T && ss == s2 && w == (i_t >> 1) && kap == kap_t;
+                            const bool hit = TT == Tn && ss == sn && w == (i_t >> 1) && kap == kap_t;
                             const uint32_t old = vop[ct][TT][ss][w];
                             const uint32_t pat = (i_t & 1) ? ((old & 0xffffu) | (vn << 16)) : ((old & 0xffff0000u) | vn);
                             vop[ct][TT][ss][w] = hit ? pat : old;
                         }
             }
+            // 0. the new row goes into the cache (other waves of this launch never read what is written here)
+            append_row_runs(c, unit, lane, k_new, v_new, mask_row, t);
         }
-    };
-    // 0. the new row goes into the cache (other waves of this launch never read what is written here)
-    if (newest) append_row_runs(c, unit, lane, k_new, v_new, mask_row, t);
 
-    // 1. one key row per lane
-    uint32_t kreg[NK];
-    if (hist_rows > 0) {
+        // 1. one key row per lane
+        uint32_t kreg[NK];
+        if (hist_rows > 0) {
+            uint32_t run = 0;                                // uniform: survivors of the channels before this one
+            const char *svb = (const char *)sv;
 #pragma unroll
-        for (int p = 0; p < kEager; ++p) *(u32x4 *)(sv + p * 512 + lane * 8) = sp[p];
-        for (int p = kEager; p < kPieces && (uint32_t)p * 512u < total; ++p)
-            if (p * 512 + lane * 8 + 8 <= kRoom)
-                *(u32x4 *)(sv + p * 512 + lane * 8) = *(const u32x4 *)(runs + p * 512 + lane * 8);
-        __syncthreads();
-        uint32_t run = 0;                                    // uniform: survivors of the channels before this one
-        const char *svb = (const char *)sv;
+            for (int ch = 0; ch < D; ch += 2) {
+                uint32_t val[2];
 #pragma unroll
-        for (int ch = 0; ch < D; ch += 2) {
-            uint32_t val[2];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const uint32_t bit = (mk[(ch + e) >> 5] >> ((ch + e) & 31)) & 1u;
-                const uint64_t cm = __ballot(bit != 0u);
-                const uint32_t idx =
-                    __builtin_amdgcn_mbcnt_hi((uint32_t)(cm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)cm, bit));
-                val[e] = *(const bf16_t *)(svb + ((idx + run) << 1) + 2 * (ch + e));   // run start = run + ch + e
-                run += (uint32_t)__popcll(cm);
-            }
-            kreg[ch >> 1] = val[0] | (val[1] << 16);
-        }
-    }
-    if (hist_rows < kChunk) {
-        if (lane >= hist_rows) {
-            if (lane < nrows) {
-                const int row = r0 + lane;
-                const bf16_t *src = row == t ? k_new + (size_t)unit * D
-                                             : (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * D;
-#pragma unroll
-                for (int i = 0; i < D / 8; ++i) {
-                    const u32x4 v = *(const u32x4 *)(src + 8 * i);
-                    kreg[4 * i] = v[0];
-                    kreg[4 * i + 1] = v[1];
-                    kreg[4 * i + 2] = v[2];
-                    kreg[4 * i + 3] = v[3];
+                for (int e = 0; e < 2; ++e) {
+                    const uint32_t bit = (mk[(ch + e) >> 5] >> ((ch + e) & 31)) & 1u;
+                    const uint64_t cm = __ballot(bit != 0u);
+                    const uint32_t idx =
+                        __builtin_amdgcn_mbcnt_hi((uint32_t)(cm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)cm, bit));
+                    val[e] = *(const bf16_t *)(svb + ((idx + run) << 1) + 2 * (ch + e));   // run start = run + ch + e
+                    run += (uint32_t)__popcll(cm);
                 }
-            } else {
-#pragma unroll
-                for (int i = 0; i < NK; ++i) kreg[i] = 0u;
+                kreg[ch >> 1] = val[0] | (val[1] << 16);
             }
         }
-    }
-    // 2. operand order: kop[T][s] = rows 32 T + l % 32, channels 16 s + 8 (l / 32)..+7
-    u32x4 kop[2][KS];
+        if (hist_rows < kChunk) {
+            if (lane >= hist_rows) {
+                if (lane < nrows) {
+                    const int row = r0 + lane;
+                    const bf16_t *src = row == t ? k_new + (size_t)unit * D
+                                                 : (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * D;
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
+                    for (int i = 0; i < D / 8; ++i) {
+                        const u32x4 v = *(const u32x4 *)(src + 8 * i);
+                        kreg[4 * i] = v[0];
+                        kreg[4 * i + 1] = v[1];
+                        kreg[4 * i + 2] = v[2];
+                        kreg[4 * i + 3] = v[3];
+                    }
+                } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const auto sw = __builtin_amdgcn_permlane32_swap(kreg[8 * s + i], kreg[8 * s + 4 + i], false, false);
-            kop[0][s][i] = sw[0];
-            kop[1][s][i] = sw[1];
+                    for (int i = 0; i < NK; ++i) kreg[i] = 0u;
+                }
+            }
+            // the raw rows are awaited here, inside the branch only window chunks take: left to the compiler the
+            // wait lands after the join and history chunks would drain their in-flight V and run copies there
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         }
-
-    load_v();
-
-    {
-        const int hbase = 0, gh = g;                         // at most 32 query heads per KV head in this layout
+        // 2. operand order: kop[T][s] = rows 32 T + l % 32, channels 16 s + 8 (l / 32)..+7
+        u32x4 kop[2][KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(kreg[8 * s + i], kreg[8 * s + 4 + i], false, false);
+                kop[0][s][i] = sw[0];
+                kop[1][s][i] = sw[1];
+            }
         // 3. scores: lane l holds head l % 32 at rows 32 T + 8 (r / 4) + 4 (l / 32) + r % 4
         f32x16 acc[2];
 #pragma unroll
@@ -314,7 +353,7 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
                 acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[T][s]),
                                                                  __builtin_bit_cast(bf16x8, qop[s]), acc[T], 0, 0, 0);
         }
-        float m = -INFINITY;
+        float m = m_run;
 #pragma unroll
         for (int T = 0; T < 2; ++T)
 #pragma unroll
@@ -323,8 +362,14 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
                 acc[T][r] = valid ? acc[T][r] * scale_log2 : -INFINITY;
                 m = fmaxf(m, acc[T][r]);
             }
-        m = fmaxf(m, __shfl_xor(m, 32));                     // row r0 is always valid, so m is finite
-        float l = 0.f;
+        m = fmaxf(m, __shfl_xor(m, 32));                     // row r0 of a chunk is always valid, so m is finite
+        if (__any(m > m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m);   // first chunk: exp2(-inf) = 0 on zeros
+            l_run *= alpha;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) o[ct] *= alpha;
+            m_run = m;
+        }
         u32x4 pa[2][2];
 #pragma unroll
         for (int T = 0; T < 2; ++T)
@@ -332,40 +377,69 @@ __global__ __launch_bounds__(64, D == 64 ? 4 : 2) void decode_step_runs_kernel(d
             for (int r = 0; r < 16; r += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(acc[T][r] - m);
                 const float p1 = __builtin_amdgcn_exp2f(acc[T][r + 1] - m);
-                l += p0 + p1;
+                l_run += p0 + p1;
                 pa[T][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
             }
-        l += __shfl_xor(l, 32);
-        if (lane < gh) {
-            float *out = c.part + (((size_t)b * c.Hq + hk * g + hbase + lane) * c.max_chunks + chunk) * part_stride(D);
-            out[D] = m;
-            out[D + 1] = l;
-        }
-        // 4. P V: heads x channels, contraction over the chunk's 64 rows in accumulator order
+        // 4. O^T += V^T P^T: channels x heads, contraction over the chunk's 64 rows in accumulator order
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            f32x16 o;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[r] = 0.f;
-            const int ch = 32 * ct + n32;
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2)
-                    o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pa[T][s2]),
-                                                                __builtin_bit_cast(bf16x8, vop[ct][T][s2]), o, 0, 0, 0);
-            // lane l holds channel 32 ct + l % 32 of heads 8 (r / 4) + 4 (l / 32) + r % 4
+                    o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[ct][T][s2]),
+                                                                    __builtin_bit_cast(bf16x8, pa[T][s2]), o[ct], 0, 0, 0);
+    };
+    for (int chunk = c_begin; chunk < c_end; chunk += 2) {
+        do_chunk(chunk, stage_a, stage_b);
+        if (chunk + 1 < c_end) do_chunk(chunk + 1, stage_b, stage_a);
+    }
+    const float l_all = l_run + __shfl_xor(l_run, 32);
+    if (NW == 1) {
+        // partial (o, m, l) of this wave's rows, merged by a second launch
+        if (n32 < g) {
+            float *out = c.part + (((size_t)b * c.Hq + hk * g + n32) * c.max_chunks + part_i) * part_stride(D);
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                if (8 * rq >= gh) break;
+            for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int h = 8 * rq + 4 * kap + r4;
-                    if (h < gh)
-                        c.part[(((size_t)b * c.Hq + hk * g + hbase + h) * c.max_chunks + chunk) * part_stride(D) + ch] =
-                            o[4 * rq + r4];
-                }
+                for (int rq = 0; rq < 4; ++rq)
+                    *(f32x4 *)(out + 32 * ct + 8 * rq + 4 * kap) =
+                        f32x4{o[ct][4 * rq], o[ct][4 * rq + 1], o[ct][4 * rq + 2], o[ct][4 * rq + 3]};
+            if (kap == 0) {
+                out[D] = m_run;
+                out[D + 1] = l_all;
             }
+        }
+    } else {
+        // the work group holds every row of the unit: its waves' (o, m, l) meet in LDS and the normalised
+        // output row of each head is written here (a wave without chunks contributes m = -inf, l = 0)
+        float *obuf = (float *)stage_a;                      // [g][D] of this wave; its staging areas are idle now
+        if (n32 < g) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq)
+                    *(f32x4 *)(obuf + n32 * D + 32 * ct + 8 * rq + 4 * kap) =
+                        f32x4{o[ct][4 * rq], o[ct][4 * rq + 1], o[ct][4 * rq + 2], o[ct][4 * rq + 3]};
+            if (kap == 0) {
+                ml_all[wave][n32][0] = m_run;
+                ml_all[wave][n32][1] = l_all;
+            }
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < g * D; e += 64 * NW) {
+            const int h = e / D;
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) M = fmaxf(M, ml_all[w][h][0]);
+            float L = 0.f, O = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float f = __builtin_amdgcn_exp2f(ml_all[w][h][0] - M);   // wave 0 always has rows: M is finite
+                L = fmaf(f, ml_all[w][h][1], L);
+                O = fmaf(f, ((const float *)stage_a_all[w])[e], O);
+            }
+            o_out[((size_t)b * c.Hq + hk * g) * D + e] = f32_to_bf16(O / L);
         }
     }
 }
@@ -381,17 +455,42 @@ void cache_fill_runs(da_cache *c, int n, const void *K, const void *V, const voi
                        (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)Khat, mask_bits, nnz, *c, n);
 }
 
-void decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, uint32_t *mask_row, int t,
-                      float scale_log2, hipStream_t s) {
-    const int units = c->B * c->Hkv;
-    const dim3 grid(t / kChunk + 1, units), block(64);
-    const size_t lds = (size_t)(kChunk + 1) * c->d * sizeof(bf16_t);
+int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,
+                     float scale_log2, hipStream_t s) {
+    const int units = c->B * c->Hkv, nchunks = t / kChunk + 1;
+    // A launch is sized so that all of its waves are resident at once (4 SIMDs per CU; the kernel's register
+    // budget allows 2 waves per SIMD at head_dim 64, 1 at 128).
+    static int cus = 0;
+    if (!cus && (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1))
+        cus = 256;
+    const int slots = c->plan_slots > 0 ? c->plan_slots : cus * (c->d == 64 ? 8 : 4);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
+    // one work group per unit whose waves split the unit's chunks and merge in LDS, if that fills at least half
+    // of the wave slots; the normalised output is written by this launch (returns 0: nothing left to merge)
+    const int nw = c->d == 64 ? 8 : 4;
+    if (c->plan_merge == 1 || (c->plan_merge < 0 && (int64_t)units * nw * 2 >= slots)) {
+        const int nc = (nchunks + nw - 1) / nw;
+        const dim3 grid(1, units), block(64 * nw);
+        if (c->d == 64)
+            hipLaunchKernelGGL((decode_step_runs_kernel<64, 8>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row,
+                               t, scale_log2, nc);
+        else
+            hipLaunchKernelGGL((decode_step_runs_kernel<128, 4>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o,
+                               mask_row, t, scale_log2, nc);
+        return 0;
+    }
+    // otherwise single-wave work groups, as few chunks per wave as keep the launch resident; partial rows
+    int nc = (int)(((int64_t)units * nchunks + slots - 1) / slots);
+    if (nc < 1) nc = 1;
+    const int nparts = (nchunks + nc - 1) / nc;
+    const dim3 grid(nparts, units), block(64);
     if (c->d == 64)
-        hipLaunchKernelGGL(decode_step_runs_kernel<64>, grid, block, lds, s, *c, (const bf16_t *)q, (const bf16_t *)k,
-                           (const bf16_t *)v, mask_row, t, scale_log2);
+        hipLaunchKernelGGL((decode_step_runs_kernel<64, 1>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row, t,
+                           scale_log2, nc);
     else
-        hipLaunchKernelGGL(decode_step_runs_kernel<128>, grid, block, lds, s, *c, (const bf16_t *)q,
-                           (const bf16_t *)k, (const bf16_t *)v, mask_row, t, scale_log2);
+        hipLaunchKernelGGL((decode_step_runs_kernel<128, 1>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row,
+                           t, scale_log2, nc);
+    return nparts;
 }
 
 void seal_chunk_runs(da_cache *c, int chunk, hipStream_t s) {

@@ -12,12 +12,14 @@ from util import check_output, rand_walk, to_dev, unpack_mask
 pytestmark = pytest.mark.gpu
 
 
-def run_decode(Q, K, V, n, steps, theta, Wd, dtype, W_prefill=16, check_every=1, scale=0.0):
+def run_decode(Q, K, V, n, steps, theta, Wd, dtype, W_prefill=16, check_every=1, scale=0.0, plan=None):
     """Prefill n rows into a cache, then `steps` decode steps; compares every check_every-th step."""
     B, Hq, _, d = Q.shape
     Hkv = K.shape[1]
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     cache = da.Cache(B, Hq, Hkv, d, n + steps, Wd, theta, tdt, scale=scale)
+    if plan is not None:
+        cache.set_launch_plan(*plan)
     st = orc.DecodeState(theta, Wd, scale=None if scale == 0.0 else scale)
     Qd, Kd, Vd = (to_dev(x, dtype) for x in (Q, K, V))
     if n > 0:
@@ -79,6 +81,17 @@ def test_decode_column_run_layout(n, steps, d, Wd, B, Hq, Hkv, theta):
     run_decode(Q, K, V, n, steps, theta, Wd, "bf16")
 
 
+@pytest.mark.parametrize("plan", [(1, 0), (0, 2), (0, 5), (1, 1)])
+@pytest.mark.parametrize("n,steps,d,Hq,Hkv", [(300, 70, 64, 4, 2), (0, 200, 64, 8, 1), (260, 130, 128, 4, 1)])
+def test_decode_launch_plans(plan, n, steps, d, Hq, Hkv):
+    """Every way of laying a step out over the GPU gives the same result: one work group per unit whose
+    waves merge on chip (with idle waves while the cache is short), or single-wave work groups that walk
+    several chunks each (2 or 5 wave slots for 2 units force up to all chunks into one wave) + merge launch."""
+    B, L = 2, n + steps
+    Q, K, V = rand_walk(41, B, Hq, L, d), rand_walk(42, B, Hkv, L, d), rand_walk(43, B, Hkv, L, d, clip=3.5)
+    run_decode(Q, K, V, n, steps, 0.2, 64, "bf16", check_every=7, plan=plan)
+
+
 def test_decode_from_empty_cache_and_dense_limits():
     B, Hq, Hkv, L, d = 1, 2, 1, 40, 64
     Q, K, V = rand_walk(14, B, Hq, L, d), rand_walk(15, B, Hkv, L, d), rand_walk(16, B, Hkv, L, d, clip=3.5)
@@ -100,6 +113,10 @@ def test_cache_state_errors():
     with pytest.raises(da.DeltaAttnError) as e:
         da.delta_attn_decode(cache, z(2), z(1), z(1))
     assert e.value.status == 4                                # cache full
+    with pytest.raises(da.DeltaAttnError):
+        cache.set_launch_plan(2, 0)
+    with pytest.raises(da.DeltaAttnError):
+        cache.set_launch_plan(0, -1)
     Q = torch.zeros(1, 2, 4, 64, dtype=torch.bfloat16, device="cuda")
     K = torch.zeros(1, 1, 4, 64, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(da.DeltaAttnError) as e:
