@@ -24,6 +24,15 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
 PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS = 78.6   # same without packed-fp32 instructions (not emitted by this build)
 
+# HBM-side bytes per launch of the dominant kernel (fetch + write), measured once with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
+# Counters cannot be read from inside this process, so other workloads report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("C5/p05/s60", "gather"): (1683.6 + 160.0) * 2 ** 20,
+    ("C5/p05/s60", "rebase"): (1100.9 + 160.0) * 2 ** 20,
+    ("C4/p05/s57", "decode"): (110.29 + 0.71) * 2 ** 20,
+}
+
 
 def outside_rows(n, W):
     """rows_out[j]: number of query rows for which key column j lies outside the exact window."""
@@ -101,7 +110,9 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
         roof["frac"] = roof["achieved"] / roof["peak"]
     es = 2
     hbm_bytes = (2 * B * Hq * n * d + 2 * B * Hkv * n * d) * es + B * Hkv * n * d / 8
-    roof.update({"traffic": None, "kernel": "prefill attention", "kernel_ms": attn_ms,
+    roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "gather" if mode == da.DA_SCORE_GATHER else "rebase")),
+                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                 "kernel": "prefill attention", "kernel_ms": attn_ms,
                  "algorithmic_sparse_gmac": sparse_macs / 1e9, "row_weighted_density": sparse_macs / max(outside_pairs * d, 1),
                  "mfma_tflops": mfma_flops / (attn_ms * 1e-3) / 1e12,
                  "mfma_frac": mfma_flops / (attn_ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
@@ -152,20 +163,24 @@ def decode_bench(args, da, wl, torch, np):
     o = torch.empty_like(qs[0])
     mrow = torch.empty((B, Hkv, d // 32), dtype=torch.int32, device="cuda")
 
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
     def run(stage_timing):
         cache.reset()
         da.delta_attn_prefill(Qp, Kp, Vp, theta, w.window, cache=cache)
         torch.cuda.synchronize()
         da.delta_attn_stage_timing_enable(stage_timing)
         t0 = time.perf_counter()
+        ev0.record()
         for i in range(steps):
             da.delta_attn_decode(cache, qs[i], ks[i], vs[i], out=o, mask_row=mrow)
+        ev1.record()
         t1 = time.perf_counter()
         torch.cuda.synchronize()
-        return time.perf_counter() - t0, t1 - t0
+        return time.perf_counter() - t0, t1 - t0, ev0.elapsed_time(ev1)
 
     run(False)
-    dt, enqueue = run(False)          # the reported rate: no per-stage events in the stream
+    dt, enqueue, dev_ms = run(False)  # the reported rate: no per-stage events in the stream
     run(True)                         # per-kernel durations from HIP events around each launch
     stages = da.delta_attn_stage_timing_read()
     da.delta_attn_stage_timing_enable(False)
@@ -178,16 +193,43 @@ def decode_bench(args, da, wl, torch, np):
     hist = t_avg - w.window
     bytes_step = units * (t_avg * d * 2 + hist * d / 8 + (nnz / units) * (hist / L) * 2 + w.window * d * 2) \
         + 2 * B * Hq * d * 2
-    chunk_ms = stages["chunk"][0] / max(stages["chunk"][1], 1)
+    # The step is one launch (work groups merge on chip), so the device time of the whole loop (one HIP event pair
+    # on the launch stream around all steps) divided by the steps is that kernel's average duration plus the launch
+    # gaps; the per-stage event pairs add about 2 us to a 24 us kernel and are reported separately.
+    chunk_ms = dev_ms / steps
     cache.close()
     return {"workload": f"{w.key()}: decode B{B} Hq{Hq} Hkv{Hkv} d{d} cached {n} + {steps} steps W_d{w.window} "
                         f"theta={theta:.6g}", "value": B * steps / dt, "unit": "tokens/s",
             "ms_per_step": dt / steps * 1e3, "host_enqueue_ms_per_step": enqueue / steps * 1e3, "s_m": s_m, "s_c": s_c,
-            "stage_ms": {k: v[0] / v[1] for k, v in stages.items() if v[1]},
-            "roofline": {"bound": "hbm", "kernel": "decode chunk", "kernel_ms": chunk_ms,
+            "stage_ms_with_event_pairs": {k: v[0] / v[1] for k, v in stages.items() if v[1]},
+            "roofline": {"bound": "hbm", "kernel": "decode step", "kernel_ms": chunk_ms,
                          "achieved": bytes_step / (chunk_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": bytes_step / (chunk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                         "frac": bytes_step / (chunk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "decode")),
+                         "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
                          "algorithmic_mb_per_step": bytes_step / 1e6}}
+
+
+def hbm_read_probe(da, torch):
+    """Streaming-read rate this GPU reaches on a buffer of the decode step's size and on 1 GiB, with the access
+    shape of the decode kernel (delta_attn_stream_read): the practical ceiling to read the decode GB/s against."""
+    out = {}
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for name, nbytes, nbuf in (("108_MiB", 108 << 20, 4), ("1_GiB", 1 << 30, 2)):
+        xs = [torch.ones(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(nbuf)]   # rotate: no cache reuse
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best, launches = float("inf"), 16   # back to back, so that host launch latency is not in the figure
+        for rep in range(4):
+            e0.record()
+            for i in range(launches):
+                da.delta_attn_stream_read(xs[i % nbuf], sink)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 1:
+                best = min(best, e0.elapsed_time(e1) / launches)
+        out[name] = {"ms": best, "GB/s": nbytes / (best * 1e-3) / 1e9}
+        del xs
+    return out
 
 
 def main():
@@ -204,6 +246,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (profiling aid for scaling FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--hbm-read-probe", action="store_true",
+                    help="only measure the streaming-read rate of this GPU (context for the decode roofline) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build is a single-GPU kernel library; run with --gpus 1\n")
@@ -216,6 +260,9 @@ def main():
         sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
         sys.exit(1)
     da.lib()
+    if args.hbm_read_probe:
+        print(json.dumps({"hbm_read_probe": hbm_read_probe(da, torch)}))
+        return
     res, (w, x, theta, dev) = prefill_bench(args, da, wl, torch, np, args.mode)
     if not args.no_other_mode:
         # the same workload through the other score mode (same results; see include/delta_attn.h)

@@ -79,6 +79,13 @@ enum { DA_STAGE_SCAN = 0, DA_STAGE_EMIT = 1, DA_STAGE_ATTN = 2, DA_STAGE_CACHE_F
 void delta_attn_stage_timing_enable(int32_t on);
 int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_stage);
 
+/* Measurement aid for the decode roofline (no part of the method): one launch that reads `bytes` (a
+ * multiple of 1024) of device memory at `src` once, with the access shape of the decode kernel's streams
+ * (single-wave work groups, 16 KiB each, 128-bit loads), and writes one word to `sink` (device, may equal
+ * nothing else in use).  Timed by the caller, it gives the streaming-read rate this GPU reaches on a buffer
+ * of that size, which is below the published HBM peak. */
+da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Eq. 5: min(floor(gamma * n), w_max), clamped to >= 1.  Host only. */
 int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);
 

@@ -17,7 +17,7 @@ DA_SCORE_GATHER, DA_SCORE_REBASE = 0, 1
 
 EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
-    "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
+    "delta_attn_stream_read", "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
     "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_set_launch_plan", "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_status_string.restype = ctypes.c_char_p
         L.delta_attn_status_string.argtypes = [ctypes.c_int]
         L.delta_attn_last_error.restype = ctypes.c_char_p
+        L.delta_attn_stream_read.restype = ctypes.c_int
+        L.delta_attn_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.delta_attn_stage_timing_enable.restype = None
         L.delta_attn_stage_timing_enable.argtypes = [i32]
         L.delta_attn_stage_timing_read.restype = i32
@@ -103,6 +105,13 @@ def delta_attn_window_from_gamma(n: int, gamma: float, w_max: int) -> int:
 
 
 STAGES = ("scan", "emit", "attn", "cache_fill", "append", "chunk", "combine")
+
+
+def delta_attn_stream_read(buf, sink):
+    """Measurement aid: one streaming read of the device tensor `buf` (byte size a multiple of 1024)."""
+    _dev(buf, "buf")
+    _check(lib().delta_attn_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()),
+           "delta_attn_stream_read")
 
 
 def delta_attn_stage_timing_enable(on: bool):

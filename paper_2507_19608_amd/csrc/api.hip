@@ -70,11 +70,45 @@ inline float score_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f
 
 }  // namespace
 
+namespace {
+typedef __attribute__((ext_vector_type(4))) uint32_t stream_u32x4;
+// streaming read: a wave sums 16 pieces of 1 KiB; the (never true) comparison keeps the loads alive
+__global__ __launch_bounds__(64) void stream_read_kernel(const stream_u32x4 *__restrict__ src, size_t pieces,
+                                                         uint32_t *__restrict__ sink) {
+    const size_t p0 = (size_t)blockIdx.x * 16;
+    stream_u32x4 acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        stream_u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const size_t p = p0 + half * 8 + u;
+            const size_t i = p * 64 + threadIdx.x;
+            v[u] = i < pieces * 64 ? src[i] : stream_u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && acc[0] == 0x7f4a7c15u && acc[1] == 0x12345678u) *sink = acc[2];
+}
+}  // namespace
+
 extern "C" {
 
 const char *delta_attn_last_error(void) { return last_error_text(); }
 
 void delta_attn_stage_timing_enable(int32_t on) { timing_enable(on != 0); }
+
+da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream) {
+    if (!src || !sink || bytes == 0 || bytes % 1024 != 0) return DA_ERR_INVALID_ARG;
+    const size_t pieces = bytes / 1024;                      // 1 KiB per wave-wide 128-bit load
+    const size_t groups = (pieces + 15) / 16;
+    if (groups > 0x7fffffffull) return DA_ERR_UNSUPPORTED;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)groups), dim3(64), 0, (hipStream_t)hip_stream,
+                       (const stream_u32x4 *)src, pieces, sink);
+    return launch_ok("stream_read") ? DA_OK : DA_ERR_HIP;
+}
 
 int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_stage) {
     if (!ms_per_stage || !calls_per_stage) return -1;
