@@ -35,7 +35,7 @@ typedef enum {
     DA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, Hq % Hkv != 0, window < 1, theta < 0 or NaN */
     DA_ERR_UNSUPPORTED = 2,   /* head_dim not a multiple of 32 or > 256, unknown dtype or mode */
     DA_ERR_WORKSPACE = 3,     /* workspace pointer null or smaller than *_workspace_bytes() */
-    DA_ERR_STATE = 4,         /* cache full, cache/params mismatch, decode on an empty cache */
+    DA_ERR_STATE = 4,         /* cache full, prefill into a non-empty cache, cache/params mismatch */
     DA_ERR_HIP = 5            /* a HIP runtime call failed */
 } da_status;
 
@@ -125,9 +125,11 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Decode cache: per (batch, KV head) the delta matrix in compact form (mask bits + surviving key
- * values), reference-key checkpoints, the current reference key, a ring of the last decode_window
- * raw keys, and V (Sec. III-A last paragraph, Sec. III-C).  All sequences of the batch advance
- * together.  Allocates device memory on the current device. */
+ * values), the reference key at the start of every 64 rows, the current reference key, a ring of
+ * the last decode_window raw keys, and V (Sec. III-A last paragraph, Sec. III-C).  All sequences of
+ * the batch advance together.  A cache may start empty (the first decoded row is then the basis
+ * row) or be filled by delta_attn_prefill.  Allocates device memory on the current device; owned
+ * by the library until delta_attn_cache_destroy. */
 da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
                                   int32_t head_dim, int32_t max_seq, int32_t decode_window, float theta,
                                   float scale, int32_t dtype);
