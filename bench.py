@@ -34,16 +34,20 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def outside_rows(n, W):
-    """rows_out[j]: number of query rows for which key column j lies outside the exact window."""
+def outside_rows(n, W, sliding=False):
+    """rows_out[j]: number of query rows for which key column j lies outside the exact window
+    (rows below the column's square, or rows i >= j + W for the band)."""
     import numpy as np
     j = np.arange(n)
+    if sliding:
+        return np.maximum(0, n - np.minimum(n, j + W))
     return np.maximum(0, n - np.minimum(n, (j // W + 1) * W))
 
 
 def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
     w = {"C5": wl.c5(args.sparsity, args.p_jump), "C3": wl.C3, "C2": wl.C2}[args.workload]
     mode = da.DA_SCORE_GATHER if mode_name == "gather" else da.DA_SCORE_REBASE
+    wmode = da.DA_WINDOW_SLIDING if args.window_mode == "sliding" else da.DA_WINDOW_BLOCK
     theta = wl.theta_for(w)
     tdt = torch.bfloat16
     if data is None:
@@ -54,13 +58,13 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
     B, Hq, n, d = Q.shape
     Hkv = K.shape[1]
     g = Hq // Hkv
-    p = da.make_params(Q, K, w.window, theta, 0.0, mode)
+    p = da.make_params(Q, K, w.window, theta, 0.0, mode, wmode)
     ws = torch.empty(da.delta_attn_prefill_workspace_bytes(p), dtype=torch.uint8, device="cuda")
     out = (torch.empty_like(Q), torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device="cuda"),
            torch.empty((B, Hkv), dtype=torch.int64, device="cuda"))
 
     def step():
-        da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out)
+        da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out, window_mode=wmode)
 
     if args.calibrate_copy:   # a plain copy of known size, to scale the profiler's byte counters
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
@@ -88,7 +92,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
     # algorithmic work of the attention kernel (dominant kernel)
     mask = out[1].cpu().numpy().view(np.uint32)
     nnz_col = np.bitwise_count(mask).sum(axis=-1).astype(np.int64)   # [B, Hkv, n]
-    rows_out = outside_rows(n, w.window)
+    rows_out = outside_rows(n, w.window, args.window_mode == "sliding")
     sparse_macs = float((nnz_col * rows_out[None, None, :]).sum()) * g
     outside_pairs = float(rows_out.sum()) * B * Hq
     causal_pairs = n * (n + 1) / 2.0 * B * Hq
@@ -110,7 +114,8 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
         roof["frac"] = roof["achieved"] / roof["peak"]
     es = 2
     hbm_bytes = (2 * B * Hq * n * d + 2 * B * Hkv * n * d) * es + B * Hkv * n * d / 8
-    roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "gather" if mode == da.DA_SCORE_GATHER else "rebase")),
+    roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "gather" if mode == da.DA_SCORE_GATHER else "rebase"))
+                 if args.window_mode == "block" else None,
                  "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
                  "kernel": "prefill attention", "kernel_ms": attn_ms,
                  "algorithmic_sparse_gmac": sparse_macs / 1e9, "row_weighted_density": sparse_macs / max(outside_pairs * d, 1),
@@ -123,7 +128,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.key()}: prefill B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} W{w.window} theta={theta:.6g} "
-                               f"p_jump={w.p_jump}", "score_mode": mode_name, "s_m": s_m, "s_c": s_c},
+                               f"p_jump={w.p_jump}", "score_mode": mode_name, "window_mode": args.window_mode, "s_m": s_m, "s_c": s_c},
         "stage_ms": {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items() if v[1]},
         "roofline": roof,
     }
@@ -241,6 +246,9 @@ def main():
     ap.add_argument("--mode", default="gather", choices=["gather", "rebase"])
     ap.add_argument("--sparsity", type=float, default=0.60, help="C5 only: 0, 0.4, 0.6 or 0.8 (tuned theta)")
     ap.add_argument("--p-jump", type=float, default=0.05, help="C5 only: 0.01, 0.05 or 0.20")
+    ap.add_argument("--window-mode", default="block", choices=["block", "sliding"],
+                    help="exact region of the prefill: squares of side W on the diagonal (the paper's prefill stage, "
+                         "the headline) or the band of the W newest keys")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

@@ -48,14 +48,24 @@ typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
  *                    score is the dense product q . k_hat(j) (no multiply is skipped). */
 typedef enum { DA_SCORE_GATHER = 0, DA_SCORE_REBASE = 1 } da_score_mode;
 
+/* Shape of the prefill's exact region (Sec. III-B).
+ *   DA_WINDOW_BLOCK    squares of side W along the diagonal: (i, j) exact iff j <= i and
+ *                      floor(i / W) == floor(j / W) - the prefill stage as the paper draws it and
+ *                      the region whose area Eq. 6 uses.
+ *   DA_WINDOW_SLIDING  a band: (i, j) exact iff 0 <= i - j < W - the decode stage's rule applied to
+ *                      every prefill row, so prefill row t equals the decode step at position t with
+ *                      decode_window W. */
+typedef enum { DA_WINDOW_BLOCK = 0, DA_WINDOW_SLIDING = 1 } da_window_mode;
+
 typedef struct {
     int32_t batch, n_q_heads, n_kv_heads, head_dim, seq_len;
-    int32_t window;     /* W >= 1: side of the exact squares on the diagonal (Sec. III-B);
+    int32_t window;     /* W >= 1: side of the exact squares on the diagonal / width of the band;
                            W >= seq_len gives dense causal attention */
     float theta;        /* >= 0 (may be +inf) */
     float scale;        /* score scale; 0 selects 1/sqrt(head_dim) (Eq. 1) */
     int32_t dtype;      /* da_dtype of Q, K, V, O */
     int32_t score_mode; /* da_score_mode */
+    int32_t window_mode; /* da_window_mode */
 } da_prefill_params;
 
 typedef struct da_cache da_cache;   /* decode-time cache (Sec. III-C), opaque */

@@ -131,8 +131,10 @@ def window_from_gamma(n, gamma, w_max):
     return max(1, min(int(math.floor(gamma * n)), int(w_max)))
 
 
-def prefill(Q, K, V, theta, window, scale=None, rows=None, q_heads=None):
+def prefill(Q, K, V, theta, window, scale=None, rows=None, q_heads=None, window_mode=0):
     """Whole-layer prefill.  Q [B, Hq, n, d], K/V [B, Hkv, n, d] (float64).
+    window_mode 0: exact squares of side `window` on the diagonal (Sec. III-B prefill stage);
+    1: exact band of the `window` newest keys per row (the decode stage's rule, row by row).
 
     Returns dict(O [B, Hq, r, d], mask [B, Hkv, n, d] uint8, nnz [B, Hkv] int64,
     s_m, s_c, knife).  rows=(r0, r1) restricts the output rows; q_heads restricts
@@ -158,7 +160,7 @@ def prefill(Q, K, V, theta, window, scale=None, rows=None, q_heads=None):
             for h in range(hk * g, (hk + 1) * g):
                 if q_heads is not None and h not in q_heads:
                     continue
-                O[b, h] = hybrid_rows(Q[b, h], K[b, hk], V[b, hk], dK, window, 0, scale, 0, (r0, r1))
+                O[b, h] = hybrid_rows(Q[b, h], K[b, hk], V[b, hk], dK, window, int(window_mode), scale, 0, (r0, r1))
     s_m, s_c = sparsity(int(nnz.sum()), n, d, B * Hkv, window)
     return dict(O=O, mask=mask, nnz=nnz, s_m=s_m, s_c=s_c, knife=knife)
 

@@ -14,6 +14,7 @@ LIB_PATH = os.environ.get("DELTA_ATTN_LIB", os.path.join(HERE, "libdelta_attn.so
 DA_OK = 0
 DA_F32, DA_BF16 = 0, 1
 DA_SCORE_GATHER, DA_SCORE_REBASE = 0, 1
+DA_WINDOW_BLOCK, DA_WINDOW_SLIDING = 0, 1
 
 EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
@@ -29,7 +30,7 @@ class PrefillParams(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("theta", ctypes.c_float), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32),
-                ("score_mode", ctypes.c_int32)]
+                ("score_mode", ctypes.c_int32), ("window_mode", ctypes.c_int32)]
 
 
 class DeltaAttnError(RuntimeError):
@@ -161,10 +162,11 @@ def _dev(t, name):
     return t
 
 
-def make_params(Q, K, window: int, theta: float, scale: float = 0.0, score_mode: int = DA_SCORE_GATHER):
+def make_params(Q, K, window: int, theta: float, scale: float = 0.0, score_mode: int = DA_SCORE_GATHER,
+                window_mode: int = DA_WINDOW_BLOCK):
     B, Hq, n, d = Q.shape
     return PrefillParams(B, Hq, K.shape[1], d, n, int(window), float(theta), float(scale), _dtype_code(Q),
-                         int(score_mode))
+                         int(score_mode), int(window_mode))
 
 
 def delta_attn_prefill_workspace_bytes(params: PrefillParams) -> int:
@@ -260,7 +262,7 @@ def delta_attn_delta_scan(K, theta: float, want_khat: bool = False):
 
 
 def delta_attn_prefill(Q, K, V, theta: float, window: int, scale: float = 0.0, score_mode: int = DA_SCORE_GATHER,
-                       cache: Optional[Cache] = None, workspace=None, out=None):
+                       cache: Optional[Cache] = None, workspace=None, out=None, window_mode: int = DA_WINDOW_BLOCK):
     """Returns (O, mask_bits int32 [B, Hkv, n, d/32], nnz int64 [B, Hkv]).  Buffers may be passed in
     (workspace: uint8 tensor, out: (O, mask_bits, nnz)) so a timing loop allocates nothing."""
     torch = _torch()
@@ -269,7 +271,7 @@ def delta_attn_prefill(Q, K, V, theta: float, window: int, scale: float = 0.0, s
     if K.shape != V.shape or Q.shape[0] != K.shape[0] or Q.shape[2:] != K.shape[2:] or Q.dtype != K.dtype \
             or K.dtype != V.dtype:
         raise ValueError("Q/K/V shapes or dtypes disagree")
-    p = make_params(Q, K, window, theta, scale, score_mode)
+    p = make_params(Q, K, window, theta, scale, score_mode, window_mode)
     need = delta_attn_prefill_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=Q.device)

@@ -32,6 +32,7 @@ da_status check_params(const da_prefill_params *p) {
     if (p->head_dim % 32 != 0 || p->head_dim > 256) return DA_ERR_UNSUPPORTED;
     if (p->dtype != DA_F32 && p->dtype != DA_BF16) return DA_ERR_UNSUPPORTED;
     if (p->score_mode != DA_SCORE_GATHER && p->score_mode != DA_SCORE_REBASE) return DA_ERR_UNSUPPORTED;
+    if (p->window_mode != DA_WINDOW_BLOCK && p->window_mode != DA_WINDOW_SLIDING) return DA_ERR_UNSUPPORTED;
     if ((int64_t)p->batch * p->n_q_heads > 65535 * 64) return DA_ERR_UNSUPPORTED;
     return DA_OK;
 }
@@ -207,6 +208,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.W = p->window;
     a.scale_log2 = score_scale(p->scale, p->head_dim) * 1.4426950408889634f;
     a.rebase = p->score_mode == DA_SCORE_REBASE;
+    a.sliding = p->window_mode == DA_WINDOW_SLIDING;
     a.Q = Q;
     a.K = K;
     a.V = V;

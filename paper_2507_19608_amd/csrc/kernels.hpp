@@ -23,6 +23,7 @@ struct PrefillArgs {
     int B, Hq, Hkv, d, n, W;
     float scale_log2;     // score scale * log2(e)
     int rebase;           // 1: outside scores from q . k_hat instead of the entry lists
+    int sliding;          // 1: exact region is the band i - j < W instead of squares of side W
     const void *Q, *K, *V, *Khat;
     void *O;
     const void *ents;     // EntryChunk lists, column (unit, j) at chunk (unit * n + j) * d / 8

@@ -20,7 +20,7 @@ struct KArgs {
     T *__restrict__ O;
     const EntryChunk *__restrict__ ents;
     const uint32_t *__restrict__ counts;
-    int Hq, Hkv, n, W, rebase;
+    int Hq, Hkv, n, W, rebase, sliding;
     float scale_log2;
 };
 
@@ -47,9 +47,11 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
     __syncthreads();
 
     const int i_last = min(n - 1, tile * 64 + 63);          // last row of the tile
-    const int win_first = ((tile * 64) / W) * W;            // window start of the tile's first row
-    const int win_last = (i_last / W) * W;                  // window start of its last row
-    const int my_win = valid ? (i / W) * W : 0;
+    // first exact column of row r: start of its square, or of its band (monotone in r either way)
+    auto win_start = [&](int r) { return a.sliding ? max(r - W + 1, 0) : (r / W) * W; };
+    const int win_first = win_start(tile * 64);             // window start of the tile's first row
+    const int win_last = win_start(i_last);                 // window start of its last row
+    const int my_win = valid ? win_start(i) : 0;
 
     float o[D];
 #pragma unroll
@@ -135,6 +137,7 @@ static void launch_one(const PrefillArgs &p, hipStream_t s) {
     a.Hkv = p.Hkv;
     a.n = p.n;
     a.W = p.W;
+    a.sliding = p.sliding;
     a.rebase = p.rebase;
     a.scale_log2 = p.scale_log2;
     const size_t lds = (size_t)D * 64 * sizeof(float);

@@ -2,13 +2,13 @@
 //
 // Work group = 512 threads (8 waves) on 256 "score rows": RT consecutive query rows x GH query heads of
 // one KV head (they share K, V and the delta matrix).  Key columns are walked left to right in blocks
-// of 32.
+// of 32.  A row's window is its square of side W on the diagonal, or the band of the W newest keys.
 //
 //   far blocks   (every row of the tile has the column outside its window): Eq. 4 as written.  Wave w
-//                takes columns w, w+8, w+16, w+24 of the block; a lane owns 4 score rows and adds
+//                takes columns 4w .. 4w+3 of the block; a lane owns 4 score rows and adds
 //                q[c] * delta for each surviving (channel, delta) entry of the column.  The entry list is
-//                wave-uniform and arrives through scalar loads; q comes from a transposed fp16 copy of the
-//                Q tile in LDS (one 8-byte read feeds 4 multiply-adds).  The per-column updates u are
+//                wave-uniform and arrives as uniform LDS reads from a per-wave ring; q comes from a transposed
+//                fp16 copy of the Q tile in LDS (one 8-byte read feeds 4 multiply-adds).  The per-column updates u are
 //                exchanged through LDS; the owner of a score row adds them up in column order (its running
 //                Eq. 4 score).
 //   near blocks  (some row has the column inside its window): exact scores K Q^T on the matrix cores;
@@ -48,7 +48,7 @@ struct MfmaArgs {
     bf16_t *__restrict__ O;
     const EntryChunk *__restrict__ ents;
     const uint8_t *__restrict__ nch8;
-    int Hq, Hkv, n, n_pad, W, rebase;
+    int Hq, Hkv, n, n_pad, W, rebase, sliding;
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     float scale_log2;
 };
@@ -142,7 +142,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int my_hh = my_sr / RT, my_r = my_sr - my_hh * RT;
     const int my_i = i0 + my_r;
     const bool my_valid = my_i < n;
-    const int my_win = (min(my_i, n - 1) / W) * W;
+    // first exact column of row r: start of its square, or of its band (monotone in r either way)
+    auto win_start = [&](int r) { return a.sliding ? max(r - W + 1, 0) : (r / W) * W; };
+    const int my_win = win_start(min(my_i, n - 1));
     const bf16_t *my_q = q_row_ptr(my_sr);
 
     constexpr int KS = D / 16;     // k-steps of Q K^T
@@ -155,8 +157,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         for (int r = 0; r < 16; ++r) oacc[mt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f, r_run = 0.f;
 
-    const int win_first = (i0 / W) * W;
-    const bool aligned = (win_first % kTB == 0) && (i0 / W == i_last / W);
+    const int win_first = win_start(i0);         // smallest window start of the tile's rows
+    const int win_last = win_start(i_last);      // largest
+    const bool aligned = (win_first % kTB == 0) && (win_first == win_last);
     const int far_blocks = a.rebase ? 0 : win_first / kTB;
     const int nblocks = i_last / kTB + 1;
 
@@ -422,9 +425,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[r] = sk[r];
             }
-            if (!aligned && first_src(jb) == Kp) {
-                // the tile straddles window squares: exact score inside the row's own window, K_hat score
-                // (telescoped Eq. 4) left of it
+            if (!aligned && first_src(jb) == Kp && jb < win_last) {
+                // some row has part of the block left of its window: exact score inside the row's own
+                // window, K_hat score (telescoped Eq. 4) left of it
                 const f32x16 sh = score_tile(base + kTileBytes);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -545,6 +548,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.n_pad = n_pad;
     a.W = p.W;
     a.rebase = p.rebase;
+    a.sliding = p.sliding;
     const int g = p.Hq / p.Hkv;
     a.GH = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
     a.RT = kRows / a.GH;

@@ -51,7 +51,7 @@ def test_workspace_size_and_argument_checks():
     rows = 2 * 128
     assert need >= rows * 64 * 2 + rows * 64 * 8 + rows * 4
     for bad in (dict(n_q_heads=3), dict(window=0), dict(theta=-1.0), dict(theta=float("nan")), dict(seq_len=0),
-                dict(head_dim=48), dict(head_dim=512), dict(dtype=7), dict(score_mode=5)):
+                dict(head_dim=48), dict(head_dim=512), dict(dtype=7), dict(score_mode=5), dict(window_mode=2)):
         assert binding.delta_attn_prefill_workspace_bytes(_params(**bad)) == 0, bad
     # invalid arguments are rejected before anything touches the GPU
     st = L.delta_attn_prefill(ctypes.byref(_params(n_q_heads=3)), 1, 1, 1, 1, 1, 1, None, 1, 1 << 40, None)

@@ -325,6 +325,21 @@ def test_decode_matches_brute_force_and_masks_match_prefill(oracle):
     assert (whole["nnz"] == st.nnz()).all()
 
 
+def test_sliding_window_prefill_rows_are_decode_steps(oracle):
+    """The band reading of the prefill window: row t of a sliding-window prefill is, by definition, the
+    decode step at position t with the same window; checked row by row against the Eq. 1-4 loops."""
+    Q, K, V = rand_qkv(21, 1, 1, 11, 4)
+    for W, theta in [(1, 0.3), (3, 0.35), (4, 0.0), (20, 0.5)]:
+        r = oracle.prefill(Q[None], K[None], V[None], theta, W, window_mode=1)
+        for t in range(11):
+            ref = brute_force_decode_row(Q[0, t].tolist(), K[0, :t + 1].tolist(), V[0, :t + 1].tolist(), theta, W)
+            assert np.abs(r["O"][0, 0, t] - ref).max() < 1e-12
+    # and it differs from the squares reading wherever a row's band crosses a square boundary
+    a = oracle.prefill(Q[None], K[None], V[None], 0.35, 3, window_mode=0)["O"]
+    b = oracle.prefill(Q[None], K[None], V[None], 0.35, 3, window_mode=1)["O"]
+    assert np.abs(a - b).max() > 1e-6 and np.abs(a[0, 0, :3] - b[0, 0, :3]).max() < 1e-15
+
+
 def test_decode_window_covering_history_is_dense(oracle):
     Q, K, V = rand_qkv(14, 2, 1, 30, 8)
     for theta, Wd in [(0.0, 2), (0.6, 30), (0.6, 64)]:

@@ -14,12 +14,13 @@ pytestmark = pytest.mark.gpu
 MODES = [da.DA_SCORE_GATHER, da.DA_SCORE_REBASE]
 
 
-def run_case(Q, K, V, theta, W, dtype, mode, rows=None, q_heads=None, scale=0.0):
+def run_case(Q, K, V, theta, W, dtype, mode, rows=None, q_heads=None, scale=0.0, window_mode=0):
     d = Q.shape[-1]
     Og, maskg, nnzg = da.delta_attn_prefill(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), theta, W,
-                                            scale=scale, score_mode=mode)
+                                            scale=scale, score_mode=mode, window_mode=window_mode)
     torch.cuda.synchronize()
-    ref = orc.prefill(Q, K, V, theta, W, scale=None if scale == 0.0 else scale, rows=rows, q_heads=q_heads)
+    ref = orc.prefill(Q, K, V, theta, W, scale=None if scale == 0.0 else scale, rows=rows, q_heads=q_heads,
+                      window_mode=window_mode)
     assert ref["knife"] == 0
     assert (unpack_mask(maskg, d) == ref["mask"]).all()
     assert (nnzg.cpu().numpy() == ref["nnz"]).all()
@@ -55,6 +56,41 @@ def test_small_shapes_bf16(mode, n, d, W, B, Hq, Hkv, theta):
 
 
 @pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n,d,W,B,Hq,Hkv,theta,dtype", [
+    (333, 64, 48, 2, 4, 2, 0.2, "bf16"),     # band narrower than a row tile, ragged tail
+    (200, 128, 5, 1, 4, 1, 0.15, "bf16"),    # the paper's small windows
+    (300, 64, 64, 1, 8, 1, 0.2, "bf16"),     # band = one key block
+    (260, 128, 1, 1, 2, 2, 0.25, "bf16"),    # W = 1: only the diagonal is exact
+    (150, 64, 1000, 1, 2, 1, 0.3, "bf16"),   # band covers everything: dense attention
+    (130, 96, 10, 1, 3, 1, 0.25, "bf16"),    # vector-ALU kernel
+    (120, 32, 7, 1, 1, 1, 0.05, "f32"),
+])
+def test_sliding_window_prefill(mode, n, d, W, B, Hq, Hkv, theta, dtype):
+    """The band reading of the prefill window (DA_WINDOW_SLIDING) against the oracle's."""
+    step = 0.05 if dtype == "f32" else 0.15
+    Q = rand_walk(51, B, Hq, n, d, dtype)
+    K = rand_walk(52, B, Hkv, n, d, dtype, step)
+    V = rand_walk(53, B, Hkv, n, d, dtype, clip=3.5)
+    run_case(Q, K, V, theta, W, dtype, mode, window_mode=da.DA_WINDOW_SLIDING)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_sliding_prefill_rows_equal_decode_steps(mode):
+    """Two separate GPU paths, one definition: row t of a sliding-window prefill is the decode step at
+    position t with decode_window W (Sec. III-B decode stage); both within tolerance of the oracle,
+    hence within twice the tolerance of each other, at every position."""
+    B, Hq, Hkv, n, d, W, theta = 1, 4, 1, 230, 64, 64, 0.2
+    Q, K, V = rand_walk(61, B, Hq, n, d), rand_walk(62, B, Hkv, n, d), rand_walk(63, B, Hkv, n, d, clip=3.5)
+    Qd, Kd, Vd = (to_dev(x, "bf16") for x in (Q, K, V))
+    O, _, _ = da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=da.DA_WINDOW_SLIDING)
+    cache = da.Cache(B, Hq, Hkv, d, n, W, theta, torch.bfloat16)
+    for t in range(n):
+        o, _ = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        assert (o.float() - O[:, :, t].float()).abs().max().item() <= 4e-2, t
+    cache.close()
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("n,d,W,theta", [(300, 64, 32, 0.1), (150, 128, 50, 0.05)])
 def test_small_shapes_fp32(mode, n, d, W, theta):
     Q = rand_walk(4, 1, 2, n, d, "f32")
@@ -85,16 +121,16 @@ def test_c2_llama_shape_full(mode):
     run_case(x["Q"], x["K"], x["V"], wl.theta_for(w), w.window, w.dtype, mode)
 
 
-def _sampled(w, mode, row_ranges, heads):
+def _sampled(w, mode, row_ranges, heads, window_mode=0):
     x = wl.generate(w)
     d = w.head_dim
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     theta = wl.theta_for(w)
-    Og, maskg, nnzg = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+    Og, maskg, nnzg = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode, window_mode=window_mode)
     torch.cuda.synchronize()
     first = True
     for rows in row_ranges:
-        ref = orc.prefill(x["Q"], x["K"], x["V"], theta, w.window, rows=rows, q_heads=heads)
+        ref = orc.prefill(x["Q"], x["K"], x["V"], theta, w.window, rows=rows, q_heads=heads, window_mode=window_mode)
         if first:   # masks of every unit, all rows
             assert (unpack_mask(maskg, d) == ref["mask"]).all()
             assert (nnzg.cpu().numpy() == ref["nnz"]).all()
@@ -108,6 +144,11 @@ def _sampled(w, mode, row_ranges, heads):
 @pytest.mark.parametrize("mode", MODES)
 def test_c3_bitnet_shape_sampled(mode):
     _sampled(wl.C3, mode, [(0, 40), (2030, 2070), (4064, 4096)], [0, 7, 19])
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_c3_sliding_window_sampled(mode):
+    _sampled(wl.C3, mode, [(200, 230), (2040, 2060), (4070, 4096)], [1, 18], window_mode=da.DA_WINDOW_SLIDING)
 
 
 @pytest.mark.parametrize("mode", MODES)
