@@ -215,6 +215,28 @@ def decode_bench(args, da, wl, torch, np):
                          "algorithmic_mb_per_step": bytes_step / 1e6}}
 
 
+def c5_sweep(args, da, wl, torch, np):
+    """The 12-point C5 sweep (threshold for S_m ~ 0, 0.4, 0.6, 0.8 x jump rate 1, 5, 20 %), both score modes."""
+    rows = []
+    for p_jump in (0.01, 0.05, 0.20):
+        for sp in (0.0, 0.40, 0.60, 0.80):
+            args.sparsity, args.p_jump = sp, p_jump
+            r, (w, x, theta, dev) = prefill_bench(args, da, wl, torch, np, "gather")
+            r2, _ = prefill_bench(args, da, wl, torch, np, "rebase", data=(x, dev))
+            rows.append({"workload": w.key(), "theta": theta, "s_m": r["config"]["s_m"],
+                         "row_weighted_density": r["roofline"]["row_weighted_density"],
+                         "sparse_gmac": r["roofline"]["algorithmic_sparse_gmac"],
+                         "gather_attn_ms": r["roofline"]["kernel_ms"], "gather_tokens_per_s": r["value"],
+                         "gather_alu_tflops": r["roofline"]["achieved"],
+                         "rebase_attn_ms": r2["roofline"]["kernel_ms"], "rebase_tokens_per_s": r2["value"],
+                         "rebase_mfma_frac": r2["roofline"]["frac"]})
+            sys.stderr.write(json.dumps(rows[-1]) + "\n")
+            sys.stderr.flush()
+            del x, dev
+            torch.cuda.empty_cache()
+    return rows
+
+
 def hbm_read_probe(da, torch):
     """Streaming-read rate this GPU reaches on a buffer of the decode step's size and on 1 GiB, with the access
     shape of the decode kernel (delta_attn_stream_read): the practical ceiling to read the decode GB/s against."""
@@ -254,6 +276,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (profiling aid for scaling FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="only run the 12-point C5 sweep (threshold x jump rate), both score modes, and exit")
     ap.add_argument("--hbm-read-probe", action="store_true",
                     help="only measure the streaming-read rate of this GPU (context for the decode roofline) and exit")
     args = ap.parse_args()
@@ -270,6 +294,10 @@ def main():
     da.lib()
     if args.hbm_read_probe:
         print(json.dumps({"hbm_read_probe": hbm_read_probe(da, torch)}))
+        return
+    if args.sweep:
+        print(json.dumps({"c5_sweep": c5_sweep(args, da, wl, torch, np), "steps": args.steps, "warmup": args.warmup,
+                          "window_mode": args.window_mode}))
         return
     res, (w, x, theta, dev) = prefill_bench(args, da, wl, torch, np, args.mode)
     if not args.no_other_mode:
