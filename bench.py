@@ -44,8 +44,8 @@ def outside_rows(n, W, sliding=False):
     return np.maximum(0, n - np.minimum(n, (j // W + 1) * W))
 
 
-def prefill_bench(args, da, wl, torch, np, mode_name, data=None):
-    w = {"C5": wl.c5(args.sparsity, args.p_jump), "C3": wl.C3, "C2": wl.C2}[args.workload]
+def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
+    w = workload or {"C5": wl.c5(args.sparsity, args.p_jump), "C3": wl.C3, "C2": wl.C2}[args.workload]
     mode = da.DA_SCORE_GATHER if mode_name == "gather" else da.DA_SCORE_REBASE
     wmode = da.DA_WINDOW_SLIDING if args.window_mode == "sliding" else da.DA_WINDOW_BLOCK
     theta = wl.theta_for(w)
@@ -237,6 +237,27 @@ def c5_sweep(args, da, wl, torch, np):
     return rows
 
 
+def eq5_sweep(args, da, wl, torch, np):
+    """Prompt lengths 64 .. 8192 with the window of Eq. 5 (gamma as given, W_max = 512): the C5 head shape,
+    generator and threshold at every length (the paper's own regime is the short end, windows of 2 - 10 keys)."""
+    import dataclasses
+    base = wl.c5(0.60, 0.05)
+    theta = wl.theta_for(base)
+    rows = []
+    for n in (64, 128, 256, 512, 1024, 2048, 4096, 8192):
+        W = da.delta_attn_window_from_gamma(n, args.gamma, 512)
+        w = dataclasses.replace(base, seq_len=n, window=W, theta=theta, target_sparsity=None)
+        r, (_, x, _, dev) = prefill_bench(args, da, wl, torch, np, "gather", workload=w)
+        r2, _ = prefill_bench(args, da, wl, torch, np, "rebase", data=(x, dev), workload=w)
+        rows.append({"n": n, "window": W, "s_m": r["config"]["s_m"], "s_c": r["config"]["s_c"],
+                     "gather_ms_per_step": r["ms_per_step"], "gather_tokens_per_s": r["value"],
+                     "rebase_ms_per_step": r2["ms_per_step"], "rebase_tokens_per_s": r2["value"]})
+        sys.stderr.write(json.dumps(rows[-1]) + "\n")
+        sys.stderr.flush()
+        del x, dev
+    return rows
+
+
 def hbm_read_probe(da, torch):
     """Streaming-read rate this GPU reaches on a buffer of the decode step's size and on 1 GiB, with the access
     shape of the decode kernel (delta_attn_stream_read): the practical ceiling to read the decode GB/s against."""
@@ -276,6 +297,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (profiling aid for scaling FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--eq5-sweep", action="store_true",
+                    help="only run prompt lengths 64..8192 with the window of Eq. 5 (see --gamma) and exit")
+    ap.add_argument("--gamma", type=float, default=0.05, help="Eq. 5 scaling factor for --eq5-sweep")
     ap.add_argument("--sweep", action="store_true",
                     help="only run the 12-point C5 sweep (threshold x jump rate), both score modes, and exit")
     ap.add_argument("--hbm-read-probe", action="store_true",
@@ -294,6 +318,10 @@ def main():
     da.lib()
     if args.hbm_read_probe:
         print(json.dumps({"hbm_read_probe": hbm_read_probe(da, torch)}))
+        return
+    if args.eq5_sweep:
+        print(json.dumps({"eq5_sweep": eq5_sweep(args, da, wl, torch, np), "gamma": args.gamma, "w_max": 512,
+                          "steps": args.steps, "warmup": args.warmup, "window_mode": args.window_mode}))
         return
     if args.sweep:
         print(json.dumps({"c5_sweep": c5_sweep(args, da, wl, torch, np), "steps": args.steps, "warmup": args.warmup,
