@@ -63,8 +63,21 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     out = (torch.empty_like(Q), torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device="cuda"),
            torch.empty((B, Hkv), dtype=torch.int64, device="cuda"))
 
+    pieces = max(1, args.chunks)
+    if pieces > 1:   # chunked prefill onto a growing cache: same rows, same results, `pieces` calls per step
+        cache = da.Cache(B, Hq, Hkv, d, n, max(w.window, 64), theta, tdt)
+        cuts = [n * i // pieces for i in range(pieces + 1)]
+        parts = [tuple(t[:, :, cuts[i]:cuts[i + 1]].contiguous() for t in (Q, K, V)) for i in range(pieces)]
+
     def step():
-        da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out, window_mode=wmode)
+        if pieces == 1:
+            da.delta_attn_prefill(Q, K, V, theta, w.window, score_mode=mode, workspace=ws, out=out, window_mode=wmode)
+            return
+        cache.reset()
+        for q_, k_, v_ in parts:
+            o_, _, nz_ = da.delta_attn_prefill_append(cache, q_, k_, v_, theta, w.window, score_mode=mode,
+                                                      window_mode=wmode)
+        out[2].copy_(cache.nnz())
 
     if args.calibrate_copy:   # a plain copy of known size, to scale the profiler's byte counters
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
@@ -90,14 +103,14 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     s_m, s_c = da.delta_attn_sparsity(out[2], n, d, w.window)
 
     # algorithmic work of the attention kernel (dominant kernel)
-    mask = out[1].cpu().numpy().view(np.uint32)
+    mask = (out[1] if pieces == 1 else cache.mask_rows()).cpu().numpy().view(np.uint32)
     nnz_col = np.bitwise_count(mask).sum(axis=-1).astype(np.int64)   # [B, Hkv, n]
     rows_out = outside_rows(n, w.window, args.window_mode == "sliding")
     sparse_macs = float((nnz_col * rows_out[None, None, :]).sum()) * g
     outside_pairs = float(rows_out.sum()) * B * Hq
     causal_pairs = n * (n + 1) / 2.0 * B * Hq
     window_pairs = causal_pairs - outside_pairs
-    attn_ms = stages["attn"][0] / max(stages["attn"][1], 1)
+    attn_ms = stages["attn"][0] / args.steps      # per step: one launch, or one per piece
     if mode == da.DA_SCORE_GATHER:
         alu_flops = 2.0 * sparse_macs
         mfma_flops = 2.0 * (window_pairs + causal_pairs) * d
@@ -115,7 +128,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     es = 2
     hbm_bytes = (2 * B * Hq * n * d + 2 * B * Hkv * n * d) * es + B * Hkv * n * d / 8
     roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "gather" if mode == da.DA_SCORE_GATHER else "rebase"))
-                 if args.window_mode == "block" else None,
+                 if args.window_mode == "block" and pieces == 1 else None,
                  "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
                  "kernel": "prefill attention", "kernel_ms": attn_ms,
                  "algorithmic_sparse_gmac": sparse_macs / 1e9, "row_weighted_density": sparse_macs / max(outside_pairs * d, 1),
@@ -128,7 +141,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.key()}: prefill B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} W{w.window} theta={theta:.6g} "
-                               f"p_jump={w.p_jump}", "score_mode": mode_name, "window_mode": args.window_mode, "s_m": s_m, "s_c": s_c},
+                               f"p_jump={w.p_jump}", "score_mode": mode_name, "window_mode": args.window_mode, "pieces": pieces, "s_m": s_m, "s_c": s_c},
         "stage_ms": {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items() if v[1]},
         "roofline": roof,
     }
@@ -292,6 +305,8 @@ def main():
     ap.add_argument("--window-mode", default="block", choices=["block", "sliding"],
                     help="exact region of the prefill: squares of side W on the diagonal (the paper's prefill stage, "
                          "the headline) or the band of the W newest keys")
+    ap.add_argument("--chunks", type=int, default=1,
+                    help="prefill the sequence in this many equal pieces onto a growing cache (delta_attn_prefill_append)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

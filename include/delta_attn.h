@@ -134,6 +134,25 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
                              void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Chunked prefill (Sec. III-C: the cache built so far is carried on): the m = p->seq_len rows of Q, K, V
+ * are positions t0 .. t0 + m - 1 of a sequence whose first t0 rows the cache holds (t0 = cache length; 0
+ * is allowed).  The delta rows of the new keys continue from the cache's reference key (Eq. 2-3), the new
+ * query rows attend over all t0 + m keys with the window squares anchored at position 0 (or the band, by
+ * p->window_mode), exactly as rows t0 .. t0 + m - 1 of one prefill over the whole sequence would, and the
+ * new rows are appended to the cache.
+ *   Q, O [B, Hq, m, d];  K, V [B, Hkv, m, d];  mask_bits [B, Hkv, m, d/32], nnz [B, Hkv]: the new rows only
+ *   cache     bf16, head_dim 64 or 128, decode_window >= 64 (and >= p->window unless the cache is empty:
+ *             the exact scores against cached keys are taken from the cache's ring of raw keys),
+ *             at most 32 query heads per KV head; otherwise DA_ERR_UNSUPPORTED
+ *   workspace device scratch of at least delta_attn_prefill_append_workspace_bytes(p, cache), which
+ *             depends on the cache length at the time of the call (0 if the arguments are invalid)
+ */
+size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache);
+da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, const void *K, const void *V,
+                                    void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Decode cache: per (batch, KV head) the delta matrix in compact form (mask bits + surviving key
  * values), the reference key at the start of every 64 rows, the current reference key, a ring of
  * the last decode_window raw keys, and V (Sec. III-A last paragraph, Sec. III-C).  All sequences of

@@ -20,7 +20,7 @@ EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
     "delta_attn_stream_read", "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
-    "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
+    "delta_attn_prefill_append_workspace_bytes", "delta_attn_prefill_append", "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_set_launch_plan", "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
     "delta_attn_sparsity",
 ]
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_delta_scan.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.delta_attn_prefill.restype = ctypes.c_int
         L.delta_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.delta_attn_prefill_append_workspace_bytes.restype = ctypes.c_size_t
+        L.delta_attn_prefill_append_workspace_bytes.argtypes = [pp, vp]
+        L.delta_attn_prefill_append.restype = ctypes.c_int
+        L.delta_attn_prefill_append.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.delta_attn_cache_create.restype = ctypes.c_int
         L.delta_attn_cache_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i32, i32, f32, f32, i32]
         L.delta_attn_cache_destroy.restype = ctypes.c_int
@@ -286,6 +290,33 @@ def delta_attn_prefill(Q, K, V, theta: float, window: int, scale: float = 0.0, s
                                   mask.data_ptr(), nnz.data_ptr(), None if cache is None else cache.handle,
                                   workspace.data_ptr(), workspace.numel(), _stream())
     _check(st, "delta_attn_prefill")
+    return O, mask, nnz
+
+
+def delta_attn_prefill_append(cache: Cache, Q, K, V, theta: float, window: int, scale: float = 0.0,
+                              score_mode: int = DA_SCORE_GATHER, window_mode: int = DA_WINDOW_BLOCK):
+    """Chunked prefill: the rows of Q, K, V continue the sequence the cache holds.  Returns
+    (O, mask_bits int32 [B, Hkv, m, d/32], nnz int64 [B, Hkv]) of the new rows; the cache is extended."""
+    torch = _torch()
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
+        _dev(t, name)
+    if K.shape != V.shape or Q.shape[0] != K.shape[0] or Q.shape[2:] != K.shape[2:] or Q.dtype != K.dtype \
+            or K.dtype != V.dtype:
+        raise ValueError("Q/K/V shapes or dtypes disagree")
+    p = make_params(Q, K, window, theta, scale, score_mode, window_mode)
+    need = int(lib().delta_attn_prefill_append_workspace_bytes(ctypes.byref(p), cache.handle))
+    if need == 0:
+        # let the call itself say why
+        need = 1
+    workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    B, Hkv, m, d = K.shape
+    O = torch.empty_like(Q)
+    mask = torch.empty((B, Hkv, m, d // 32), dtype=torch.int32, device=Q.device)
+    nnz = torch.empty((B, Hkv), dtype=torch.int64, device=Q.device)
+    st = lib().delta_attn_prefill_append(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                         mask.data_ptr(), nnz.data_ptr(), cache.handle, workspace.data_ptr(),
+                                         workspace.numel(), _stream())
+    _check(st, "delta_attn_prefill_append")
     return O, mask, nnz
 
 

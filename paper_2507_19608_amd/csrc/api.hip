@@ -205,6 +205,8 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.Hkv = p->n_kv_heads;
     a.d = p->head_dim;
     a.n = p->seq_len;
+    a.q_off = 0;
+    a.nq = p->seq_len;
     a.W = p->window;
     a.scale_log2 = score_scale(p->scale, p->head_dim) * 1.4426950408889634f;
     a.rebase = p->score_mode == DA_SCORE_REBASE;
@@ -232,6 +234,148 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
         stage_end(kStageCacheFill, s);
         if (!launch_ok("cache_fill")) return DA_ERR_HIP;
     }
+    return DA_OK;
+}
+
+namespace {
+// workspace of delta_attn_prefill_append: whole-sequence arrays of n_k = cached + new rows
+struct AppendLayout {
+    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, vt, total;
+};
+
+AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
+    const size_t units = (size_t)p->batch * p->n_kv_heads, d = p->head_dim, es = elt_size(p->dtype);
+    const size_t m = p->seq_len, nk = (size_t)cached + m;
+    AppendLayout w;
+    size_t off = 0;
+    w.kfull = off;
+    off += align_up(units * nk * d * es);
+    w.hfull = off;
+    off += align_up(units * nk * d * es);
+    w.vfull = off;
+    off += align_up(units * nk * d * es);
+    w.mfull = off;
+    off += align_up(units * nk * (d / 32) * 4);
+    w.hnew = off;
+    off += align_up(units * m * d * es);
+    w.chunk_out = off;
+    off += align_up(2 * units * (size_t)delta_scan_num_chunks((int)m) * d * es);
+    w.ents = off;
+    off += align_up(units * nk * d * 8);
+    w.counts = off;
+    off += align_up(units * nk * sizeof(uint32_t));
+    w.nch8 = off;
+    off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk));
+    w.vt = off;
+    off += align_up(units * d * (size_t)prefill_mfma_n_pad((int)nk) * 2);
+    w.total = off;
+    return w;
+}
+
+da_status check_append(const da_prefill_params *p, const da_cache *c) {
+    da_status st = check_params(p);
+    if (st != DA_OK) return st;
+    if (!c) return DA_ERR_INVALID_ARG;
+    if (!c->fast) return DA_ERR_UNSUPPORTED;                 // only the column-run cache layout can be continued
+    if (c->B != p->batch || c->Hq != p->n_q_heads || c->Hkv != p->n_kv_heads || c->d != p->head_dim ||
+        c->dtype != p->dtype || c->theta != p->theta)
+        return DA_ERR_STATE;
+    if (c->len + p->seq_len > c->max_seq) return DA_ERR_STATE;
+    if (c->len > 0 && p->window > c->Wd) return DA_ERR_UNSUPPORTED;   // raw keys of the window come from the ring
+    return DA_OK;
+}
+}  // namespace
+
+size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache) {
+    if (check_append(p, cache) != DA_OK) return 0;
+    return append_layout(p, cache->len).total;
+}
+
+da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
+                                    uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+    da_status st = check_append(p, cache);
+    if (st != DA_OK) return st;
+    if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
+    const int t0 = (int)cache->len, m = p->seq_len, nk = t0 + m, d = p->head_dim;
+    const AppendLayout w = append_layout(p, t0);
+    if (!workspace || workspace_bytes < w.total) return DA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    const int units = p->batch * p->n_kv_heads;
+    const size_t row = (size_t)d * 2, mrow = (size_t)(d / 32) * 4;
+    (void)hipGetLastError();
+
+    // 1. the cached rows as plain arrays; the new rows behind them
+    expand_cache_runs(cache, t0, nk, ws + w.kfull, ws + w.hfull, ws + w.vfull, (uint32_t *)(ws + w.mfull), s);
+    if (hipMemcpy2DAsync(ws + w.kfull + (size_t)t0 * row, (size_t)nk * row, K, (size_t)m * row, (size_t)m * row, units,
+                         hipMemcpyDeviceToDevice, s) != hipSuccess ||
+        hipMemcpy2DAsync(ws + w.vfull + (size_t)t0 * row, (size_t)nk * row, V, (size_t)m * row, (size_t)m * row, units,
+                         hipMemcpyDeviceToDevice, s) != hipSuccess)
+    {
+        (void)launch_ok("prefill_append copy");   // records the error text
+        return DA_ERR_HIP;
+    }
+    // 2. Eq. 2-3 over the new rows, continuing from the cache's reference key (row 0 of an empty cache is the basis)
+    stage_begin(kStageScan, s);
+    launch_delta_scan(p->dtype, K, ws + w.hnew, mask_bits, ws + w.chunk_out, nnz, units, m, d, p->theta, s,
+                      t0 > 0 ? cache->khat : nullptr);
+    stage_end(kStageScan, s);
+    if (hipMemcpy2DAsync(ws + w.hfull + (size_t)t0 * row, (size_t)nk * row, ws + w.hnew, (size_t)m * row,
+                         (size_t)m * row, units, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+        hipMemcpy2DAsync(ws + w.mfull + (size_t)t0 * mrow, (size_t)nk * mrow, mask_bits, (size_t)m * mrow,
+                         (size_t)m * mrow, units, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    {
+        (void)launch_ok("prefill_append copy");   // records the error text
+        return DA_ERR_HIP;
+    }
+    if (!launch_ok("delta_scan")) return DA_ERR_HIP;
+    // 3. entry lists of every key column (cached ones from reference keys: where a bit is set they equal the key)
+    if (p->score_mode == DA_SCORE_GATHER) {
+        stage_begin(kStageEmit, s);
+        launch_emit_entries(p->dtype, ws + w.kfull, ws + w.hfull, (const uint32_t *)(ws + w.mfull), ws + w.ents,
+                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), units, nk, prefill_mfma_n_pad(nk), d,
+                            s);
+        stage_end(kStageEmit, s);
+        if (!launch_ok("emit_entries")) return DA_ERR_HIP;
+    }
+    // 4. attention of the new rows over all nk keys
+    PrefillArgs a;
+    a.dtype = p->dtype;
+    a.B = p->batch;
+    a.Hq = p->n_q_heads;
+    a.Hkv = p->n_kv_heads;
+    a.d = d;
+    a.n = nk;
+    a.q_off = t0;
+    a.nq = m;
+    a.W = p->window;
+    a.scale_log2 = score_scale(p->scale, d) * 1.4426950408889634f;
+    a.rebase = p->score_mode == DA_SCORE_REBASE;
+    a.sliding = p->window_mode == DA_WINDOW_SLIDING;
+    a.Q = Q;
+    a.K = ws + w.kfull;
+    a.V = ws + w.vfull;
+    a.Khat = ws + w.hfull;
+    a.O = O;
+    a.ents = ws + w.ents;
+    a.counts = (const uint32_t *)(ws + w.counts);
+    a.nch8 = (const uint8_t *)(ws + w.nch8);
+    stage_begin(kStageAttn, s);
+    bool launched = true;
+    if (prefill_mfma_supported(a) && !force_generic())
+        launch_prefill_mfma(a, ws + w.vt, s);
+    else
+        launched = launch_prefill_generic(a, s);
+    stage_end(kStageAttn, s);
+    if (!launched) return DA_ERR_UNSUPPORTED;
+    if (!launch_ok("prefill_append attention")) return DA_ERR_HIP;
+    // 5. the new rows join the cache
+    stage_begin(kStageCacheFill, s);
+    cache_fill_runs(cache, t0, nk, ws + w.kfull, V, ws + w.hfull, (const uint32_t *)(ws + w.mfull), nnz, s);
+    stage_end(kStageCacheFill, s);
+    if (!launch_ok("cache_fill")) return DA_ERR_HIP;
+    cache->len = nk;
     return DA_OK;
 }
 

@@ -49,8 +49,12 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
                              const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,
                              const uint64_t *nnz, hipStream_t s);
 // column-run layout (fast == 1)
-void cache_fill_runs(da_cache *c, int n, const void *K, const void *V, const void *Khat, const uint32_t *mask_bits,
-                     const uint64_t *nnz, hipStream_t s);
+// appends rows t0 .. n_k - 1 (t0 = rows already held) from whole-sequence arrays [units][n_k][...]
+void cache_fill_runs(da_cache *c, int t0, int n_k, const void *Kfull, const void *Vnew, const void *Hfull,
+                     const uint32_t *Mfull, const uint64_t *nnz_new, hipStream_t s);
+// writes the cached rows 0 .. t0 - 1 out as whole-sequence arrays with n_k rows of room per unit
+void expand_cache_runs(da_cache *c, int t0, int n_k, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
+                       hipStream_t s);
 // returns the number of partial rows written per head, 0 if the launch wrote the output itself
 int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,
                      float scale_log2, hipStream_t s);

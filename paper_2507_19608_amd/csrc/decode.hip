@@ -672,7 +672,7 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
     (void)counts;
     const int units = c->B * c->Hkv, n = p->seq_len;
     if (c->fast) {
-        da::cache_fill_runs(c, n, K, V, Khat, mask_bits, nnz, s);
+        da::cache_fill_runs(c, 0, n, K, V, Khat, mask_bits, nnz, s);
         c->len = n;
         return;
     }

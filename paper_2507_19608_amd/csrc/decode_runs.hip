@@ -69,48 +69,103 @@ __global__ __launch_bounds__(64) void seal_from_ring_kernel(da_cache c, int chun
         [&](int ch) { return chunk > 0 ? ckp[ch] : (bf16_t)0; });
 }
 
-// Prefill hand-off (Sec. III-C): one wave per (chunk, unit).
-__global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__restrict__ K,
-                                                             const bf16_t *__restrict__ V,
-                                                             const bf16_t *__restrict__ Khat,
-                                                             const uint32_t *__restrict__ mask_bits,
-                                                             const uint64_t *__restrict__ nnz_in, da_cache c, int n) {
-    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
-    const int d = c.d, wpr = d >> 5;
-    const int r0 = chunk * kChunk, rows = min(kChunk, n - r0);
-    const uint32_t *Mp = mask_bits + ((size_t)unit * n + r0) * wpr;
+// Hand-off of prefilled rows to the cache (Sec. III-C): rows t0 .. n_k - 1 (t0 = rows the cache already
+// holds) are appended; one wave per (chunk that contains such a row, unit).  Kfull, Hfull, Mfull describe the
+// whole sequence [units][n_k][...]: keys (for rows the decode window no longer holds raw, the reference key
+// stands in - the two agree wherever a mask bit is set, which is all that is read), reference keys, mask
+// rows; Vnew [units][n_k - t0][d] the new value rows.  With t0 = 0 these are the prefill's own arrays.
+__global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__restrict__ Kfull,
+                                                             const bf16_t *__restrict__ Vnew,
+                                                             const bf16_t *__restrict__ Hfull,
+                                                             const uint32_t *__restrict__ Mfull,
+                                                             const uint64_t *__restrict__ nnz_new, da_cache c, int t0,
+                                                             int n_k) {
+    const int chunk = blockIdx.x + t0 / kChunk, unit = blockIdx.y, lane = threadIdx.x;
+    const int d = c.d, wpr = d >> 5, m = n_k - t0;
+    const int r0 = chunk * kChunk;
+    const int ra = max(r0, t0), rb = min(r0 + kChunk, n_k);          // new rows of this chunk
+    const uint32_t *Mp = Mfull + ((size_t)unit * n_k + r0) * wpr;    // the chunk's mask rows, old ones included
     uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
-    for (int i = lane; i < rows * wpr; i += kWave) Mc[i] = Mp[i];
-    if (lane == 0 && chunk == 0) c.nnz[unit] = nnz_in[unit];
-    const bf16_t *Kp = K + ((size_t)unit * n + r0) * d;
-    const bf16_t *Hp = Khat + ((size_t)unit * n + r0) * d;
-    const bf16_t *Vp = V + ((size_t)unit * n + r0) * d;
+    for (int i = (ra - r0) * wpr + lane; i < (rb - r0) * wpr; i += kWave) Mc[i] = Mp[i];
+    if (lane == 0 && blockIdx.x == 0) c.nnz[unit] = (t0 == 0 ? 0ull : c.nnz[unit]) + nnz_new[unit];
+    const bf16_t *Kp = Kfull + ((size_t)unit * n_k + r0) * d;
+    const bf16_t *Hp = Hfull + ((size_t)unit * n_k + r0) * d;
+    const bf16_t *Vp = Vnew + (size_t)unit * m * d;
     for (int ch = lane; ch < d; ch += kWave) {
-        for (int r = 0; r < rows; ++r) {
-            const int row = r0 + r;
-            if (row >= n - c.Wd) ((bf16_t *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = Kp[(size_t)r * d + ch];
-        }
-        if (chunk > 0) ((bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = Hp[ch - d];
-        if (r0 + rows == n) ((bf16_t *)c.khat)[(size_t)unit * d + ch] = Hp[(size_t)(rows - 1) * d + ch];
-        // V: 16 rows of one channel are contiguous (32 bytes per lane, consecutive lanes adjacent)
-        for (int g16 = 0; g16 * 16 < rows; ++g16) {
-            bf16_t v16[16];
+        for (int row = ra; row < rb; ++row)
+            if (row >= n_k - c.Wd)
+                ((bf16_t *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = Kp[(size_t)(row - r0) * d + ch];
+        if (chunk > 0 && r0 >= t0) ((bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = Hp[ch - d];
+        if (rb == n_k) ((bf16_t *)c.khat)[(size_t)unit * d + ch] = Hp[(size_t)(rb - 1 - r0) * d + ch];
+        // V: 16 rows of one channel are contiguous.  A group that starts with a new row is written whole (32
+        // bytes per lane, consecutive lanes adjacent; rows past the end as zeros), one that starts with old
+        // rows only gets its new slots
+        for (int g0 = r0; g0 < rb; g0 += 16) {
+            if (g0 + 16 <= ra) continue;
+            bf16_t *dst = (bf16_t *)c.V + (((size_t)unit * (c.vrows >> 4) + (g0 >> 4)) * d + ch) * 16;
+            if (g0 >= ra) {
+                bf16_t v16[16];
 #pragma unroll
-            for (int slot = 0; slot < 16; ++slot) {
-                const int k = slot >> 3, i = slot & 7;
-                const int p = 8 * (i >> 2) + 4 * k + (i & 3);
-                v16[slot] = (g16 * 16 + p < rows) ? Vp[(size_t)(g16 * 16 + p) * d + ch] : (bf16_t)0;
+                for (int slot = 0; slot < 16; ++slot) {
+                    const int k = slot >> 3, i = slot & 7;
+                    const int row = g0 + 8 * (i >> 2) + 4 * k + (i & 3);
+                    v16[slot] = row < rb ? Vp[(size_t)(row - t0) * d + ch] : (bf16_t)0;
+                }
+#pragma unroll
+                for (int slot = 0; slot < 16; ++slot) dst[slot] = v16[slot];
+            } else {
+                for (int row = ra; row < min(g0 + 16, rb); ++row)
+                    ((bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)] = Vp[(size_t)(row - t0) * d + ch];
             }
-            bf16_t *dst = (bf16_t *)c.V + (((size_t)unit * (c.vrows >> 4) + ((r0 >> 4) + g16)) * d + ch) * 16;
-#pragma unroll
-            for (int slot = 0; slot < 16; ++slot) dst[slot] = v16[slot];
         }
     }
-    // complete chunks are sealed here (the run's first element comes from the prefill's reference keys)
-    if (rows == kChunk)
+    // chunks completed by these rows are sealed here (the run's first element comes from the reference keys)
+    if (rb - r0 == kChunk)
         seal_chunk(
             c, unit, chunk, lane, Mp, [&](int r) { return Kp + (size_t)r * d; },
             [&](int ch) { return chunk > 0 ? Hp[ch - d] : (bf16_t)0; });
+}
+
+// The inverse of the hand-off, for a prefill that continues a cached sequence: rows 0 .. t0 - 1 of the cache
+// are written out as plain arrays [units][n_k][...] (n_k >= t0 rows of room per unit): reference keys (from
+// the sealed runs, or for the unsealed last chunk from the ring), keys (raw for the rows the ring still
+// holds, the reference key otherwise), values, mask rows.  One wave per (chunk, unit), lane = channel.
+__global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, int n_k, bf16_t *__restrict__ Kfull,
+                                                          bf16_t *__restrict__ Hfull, bf16_t *__restrict__ Vfull,
+                                                          uint32_t *__restrict__ Mfull) {
+    const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
+    const int d = c.d, wpr = d >> 5;
+    const int r0 = chunk * kChunk, rows = min(kChunk, t0 - r0);
+    const bool sealed = rows == kChunk;
+    const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
+    for (int i = lane; i < rows * wpr; i += kWave) Mfull[((size_t)unit * n_k + r0) * wpr + i] = Mp[i];
+    const bf16_t *room = run_room(c, unit, chunk);
+    const bf16_t *ring = (const bf16_t *)c.ring + (size_t)unit * c.Wd * d;
+    uint32_t base = 0;
+    for (int c0 = 0; c0 < d; c0 += kWave) {
+        const int ch = c0 + lane;
+        uint64_t cm = 0;
+        for (int r = 0; r < rows; ++r) cm |= (uint64_t)((Mp[(size_t)r * wpr + (ch >> 5)] >> (ch & 31)) & 1u) << r;
+        uint32_t total = 0, p = 0;
+        bf16_t held = 0;
+        if (sealed) {
+            p = base + wave_exclusive_scan((uint32_t)__popcll(cm) + 1u, &total);
+            held = room[p];
+        } else if (chunk > 0) {
+            held = ((const bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch];
+        }
+        for (int r = 0; r < rows; ++r) {
+            const int row = r0 + r;
+            const bool raw_here = row >= t0 - c.Wd;          // always true for an unsealed chunk (Wd >= kChunk)
+            const bf16_t kraw = raw_here ? ring[(size_t)(row % c.Wd) * d + ch] : (bf16_t)0;
+            if ((cm >> r) & 1ull) held = sealed ? room[++p] : kraw;
+            const size_t o = ((size_t)unit * n_k + row) * d + ch;
+            Hfull[o] = held;
+            Kfull[o] = raw_here ? kraw : held;
+            Vfull[o] = ((const bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)];
+        }
+        base += total;
+    }
 }
 
 // D1: delta of the new key against the carried reference key (Eq. 2-3).  One wave per unit.  The
@@ -448,11 +503,19 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
 
 namespace da {
 
-void cache_fill_runs(da_cache *c, int n, const void *K, const void *V, const void *Khat, const uint32_t *mask_bits,
-                     const uint64_t *nnz, hipStream_t s) {
+void cache_fill_runs(da_cache *c, int t0, int n_k, const void *Kfull, const void *Vnew, const void *Hfull,
+                     const uint32_t *Mfull, const uint64_t *nnz_new, hipStream_t s) {
     const int units = c->B * c->Hkv;
-    hipLaunchKernelGGL(cache_fill_runs_kernel, dim3((n + kChunk - 1) / kChunk, units), dim3(64), 0, s,
-                       (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)Khat, mask_bits, nnz, *c, n);
+    const int chunks = (n_k + kChunk - 1) / kChunk - t0 / kChunk;
+    hipLaunchKernelGGL(cache_fill_runs_kernel, dim3(chunks, units), dim3(64), 0, s, (const bf16_t *)Kfull,
+                       (const bf16_t *)Vnew, (const bf16_t *)Hfull, Mfull, nnz_new, *c, t0, n_k);
+}
+
+void expand_cache_runs(da_cache *c, int t0, int n_k, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
+                       hipStream_t s) {
+    if (t0 <= 0) return;
+    hipLaunchKernelGGL(expand_cache_kernel, dim3((t0 + kChunk - 1) / kChunk, c->B * c->Hkv), dim3(64), 0, s, *c, t0,
+                       n_k, (bf16_t *)Kfull, (bf16_t *)Hfull, (bf16_t *)Vfull, Mfull);
 }
 
 int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,

@@ -79,8 +79,8 @@ int timing_collect(double *ms_per_stage, int *calls_per_stage) {
 // past every time a channel fires: from then on the held value is k(t) whatever it was before.
 // So time is cut into chunks that are scanned in parallel from a guessed incoming state:
 //
-//   pass 1  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row and is
-//           exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and records only its final
+//   pass 1  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row (or, when the
+//           rows continue a sequence, from the reference key `init` carried over from it) and is exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and records only its final
 //           held value.  That final value is already the true one for every channel that fired at
 //           least once inside the chunk at a row where the true chain fired too - nearly all.
 //   pass 2  same scan, but chunk c starts from pass 1's final value of chunk c - 1, and writes mask
@@ -98,7 +98,8 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
                                                                const T *__restrict__ guess_out,
                                                                T *__restrict__ chunk_out,
                                                                unsigned long long *__restrict__ nnz, int n, int d,
-                                                               int L, int nchunks, float theta) {
+                                                               int L, int nchunks, float theta,
+                                                               const T *__restrict__ init) {
     const int unit = blockIdx.z, chunk = blockIdx.y;
     const int lane = threadIdx.x;
     const int c = blockIdx.x * kWave + lane;
@@ -114,7 +115,9 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
     float held = 0.f;
     unsigned long long cnt = 0;
     int t = t0;
-    if (chunk == 0) {   // row 0 is the basis: kept whole
+    if (chunk == 0 && init) {   // the rows continue a sequence: its reference key is the incoming state
+        if (active) held = load_f32(init, (size_t)unit * d + c);
+    } else if (chunk == 0) {   // row 0 is the basis: kept whole
         if (active) held = load_f32(Kp, c);
         if (kFinal) {
             if (active) Hp[c] = Kp[c];
@@ -290,7 +293,7 @@ int delta_scan_num_chunks(int n) { return (n + delta_scan_chunk_len(n) - 1) / de
 
 template <typename T>
 static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz, int units,
-                       int n, int d, float theta, hipStream_t s) {
+                       int n, int d, float theta, const void *init, hipStream_t s) {
     const int L = delta_scan_chunk_len(n), nchunks = delta_scan_num_chunks(n);
     const int cw = (d + kWave - 1) / kWave;
     T *out1 = (T *)chunk_out;
@@ -298,10 +301,10 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
     if (nchunks > 1)
         hipLaunchKernelGGL((delta_scan_chunks_kernel<T, false>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
                            (const T *)K, (T *)Khat, mask_bits, (const T *)nullptr, out1,
-                           (unsigned long long *)nnz, n, d, L, nchunks, theta);
+                           (unsigned long long *)nnz, n, d, L, nchunks, theta, (const T *)init);
     hipLaunchKernelGGL((delta_scan_chunks_kernel<T, true>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
                        (const T *)K, (T *)Khat, mask_bits, (const T *)out1, out2, (unsigned long long *)nnz, n, d, L,
-                       nchunks, theta);
+                       nchunks, theta, (const T *)init);
     if (nchunks > 1)
         hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw, units), dim3(kWave), 0, s, (const T *)K, (T *)Khat,
                            mask_bits, (const T *)out1, (const T *)out2, (unsigned long long *)nnz, n, d, L, nchunks,
@@ -309,13 +312,14 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
 }
 
 // Khat [units][n][d] and chunk_out [2][units][delta_scan_num_chunks(n)][d] are required scratch/outputs.
+// init: NULL (row 0 is the basis row) or [units][d], the reference key the rows continue from.
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
-                       int units, int n, int d, float theta, hipStream_t s) {
+                       int units, int n, int d, float theta, hipStream_t s, const void *init) {
     launch_fill_u64(nnz, 0, units, s);
     if (dtype == 0)
-        scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, s);
+        scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
     else
-        scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, s);
+        scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
 }
 
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,

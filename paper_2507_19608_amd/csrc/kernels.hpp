@@ -20,7 +20,8 @@ int timing_collect(double *ms_per_stage, int *calls_per_stage);
 
 struct PrefillArgs {
     int dtype;            // 0 f32, 1 bf16
-    int B, Hq, Hkv, d, n, W;
+    int B, Hq, Hkv, d, n, W;   // n = number of key rows
+    int q_off, nq;             // the query rows are positions q_off .. q_off + nq - 1 (q_off + nq == n)
     float scale_log2;     // score scale * log2(e)
     int rebase;           // 1: outside scores from q . k_hat instead of the entry lists
     int sliding;          // 1: exact region is the band i - j < W instead of squares of side W
@@ -34,7 +35,7 @@ struct PrefillArgs {
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 int delta_scan_num_chunks(int n);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
-                       int units, int n, int d, float theta, hipStream_t s);
+                       int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr);
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
                          uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if

@@ -21,6 +21,7 @@ struct KArgs {
     const EntryChunk *__restrict__ ents;
     const uint32_t *__restrict__ counts;
     int Hq, Hkv, n, W, rebase, sliding;
+    int q_off, nq;   // query rows are positions q_off .. q_off + nq - 1 of the n keys
     float scale_log2;
 };
 
@@ -28,28 +29,29 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
     extern __shared__ float qt[];   // [D][64]: qt[c * 64 + lane] = q_row(lane)[c]
     const int lane = threadIdx.x;
-    const int tiles = (a.n + 63) / 64;
+    const int tiles = (a.nq + 63) / 64;
     const int tile = tiles - 1 - (int)blockIdx.x;   // longest rows first
+    const int i_first = a.q_off + tile * 64;        // position of the tile's first row
     const int h = blockIdx.y, b = blockIdx.z;
     const int g = a.Hq / a.Hkv;
     const int unit = b * a.Hkv + h / g;
     const int n = a.n, W = a.W;
-    const int i = tile * 64 + lane;
+    const int i = i_first + lane;
     const bool valid = i < n;
-    const T *Qp = a.Q + ((size_t)(b * a.Hq + h) * n) * D;
+    const T *Qp = a.Q + ((size_t)(b * a.Hq + h) * a.nq) * D;
     const T *Kp = a.K + (size_t)unit * n * D;
     const T *Vp = a.V + (size_t)unit * n * D;
     const T *Hp = a.Khat + (size_t)unit * n * D;
     const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
     const uint32_t *Cp = a.counts + (size_t)unit * n;
 
-    for (int c = 0; c < D; ++c) qt[c * 64 + lane] = valid ? load_f32(Qp, (size_t)i * D + c) : 0.f;
+    for (int c = 0; c < D; ++c) qt[c * 64 + lane] = valid ? load_f32(Qp, (size_t)(i - a.q_off) * D + c) : 0.f;
     __syncthreads();
 
-    const int i_last = min(n - 1, tile * 64 + 63);          // last row of the tile
+    const int i_last = min(n - 1, i_first + 63);            // last row of the tile
     // first exact column of row r: start of its square, or of its band (monotone in r either way)
     auto win_start = [&](int r) { return a.sliding ? max(r - W + 1, 0) : (r / W) * W; };
-    const int win_first = win_start(tile * 64);             // window start of the tile's first row
+    const int win_first = win_start(i_first);               // window start of the tile's first row
     const int win_last = win_start(i_last);                 // window start of its last row
     const int my_win = valid ? win_start(i) : 0;
 
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
     }
     if (valid) {
         const float inv = 1.f / l;
-        T *Op = a.O + ((size_t)(b * a.Hq + h) * n + i) * D;
+        T *Op = a.O + ((size_t)(b * a.Hq + h) * a.nq + (i - a.q_off)) * D;
 #pragma unroll
         for (int c = 0; c < D; ++c) store_from_f32(Op, c, o[c] * inv);
     }
@@ -136,6 +138,8 @@ static void launch_one(const PrefillArgs &p, hipStream_t s) {
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.n = p.n;
+    a.q_off = p.q_off;
+    a.nq = p.nq;
     a.W = p.W;
     a.sliding = p.sliding;
     a.rebase = p.rebase;
@@ -147,7 +151,7 @@ static void launch_one(const PrefillArgs &p, hipStream_t s) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_done = true;
     }
-    dim3 grid((p.n + 63) / 64, p.Hq, p.B), block(64);
+    dim3 grid((p.nq + 63) / 64, p.Hq, p.B), block(64);
     hipLaunchKernelGGL((prefill_generic_kernel<T, D>), grid, block, lds, s, a);
 }
 

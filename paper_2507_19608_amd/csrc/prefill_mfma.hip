@@ -49,6 +49,7 @@ struct MfmaArgs {
     const EntryChunk *__restrict__ ents;
     const uint8_t *__restrict__ nch8;
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
+    int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     float scale_log2;
 };
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int g = a.Hq / a.Hkv;
     const int head0 = hk * g + hchunk * a.GH;
     const int n = a.n, W = a.W, RT = a.RT;
-    const int i0 = tile * RT;
+    const int i0 = a.q_off + tile * RT;
     const int i_last = min(n - 1, i0 + RT - 1);
 
     const bf16_t *Kp = a.K + (size_t)unit * n * D;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     auto q_row_ptr = [&](int sr) -> const bf16_t * {
         const int hh = sr / RT, r = sr - hh * RT;
         const int i = min(i0 + r, n - 1);
-        return a.Q + (((size_t)b * a.Hq + head0 + hh) * n + i) * D;
+        return a.Q + (((size_t)b * a.Hq + head0 + hh) * a.nq + (i - a.q_off)) * D;
     };
 
     // ---- stage the Q tile: per-tile power-of-two scale so that the fp16 copy neither overflows nor
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (my_valid) {
         const float inv = 1.f / l_tot;
-        bf16_t *orow = a.O + (((size_t)b * a.Hq + head0 + my_hh) * n + my_i) * D;
+        bf16_t *orow = a.O + (((size_t)b * a.Hq + head0 + my_hh) * a.nq + (my_i - a.q_off)) * D;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -552,7 +553,9 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const int g = p.Hq / p.Hkv;
     a.GH = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
     a.RT = kRows / a.GH;
-    a.tiles = (p.n + a.RT - 1) / a.RT;
+    a.q_off = p.q_off;
+    a.nq = p.nq;
+    a.tiles = (p.nq + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);

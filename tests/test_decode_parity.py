@@ -159,3 +159,69 @@ def test_c4_decode_llama_shape_sampled_batch():
     s_m, _ = da.delta_attn_sparsity(cache.nnz(), n + steps, d, w.window)
     assert abs(s_m - 0.57) < 0.01
     cache.close()
+
+
+@pytest.mark.parametrize("score_mode", [da.DA_SCORE_GATHER, da.DA_SCORE_REBASE])
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+@pytest.mark.parametrize("d,Hq,Hkv,W,Wd,chunks", [
+    (64, 4, 2, 48, 64, (100, 37, 64, 91)),      # unaligned pieces: old partial chunks get completed and sealed
+    (128, 4, 1, 20, 70, (64, 130, 1, 70)),      # a piece of one row; pieces that start on chunk boundaries
+    (64, 8, 1, 64, 64, (10, 300)),              # a short first piece, then several chunks at once
+])
+def test_chunked_prefill_then_decode(score_mode, window_mode, d, Hq, Hkv, W, Wd, chunks):
+    """Prefill in pieces onto a growing cache (Sec. III-C): every piece must equal the same rows of one prefill
+    over the whole prefix (window squares anchored at position 0), the masks must equal one scan, and decode
+    must continue from the cache as if it had been filled in one go."""
+    B, steps, theta = 2, 12, 0.2
+    L = sum(chunks) + steps
+    Q, K, V = rand_walk(71, B, Hq, L, d), rand_walk(72, B, Hkv, L, d), rand_walk(73, B, Hkv, L, d, clip=3.5)
+    Qd, Kd, Vd = (to_dev(x, "bf16") for x in (Q, K, V))
+    cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
+    t0 = 0
+    for m in chunks:
+        sl = slice(t0, t0 + m)
+        O, maskg, nnzg = da.delta_attn_prefill_append(cache, Qd[:, :, sl].contiguous(), Kd[:, :, sl].contiguous(),
+                                                      Vd[:, :, sl].contiguous(), theta, W, score_mode=score_mode,
+                                                      window_mode=window_mode)
+        ref = orc.prefill(Q[:, :, :t0 + m], K[:, :, :t0 + m], V[:, :, :t0 + m], theta, W, rows=(t0, t0 + m),
+                          window_mode=window_mode)
+        assert ref["knife"] == 0
+        assert (unpack_mask(maskg, d) == ref["mask"][:, :, t0:]).all()
+        assert (nnzg.cpu().numpy() == ref["mask"][:, :, t0:].sum(axis=(2, 3))).all()
+        for h in range(Hq):
+            check_output(O[:, h], ref["O"][:, h], "bf16")
+        t0 += m
+        assert len(cache) == t0
+        assert (cache.nnz().cpu().numpy() == ref["nnz"]).all()
+    st = orc.DecodeState(theta, Wd)
+    st.append(K[:, :, :t0], V[:, :, :t0])
+    assert (unpack_mask(cache.mask_rows(), d) == st.mask).all()
+    for t in range(t0, t0 + steps):
+        o, mrow = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        o_ref, m_ref = st.step(Q[:, :, t], K[:, :, t], V[:, :, t])
+        assert (unpack_mask(mrow, d) == m_ref).all()
+        check_output(o, o_ref, "bf16")
+    assert (cache.nnz().cpu().numpy() == st.nnz()).all()
+    cache.close()
+
+
+def test_chunked_prefill_argument_checks():
+    z = lambda h, m, d=64: torch.zeros(1, h, m, d, dtype=torch.bfloat16, device="cuda")
+    small = da.Cache(1, 2, 1, 64, 300, 8, 0.1, torch.bfloat16)          # decode window below one chunk: row layout
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill_append(small, z(2, 10), z(1, 10), z(1, 10), 0.1, 4)
+    assert e.value.status == 2
+    small.close()
+    cache = da.Cache(1, 2, 1, 64, 100, 64, 0.1, torch.bfloat16)
+    da.delta_attn_prefill_append(cache, z(2, 70), z(1, 70), z(1, 70), 0.1, 16)
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill_append(cache, z(2, 31), z(1, 31), z(1, 31), 0.1, 16)   # 101 rows > max_seq
+    assert e.value.status == 4
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill_append(cache, z(2, 10), z(1, 10), z(1, 10), 0.1, 65)   # window wider than the ring
+    assert e.value.status == 2
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill_append(cache, z(2, 10), z(1, 10), z(1, 10), 0.2, 16)   # theta differs
+    assert e.value.status == 4
+    assert len(cache) == 70
+    cache.close()
