@@ -22,7 +22,9 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
-PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS = 78.6   # same without packed-fp32 instructions (not emitted by this build)
+# fp32 FMA rate measured on this chip without packed-fp32 instructions at 2 waves per SIMD, the occupancy of the
+# prefill kernel (delta_attn_rate_probe; one wave issues a vector instruction every ~7 cycles)
+MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 83.1
 
 # HBM-side bytes per launch of the dominant kernel (fetch + write), measured once with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
@@ -117,8 +119,8 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
         roof = {"bound": "alu", "achieved": alu_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_VALU_F32_TFLOPS,
                 "unit": "TFLOP/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
-        roof["peak_scalar_issue_fp32"] = PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS
-        roof["frac_scalar_issue_fp32"] = roof["achieved"] / PEAK_VALU_F32_SCALAR_ISSUE_TFLOPS
+        roof["measured_fma_rate_at_kernel_occupancy"] = MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD
+        roof["frac_of_measured_rate"] = roof["achieved"] / MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD
     else:
         alu_flops = 0.0
         mfma_flops = 2.0 * (2.0 * causal_pairs) * d
@@ -272,8 +274,9 @@ def eq5_sweep(args, da, wl, torch, np):
 
 
 def hbm_read_probe(da, torch):
-    """Streaming-read rate this GPU reaches on a buffer of the decode step's size and on 1 GiB, with the access
-    shape of the decode kernel (delta_attn_stream_read): the practical ceiling to read the decode GB/s against."""
+    """What this GPU sustains: streaming-read rate on a buffer of the decode step's size and on 1 GiB, with the access
+    shape of the decode kernel (delta_attn_stream_read); bf16 MFMA and unpacked fp32 FMA rates from register-only
+    loops at 8 waves per SIMD (delta_attn_rate_probe).  Context for the roofline fractions, which use published peaks."""
     out = {}
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     for name, nbytes, nbuf in (("108_MiB", 108 << 20, 4), ("1_GiB", 1 << 30, 2)):
@@ -290,6 +293,20 @@ def hbm_read_probe(da, torch):
                 best = min(best, e0.elapsed_time(e1) / launches)
         out[name] = {"ms": best, "GB/s": nbytes / (best * 1e-3) / 1e9}
         del xs
+    # arithmetic rates: register-only chains, 8 work groups of 4 waves per CU
+    fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 4000), ("fma_fp32_unpacked", 1, 20000)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = float("inf")
+        for rep in range(4):
+            e0.record()
+            flop = da.delta_attn_rate_probe(kind, cus * 8, iters, fsink)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 1:
+                best = min(best, e0.elapsed_time(e1))
+        out[name] = {"ms": best, "TFLOP/s": flop / (best * 1e-3) / 1e12}
     return out
 
 

@@ -96,6 +96,14 @@ int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_st
  * of that size, which is below the published HBM peak. */
 da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
 
+/* Measurement aid, like delta_attn_stream_read: one launch of `work_groups` x 256 threads in which every wave
+ * runs `iters` rounds of independent register-only chains - kind 0: four 32x32x16 bf16 MFMA accumulations per
+ * round; kind 1: sixteen fp32 fused multiply-adds per lane per round (compiled like the rest of the library,
+ * i.e. without packed-fp32 instructions).  *flop receives the floating-point operations of the launch (host);
+ * timed by the caller it gives the arithmetic rates this GPU sustains, to set beside the published peaks. */
+da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters, float *sink, double *flop,
+                                void *hip_stream);
+
 /* Eq. 5: min(floor(gamma * n), w_max), clamped to >= 1.  Host only. */
 int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);
 

@@ -19,7 +19,7 @@ def declared_symbols():
 
 def test_header_symbols_are_exported():
     names = declared_symbols()
-    assert len(names) >= 22
+    assert len(names) >= 23
     L = binding.lib()
     for n in names:
         assert hasattr(L, n), n
