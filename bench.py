@@ -22,9 +22,9 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
-# fp32 FMA rate measured on this chip without packed-fp32 instructions at 2 waves per SIMD, the occupancy of the
-# prefill kernel (delta_attn_rate_probe; one wave issues a vector instruction every ~7 cycles)
-MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 83.1
+# fp32 FMA rate measured on this chip without packed-fp32 instructions, three register operands, at 2 waves per
+# SIMD: the instruction form and occupancy of the prefill kernel's gather loop (delta_attn_rate_probe, kind 2)
+MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 80.0
 
 # HBM-side bytes per launch of the dominant kernel (fetch + write), measured once with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
@@ -296,7 +296,8 @@ def hbm_read_probe(da, torch):
     # arithmetic rates: register-only chains, 8 work groups of 4 waves per CU
     fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 4000), ("fma_fp32_unpacked", 1, 20000)):
+    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 4000), ("fma_fp32_literal_multiplier", 1, 20000),
+                              ("fma_fp32_three_registers", 2, 20000)):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         best = float("inf")
         for rep in range(4):

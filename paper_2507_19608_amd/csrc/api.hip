@@ -119,14 +119,20 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float *__rest
     if (s == 12345.678f) *sink = s;
 }
 
+// kLiteral: the multiplier is an instruction literal (two register sources per multiply-add); otherwise all three
+// operands are registers, as in the library's gather loop.  8 rounds per loop trip, so that the loop's own scalar
+// instructions and branch do not show in the rate.
+template <bool kLiteral>
 __global__ __launch_bounds__(256) void fma_rate_kernel(int iters, float *__restrict__ sink) {
     float x[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
-    const float m = 0.999f, c = 0.0001f * (float)(threadIdx.x & 3);
-    for (int it = 0; it < iters; ++it) {
+    const float m = 0.999f + 1e-6f * (float)(threadIdx.x & 1), c = 0.0001f * (float)(threadIdx.x & 3);
+    for (int it = 0; it < iters; it += 8) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = fmaf(x[i], m, c);
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = kLiteral ? fmaf(x[i], 0.999f, c) : fmaf(x[i], m, c);
     }
     float s = 0.f;
 #pragma unroll
@@ -154,14 +160,20 @@ da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, 
 
 da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters, float *sink, double *flop,
                                 void *hip_stream) {
-    if (!sink || !flop || work_groups < 1 || iters < 1 || (kind != 0 && kind != 1)) return DA_ERR_INVALID_ARG;
+    if (!sink || !flop || work_groups < 1 || iters < 1 || kind < 0 || kind > 2) return DA_ERR_INVALID_ARG;
     (void)hipGetLastError();
     const double waves = 4.0 * work_groups;
     if (kind == 0) {
         hipLaunchKernelGGL(mfma_rate_kernel, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters, sink);
         *flop = waves * iters * 4.0 * (2.0 * 32 * 32 * 16);
     } else {
-        hipLaunchKernelGGL(fma_rate_kernel, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters, sink);
+        iters = (iters + 7) / 8 * 8;
+        if (kind == 1)
+            hipLaunchKernelGGL(fma_rate_kernel<true>, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters,
+                               sink);
+        else
+            hipLaunchKernelGGL(fma_rate_kernel<false>, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters,
+                               sink);
         *flop = waves * iters * 16.0 * 64.0 * 2.0;
     }
     return launch_ok("rate_probe") ? DA_OK : DA_ERR_HIP;
