@@ -408,16 +408,20 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
                 acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[T][s]),
                                                                  __builtin_bit_cast(bf16x8, qop[s]), acc[T], 0, 0, 0);
         }
-        float m = m_run;
+        if (nrows < kChunk) {                                // only the newest chunk has rows that do not exist yet
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * T + 8 * (r >> 2) + 4 * kap + (r & 3) >= nrows) acc[T][r] = -INFINITY;
+        }
+        float mx = acc[0][0];
 #pragma unroll
         for (int T = 0; T < 2; ++T)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const bool valid = 32 * T + 8 * (r >> 2) + 4 * kap + (r & 3) < nrows;
-                acc[T][r] = valid ? acc[T][r] * scale_log2 : -INFINITY;
-                m = fmaxf(m, acc[T][r]);
-            }
-        m = fmaxf(m, __shfl_xor(m, 32));                     // row r0 of a chunk is always valid, so m is finite
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[T][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));                  // row r0 of a chunk is always valid, so mx is finite
+        const float m = fmaxf(m_run, mx * scale_log2);       // running maximum in log2 units (the scale is positive)
         if (__any(m > m_run)) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m);   // first chunk: exp2(-inf) = 0 on zeros
             l_run *= alpha;
@@ -430,8 +434,8 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
         for (int T = 0; T < 2; ++T)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(acc[T][r] - m);
-                const float p1 = __builtin_amdgcn_exp2f(acc[T][r + 1] - m);
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[T][r], scale_log2, -m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[T][r + 1], scale_log2, -m));
                 l_run += p0 + p1;
                 pa[T][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
             }
