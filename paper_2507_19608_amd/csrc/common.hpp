@@ -38,6 +38,15 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
+// Work-group barrier for hand-offs through LDS.  __syncthreads() is a fence over every address space: before
+// its s_barrier a wave also waits for all of its outstanding global loads, so a prefetch issued ahead of the
+// barrier is drained at it.  This one orders LDS traffic only; global loads stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // exclusive prefix sum over the 64 lanes; *total receives the wave sum
 __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, uint32_t *total) {
     const int lane = threadIdx.x & 63;

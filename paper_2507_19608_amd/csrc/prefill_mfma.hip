@@ -51,6 +51,7 @@ struct MfmaArgs {
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
+    int xsplit;                         // > 0: XCD-aware order, every unit split this many ways (see the kernel)
     float scale_log2;
 };
 
@@ -73,9 +74,20 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction; tell the compiler
     const int half = lane >> 5, li = lane & 31;
 
-    // ---- which tile: within a unit, heavy (late) row tiles first
+    // ---- which tile.  Work groups go to the 8 XCDs round-robin by index, and every XCD has its own L2; all
+    //      tiles of a unit stream the same K, K_hat, V and entry lists.  So the index is first turned into
+    //      (XCD, slot on that XCD), and each XCD is given whole units - or, when the unit count does not
+    //      divide by 8, units split `xsplit` ways by tile index modulo xsplit - one after the other: a unit's
+    //      streams are then fetched into xsplit L2s instead of all 8.  Within a part, heavy (late) tiles first.
     int bid = blockIdx.x;
     const int per_unit = a.tiles * a.hgroups;
+    if (a.xsplit > 0) {
+        const int xcd = bid & 7, slot = bid >> 3;
+        const int per_part = per_unit / a.xsplit;            // work groups of one part
+        const int part = xcd + 8 * (slot / per_part);        // parts xcd, xcd + 8, ... belong to this XCD
+        const int within = slot % per_part;
+        bid = (part / a.xsplit) * per_unit + within * a.xsplit + part % a.xsplit;
+    }
     const int unit = bid / per_unit;
     bid -= unit * per_unit;
     const int hchunk = bid % a.hgroups;
@@ -333,7 +345,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             gather_block(pk);
             u32x4 vreg[2 * MT];
             load_v(vreg, blk * kTB);
-            __syncthreads();                                     // u of this block complete
+            lds_barrier();                                       // u of this block complete
             // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1
             // (the matrix-core D layout).  A lane sums inside its own groups and gets the other
             // half's group totals from its partner lane, so the running Eq. 4 score advances in
@@ -350,7 +362,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 }
                 t_own[q] = run;
             }
-            __syncthreads();                                     // u buffer free for the next block
+            lds_barrier();                                       // u buffer free for the next block
 #pragma unroll
             for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
             float s[16];
@@ -447,27 +459,29 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         // Software pipeline over blocks: the score MFMAs of block b+1 are issued before the softmax of
         // block b, so matrix-core and vector-ALU work of one wave overlap.  Buffer b % 3 holds the tiles of
         // block b; its K tile is read one iteration before its V tile.
-        Pieces p0, p1;
-        load_tiles(p0, far_blocks);
-        if (far_blocks + 1 < nblocks) load_tiles(p1, far_blocks + 1);
-        __syncthreads();                                         // the far loop's LDS use is over
-        store_tiles(p0, 0);
-        p0 = p1;
-        if (far_blocks + 2 < nblocks) load_tiles(p1, far_blocks + 2);
-        __syncthreads();
+        // Two register sets of pieces alternate: a set is parked in LDS and at once re-used for the block two
+        // further on, so no set is ever copied (a copy of registers that a load is still filling waits for it).
+        // Loads and stores are issued every iteration, past the last block too (clamped to it: a dead buffer gets
+        // a copy nobody reads), so that the number of loads in flight is the same on every path and the wait
+        // before a set is parked lets the younger set's loads stay in flight.
+        Pieces pa, pb;
+        load_tiles(pa, far_blocks);
+        load_tiles(pb, min(far_blocks + 1, nblocks - 1));
+        lds_barrier();                                           // the far loop's LDS use is over
+        store_tiles(pa, 0);
+        load_tiles(pa, min(far_blocks + 2, nblocks - 1));
+        lds_barrier();
         float s_cur[16];
         block_scores(s_cur, tiles, far_blocks * kTB);
         int buf = 0;
-        for (int blk = far_blocks; blk < nblocks; ++blk) {
+        // one block: `next` holds the pieces of block blk + 1
+        auto do_block = [&](int blk, Pieces &next) {
             const char *base = tiles + buf * (3 * kTileBytes);
             const int nbuf = buf == 2 ? 0 : buf + 1;
             const bool more = blk + 1 < nblocks;
-            if (more) {
-                store_tiles(p0, nbuf);
-                p0 = p1;
-                if (blk + 3 < nblocks) load_tiles(p1, blk + 3);  // in flight for two iterations
-            }
-            __syncthreads();
+            store_tiles(next, nbuf);
+            load_tiles(next, min(blk + 3, nblocks - 1));         // in flight for two iterations
+            lds_barrier();                                       // LDS only: the tile loads stay in flight
             float s_next[16];
             if (more) block_scores(s_next, tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
             u32x4 vreg[2 * MT];
@@ -479,6 +493,10 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 for (int r = 0; r < 16; ++r) s_cur[r] = s_next[r];
             }
             buf = nbuf;
+        };
+        for (int blk = far_blocks; blk < nblocks; blk += 2) {
+            do_block(blk, pb);
+            if (blk + 1 < nblocks) do_block(blk + 1, pa);
         }
     }
 
@@ -568,6 +586,13 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
         attr_done = true;
     }
     const size_t blocks = (size_t)units * a.tiles * a.hgroups;
+    // XCD-aware order needs units * xsplit parts to deal out evenly over 8 XCDs and a unit to split evenly
+    a.xsplit = 0;
+    for (int sp = 1; sp <= 8; sp *= 2)
+        if ((units * sp) % 8 == 0) {
+            if ((a.tiles * a.hgroups) % sp == 0 && sp < 8) a.xsplit = sp;
+            break;
+        }
     hipLaunchKernelGGL((prefill_mfma_kernel<D>), dim3((unsigned)blocks), dim3(512), lds, s, a);
 }
 
