@@ -419,14 +419,15 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 *(u32x4 *)(base + 2 * kTileBytes + tid * 16) = pc.v;
             }
         };
-        // transposed score tile S^T[key][score row] = X[jb + key] . q, X tile in operand order at xt
+        // transposed score tile S^T[key][score row] = X[jb + key] . q, X tile in operand order at xt (a per-lane
+        // address: tile base + 16 * lane, so that every read below is that address plus a constant)
         auto score_tile = [&](const char *xt) -> f32x16 {
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 xa = *(const u32x4 *)(xt + (ks * 64 + lane) * 16);
+                const u32x4 xa = *(const u32x4 *)(xt + ks * 1024);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xa), as_bf16x8(qreg[ks]), acc, 0, 0, 0);
             }
             return acc;
@@ -471,32 +472,27 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         store_tiles(pa, 0);
         load_tiles(pa, min(far_blocks + 2, nblocks - 1));
         lds_barrier();
-        float s_cur[16];
-        block_scores(s_cur, tiles, far_blocks * kTB);
+        float s_a[16], s_b[16];                                  // raw scores of the current / the next block, in turn
+        const char *lane_tiles = tiles + lane * 16;              // per-lane view of the tile buffers
+        block_scores(s_a, lane_tiles, far_blocks * kTB);
         int buf = 0;
-        // one block: `next` holds the pieces of block blk + 1
-        auto do_block = [&](int blk, Pieces &next) {
-            const char *base = tiles + buf * (3 * kTileBytes);
+        // one block: `next` holds the pieces of block blk + 1, s_cur this block's scores, s_next receives the next one's
+        auto do_block = [&](int blk, Pieces &next, float (&s_cur)[16], float (&s_next)[16]) {
+            const char *base = lane_tiles + buf * (3 * kTileBytes);
             const int nbuf = buf == 2 ? 0 : buf + 1;
-            const bool more = blk + 1 < nblocks;
             store_tiles(next, nbuf);
             load_tiles(next, min(blk + 3, nblocks - 1));         // in flight for two iterations
             lds_barrier();                                       // LDS only: the tile loads stay in flight
-            float s_next[16];
-            if (more) block_scores(s_next, tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
+            if (blk + 1 < nblocks) block_scores(s_next, lane_tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
             u32x4 vreg[2 * MT];
 #pragma unroll
-            for (int k = 0; k < 2 * MT; ++k) vreg[k] = *(const u32x4 *)(base + 2 * kTileBytes + (k * 64 + lane) * 16);
+            for (int k = 0; k < 2 * MT; ++k) vreg[k] = *(const u32x4 *)(base + 2 * kTileBytes + k * 1024);
             softmax_pv(s_cur, a.scale_log2, vreg);
-            if (more) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s_cur[r] = s_next[r];
-            }
             buf = nbuf;
         };
         for (int blk = far_blocks; blk < nblocks; blk += 2) {
-            do_block(blk, pb);
-            if (blk + 1 < nblocks) do_block(blk + 1, pa);
+            do_block(blk, pb, s_a, s_b);
+            if (blk + 1 < nblocks) do_block(blk + 1, pa, s_b, s_a);
         }
     }
 
