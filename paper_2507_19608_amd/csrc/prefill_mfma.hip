@@ -63,11 +63,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 
-template <int D>
+// kGather: Eq. 4 as written for the far blocks (DA_SCORE_GATHER); otherwise every block goes through the matrix
+// cores (DA_SCORE_REBASE) and neither the fp16 Q tile nor the gather loop exists in the instantiation.
+template <int D, bool kGather>
 __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     extern __shared__ char lds_raw[];
+    constexpr size_t kQtBytes = kGather ? (size_t)D * kRows * 2 : 0;
     _Float16 *qt = (_Float16 *)lds_raw;                                   // [D][256] fp16, scaled by 2^qexp
-    float *ubuf = (float *)(lds_raw + (size_t)D * kRows * 2);             // [kTB][256]; then 8 entry rings
+    float *ubuf = (float *)(lds_raw + kQtBytes);                          // [kTB][256]; then 8 entry rings
     __shared__ float red[kWaves];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -112,40 +115,43 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         return a.Q + (((size_t)b * a.Hq + head0 + hh) * a.nq + (i - a.q_off)) * D;
     };
 
-    // ---- stage the Q tile: per-tile power-of-two scale so that the fp16 copy neither overflows nor
-    //      loses bits that matter (|q| max lands in [2^14, 2^15)).
-    float amax = 0.f;
-    for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
-        const int sr = idx / (D / 8), c8 = idx % (D / 8);
-        const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] << 16)));
-            amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] & 0xffff0000u)));
+    float qmul = 1.f;
+    if constexpr (kGather) {
+        // ---- stage the Q tile: per-tile power-of-two scale so that the fp16 copy neither overflows nor
+        //      loses bits that matter (|q| max lands in [2^14, 2^15)).
+        float amax = 0.f;
+        for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
+            const int sr = idx / (D / 8), c8 = idx % (D / 8);
+            const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
+    #pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] << 16)));
+                amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] & 0xffff0000u)));
+            }
         }
-    }
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) amax = fmaxf(amax, __shfl_xor(amax, s));
-    if (lane == 0) red[wave] = amax;
-    __syncthreads();
-    amax = red[0];
-#pragma unroll
-    for (int k = 1; k < kWaves; ++k) amax = fmaxf(amax, red[k]);
-    int qexp = 0;
-    if (amax > 0.f && amax < INFINITY) {
-        const int e = (int)((__float_as_uint(amax) >> 23) & 0xff) - 127;   // floor(log2 amax) for normal values
-        qexp = 14 - e;
-    }
-    const float qmul = __uint_as_float((uint32_t)(min(max(qexp, -126), 127) + 127) << 23);
-    for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
-        const int sr = idx % kRows, c8 = idx / kRows;    // consecutive threads -> consecutive score rows
-        const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float lo = __uint_as_float(raw[k] << 16) * qmul;
-            const float hi = __uint_as_float(raw[k] & 0xffff0000u) * qmul;
-            qt[(c8 * 8 + 2 * k) * kRows + sr] = (_Float16)lo;
-            qt[(c8 * 8 + 2 * k + 1) * kRows + sr] = (_Float16)hi;
+    #pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) amax = fmaxf(amax, __shfl_xor(amax, s));
+        if (lane == 0) red[wave] = amax;
+        __syncthreads();
+        amax = red[0];
+    #pragma unroll
+        for (int k = 1; k < kWaves; ++k) amax = fmaxf(amax, red[k]);
+        int qexp = 0;
+        if (amax > 0.f && amax < INFINITY) {
+            const int e = (int)((__float_as_uint(amax) >> 23) & 0xff) - 127;   // floor(log2 amax) for normal values
+            qexp = 14 - e;
+        }
+        qmul = __uint_as_float((uint32_t)(min(max(qexp, -126), 127) + 127) << 23);
+        for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
+            const int sr = idx % kRows, c8 = idx / kRows;    // consecutive threads -> consecutive score rows
+            const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
+    #pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float lo = __uint_as_float(raw[k] << 16) * qmul;
+                const float hi = __uint_as_float(raw[k] & 0xffff0000u) * qmul;
+                qt[(c8 * 8 + 2 * k) * kRows + sr] = (_Float16)lo;
+                qt[(c8 * 8 + 2 * k + 1) * kRows + sr] = (_Float16)hi;
+            }
         }
     }
     const float far_scale = a.scale_log2 / qmul;   // undo the tile scale together with the softmax scale
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int win_first = win_start(i0);         // smallest window start of the tile's rows
     const int win_last = win_start(i_last);      // largest
     const bool aligned = (win_first % kTB == 0) && (win_first == win_last);
-    const int far_blocks = a.rebase ? 0 : win_first / kTB;
+    const int far_blocks = kGather ? win_first / kTB : 0;
     const int nblocks = i_last / kTB + 1;
 
     __syncthreads();   // Q tile staged
@@ -238,11 +244,11 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // ring where the block's chunks sit back to back -> uniform 16-byte LDS reads that every lane
     // sees.  No scalar memory load sits in the inner loop, so all its LDS traffic completes in order
     // and the loop is software-pipelined two chunks deep (register sets A and B).
-    if (far_blocks > 0) {
+    if (kGather && far_blocks > 0) {
         const char *qtb = (const char *)qt;
         const uint32_t lane_off = (uint32_t)lane * 8u;
         constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 4 * 64;
-        char *ring = lds_raw + (size_t)D * kRows * 2 + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
+        char *ring = lds_raw + kQtBytes + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
         for (int o = lane * 16; o < kRingBytes; o += 64 * 16) *(u32x4 *)(ring + o) = u32x4{0u, 0u, 0u, 0u};
 
         auto pack_of = [&](int blk) -> uint32_t {   // chunk counts of this wave's 4 columns, one byte each
@@ -390,7 +396,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
         constexpr int kTileBytes = D * 64;                       // 32 keys x D channels, bf16
         constexpr int kPieces = kTileBytes / 16;                 // 16-byte pieces per tile (256 or 512)
-        char *tiles = lds_raw + (size_t)D * kRows * 2;           // [3 buffers][K, K_hat, V]
+        char *tiles = lds_raw + kQtBytes;                        // [3 buffers][K, K_hat, V]
         const bool has_piece = tid < kPieces;
         // K piece of thread tid: key row tid % 32, 8-channel segment tid / 32.  Its operand-order slot is then
         // tid itself, so a wave's 64 LDS stores are contiguous (a row-major thread-to-piece map made 16 lanes
@@ -574,11 +580,13 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.scale_log2 = p.scale_log2;
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
     const size_t lds_near = (size_t)9 * D * 64;
-    const size_t lds = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
+    const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
     static bool attr_done = false;
     if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds);
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gather);
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_near);
         attr_done = true;
     }
     const size_t blocks = (size_t)units * a.tiles * a.hgroups;
@@ -589,7 +597,10 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
             if ((a.tiles * a.hgroups) % sp == 0 && sp < 8) a.xsplit = sp;
             break;
         }
-    hipLaunchKernelGGL((prefill_mfma_kernel<D>), dim3((unsigned)blocks), dim3(512), lds, s, a);
+    if (p.rebase)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, false>), dim3((unsigned)blocks), dim3(512), lds_near, s, a);
+    else
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, true>), dim3((unsigned)blocks), dim3(512), lds_gather, s, a);
 }
 
 int prefill_mfma_n_pad(int n) { return (n + 63) / 64 * 64; }
