@@ -308,8 +308,9 @@ void launch_combine(da_cache *c, T *o, int nparts, hipStream_t s) {
     hipLaunchKernelGGL(decode_combine_kernel<T>, dim3(c->B * c->Hq), dim3(64), 0, s, *c, o, nparts);
 }
 
-// The decode step for bf16 caches: one wave per chunk of kChunk cached rows of one
-// unit, all query heads of the unit's group.
+// The decode step for bf16 caches in the row layout (head dims other than 64 / 128, decode windows below one
+// chunk, more than 32 query heads per KV head; the column-run layout has its own kernel): one wave per chunk of
+// kChunk cached rows of one unit, all query heads of the unit's group.
 //   0. the wave that owns the newest row appends it (D1);
 //   1. mask rows (lane = row) give the survivor count of every row, hence each row's start inside the
 //      chunk's survivor run (a wave prefix sum) - no offset table is read; the run itself is copied to
