@@ -90,7 +90,15 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    da.delta_attn_stage_timing_enable(True)
+    use_graph = args.graph and pieces == 1
+    if use_graph:   # the call allocates nothing and records no memset: replay it from a HIP graph (no launch gaps)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
+    da.delta_attn_stage_timing_enable(not use_graph)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -112,7 +120,8 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     outside_pairs = float(rows_out.sum()) * B * Hq
     causal_pairs = n * (n + 1) / 2.0 * B * Hq
     window_pairs = causal_pairs - outside_pairs
-    attn_ms = stages["attn"][0] / args.steps      # per step: one launch, or one per piece
+    # per step: one launch, or one per piece; under a graph no per-kernel events exist: the whole step stands in
+    attn_ms = stages["attn"][0] / args.steps if not use_graph else dt / args.steps * 1e3
     if mode == da.DA_SCORE_GATHER:
         alu_flops = 2.0 * sparse_macs
         mfma_flops = 2.0 * (window_pairs + causal_pairs) * d
@@ -143,7 +152,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.key()}: prefill B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} W{w.window} theta={theta:.6g} "
-                               f"p_jump={w.p_jump}", "score_mode": mode_name, "window_mode": args.window_mode, "pieces": pieces, "s_m": s_m, "s_c": s_c},
+                               f"p_jump={w.p_jump}", "score_mode": mode_name, "window_mode": args.window_mode, "pieces": pieces, "hip_graph": bool(use_graph), "s_m": s_m, "s_c": s_c},
         "stage_ms": {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items() if v[1]},
         "roofline": roof,
     }
@@ -325,6 +334,8 @@ def main():
                          "the headline) or the band of the W newest keys")
     ap.add_argument("--chunks", type=int, default=1,
                     help="prefill the sequence in this many equal pieces onto a growing cache (delta_attn_prefill_append)")
+    ap.add_argument("--graph", action="store_true",
+                    help="prefill: capture one call into a HIP graph and time replays (short prompts are launch-bound)")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

@@ -234,3 +234,34 @@ def test_generic_kernel_matches_on_matrix_core_shapes():
     torch.cuda.synchronize()
     assert torch.equal(m16, m32) and torch.equal(n16, n32)     # same keys -> same binary32 decisions
     assert (O16.float() - O32).abs().max().item() <= 2e-2
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_prefill_replays_from_a_captured_graph(mode):
+    """The prefill entry point allocates nothing and records no memset, so a caller may capture it into a HIP graph
+    (short prompts are launch-bound: six launches per call).  Replays - with eager work and synchronisations between
+    them - must reproduce the eager result bit for bit."""
+    B, Hq, Hkv, n, d, W, theta = 2, 4, 2, 200, 64, 16, 0.2
+    Q, K, V = rand_walk(81, B, Hq, n, d), rand_walk(82, B, Hkv, n, d), rand_walk(83, B, Hkv, n, d, clip=3.5)
+    Qd, Kd, Vd = (to_dev(x, "bf16") for x in (Q, K, V))
+    p = da.make_params(Qd, Kd, W, theta, 0.0, mode)
+    ws = torch.empty(da.delta_attn_prefill_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    out = (torch.empty_like(Qd), torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device="cuda"),
+           torch.empty((B, Hkv), dtype=torch.int64, device="cuda"))
+    eager = [t.clone() for t in da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, workspace=ws, out=out)]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, workspace=ws, out=out)
+    for rep in range(3):
+        for t in out:
+            t.zero_()
+        ws.random_(0, 255)                      # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(out, eager):
+            assert torch.equal(got, want), rep
+    ref = orc.prefill(Q, K, V, theta, W)
+    for h in range(Hq):
+        check_output(out[0][:, h], ref["O"][:, h], "bf16")
