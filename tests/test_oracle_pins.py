@@ -365,3 +365,18 @@ def test_no_knife_edges_on_benchmark_inputs(oracle):
     x = wl.generate(wl.C2, ("K",))["K"]
     m, _, _, knife = oracle.delta_scan(x[0, 3], wl.theta_for(wl.C2))
     assert knife == 0 and 0.2 < 1 - m.mean() < 0.9
+
+
+def test_strategy_study_reproduces_the_ordering_of_sec_3a():
+    """Sec. III-A ranks the three delta-matrix constructions (3) top-down key > (2) bottom-up query > (1) top-down
+    query by how many exact scores survive the causal mask; on the synthetic streams with an attention sink at key 0
+    the oracle-only study shows that ordering, and the adopted strategy (3) also has the smallest output error."""
+    from oracle import strategy_study as ss
+    Q, K, V = ss.inputs(11, 256, 32, sink=1.0)
+    r = ss.study(Q, K, V, 0.60)
+    s1, s2, s3 = r["(1) top-down query"], r["(2) bottom-up query"], r["(3) top-down key"]
+    for s in (s1, s2, s3):
+        assert abs(s["sparsity"] - 0.60) < 5e-3                     # compared at equal delta-matrix sparsity
+    assert s3["exact"] > s2["exact"] > s1["exact"]
+    assert s3["exact"] >= 256 and s2["exact"] >= 256 and s1["exact"] >= 1   # first column / last row / first row
+    assert s3["out_mean"] < min(s1["out_mean"], s2["out_mean"])
