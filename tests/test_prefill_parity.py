@@ -265,3 +265,13 @@ def test_prefill_replays_from_a_captured_graph(mode):
     ref = orc.prefill(Q, K, V, theta, W)
     for h in range(Hq):
         check_output(out[0][:, h], ref["O"][:, h], "bf16")
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n,d,W,dtype", [(1, 64, 4, "bf16"), (2, 128, 1, "bf16"), (33, 64, 40, "bf16"),
+                                         (1, 32, 1, "f32"), (31, 96, 5, "bf16")])
+def test_tiny_sequences(mode, n, d, W, dtype):
+    """Sequences shorter than a key block or a row tile: one token (the basis row attends to itself), two, 33."""
+    Q, K, V = rand_walk(91, 1, 2, n, d, dtype), rand_walk(92, 1, 1, n, d, dtype), rand_walk(93, 1, 1, n, d, dtype, clip=3.5)
+    run_case(Q, K, V, 0.2, W, dtype, mode)
+    run_case(Q, K, V, 0.2, W, dtype, mode, window_mode=da.DA_WINDOW_SLIDING)
