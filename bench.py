@@ -22,9 +22,9 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
-# fp32 FMA rate measured on this chip without packed-fp32 instructions, three register operands, at 2 waves per
-# SIMD: the instruction form and occupancy of the prefill kernel's gather loop (delta_attn_rate_probe, kind 2)
-MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 80.0
+# rate measured on this chip for the multiply-add of the prefill kernel's gather loop (fp16 x fp32 + fp32 in one
+# instruction, no packed-fp32 forms) at that kernel's occupancy of 2 waves per SIMD (delta_attn_rate_probe, kind 3)
+MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 71.3
 
 # HBM-side bytes per launch of the dominant kernel (fetch + write), measured once with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
@@ -285,7 +285,7 @@ def eq5_sweep(args, da, wl, torch, np):
 def hbm_read_probe(da, torch):
     """What this GPU sustains: streaming-read rate on a buffer of the decode step's size and on 1 GiB, with the access
     shape of the decode kernel (delta_attn_stream_read); bf16 MFMA and unpacked fp32 FMA rates from register-only
-    loops at 8 waves per SIMD (delta_attn_rate_probe).  Context for the roofline fractions, which use published peaks."""
+    loops at 2 and 8 waves per SIMD (delta_attn_rate_probe).  Context for the roofline fractions, which use published peaks."""
     out = {}
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     for name, nbytes, nbuf in (("108_MiB", 108 << 20, 4), ("1_GiB", 1 << 30, 2)):
@@ -302,21 +302,23 @@ def hbm_read_probe(da, torch):
                 best = min(best, e0.elapsed_time(e1) / launches)
         out[name] = {"ms": best, "GB/s": nbytes / (best * 1e-3) / 1e9}
         del xs
-    # arithmetic rates: register-only chains, 8 work groups of 4 waves per CU
+    # arithmetic rates: register-only chains, work groups of 4 waves (one per SIMD)
     fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 4000), ("fma_fp32_literal_multiplier", 1, 20000),
-                              ("fma_fp32_three_registers", 2, 20000)):
+    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 20000), ("fma_fp32_literal_multiplier", 1, 20000),
+                              ("fma_fp32_three_registers", 2, 20000), ("fma_mixed_fp16_fp32", 3, 20000)):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        best = float("inf")
-        for rep in range(4):
-            e0.record()
-            flop = da.delta_attn_rate_probe(kind, cus * 8, iters, fsink)
-            e1.record()
-            torch.cuda.synchronize()
-            if rep >= 1:
-                best = min(best, e0.elapsed_time(e1))
-        out[name] = {"ms": best, "TFLOP/s": flop / (best * 1e-3) / 1e12}
+        out[name] = {}
+        for waves_per_simd in (2, 8):                    # the prefill kernel's occupancy, and a well-filled chip
+            best = float("inf")
+            for rep in range(4):
+                e0.record()
+                flop = da.delta_attn_rate_probe(kind, cus * waves_per_simd, iters, fsink)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep >= 1:
+                    best = min(best, e0.elapsed_time(e1))
+            out[name][f"TFLOP/s_at_{waves_per_simd}_waves_per_simd"] = flop / (best * 1e-3) / 1e12
     return out
 
 

@@ -100,7 +100,8 @@ da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, 
  * runs `iters` rounds of independent register-only chains - kind 0: four 32x32x16 bf16 MFMA accumulations per
  * round; kind 1: sixteen fp32 fused multiply-adds per lane per round whose multiplier is an instruction literal
  * (two register sources each); kind 2: the same with all three operands in registers (compiled like the rest of the
- * library, i.e. without packed-fp32 instructions).  *flop receives the floating-point operations of the launch (host);
+ * library, i.e. without packed-fp32 instructions); kind 3: the same count of multiply-adds in the mixed form of the
+ * prefill kernel's gather loop (fp16 multiplicand widened by the instruction, fp32 multiplier and sum).  *flop receives the floating-point operations of the launch (host);
  * timed by the caller it gives the arithmetic rates this GPU sustains, to set beside the published peaks. */
 da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters, float *sink, double *flop,
                                 void *hip_stream);

@@ -122,7 +122,8 @@ def delta_attn_stream_read(buf, sink):
 
 
 def delta_attn_rate_probe(kind: int, work_groups: int, iters: int, sink) -> float:
-    """Measurement aid: launches the arithmetic-rate probe (0: bf16 MFMA, 1: fp32 FMA); returns its flop count."""
+    """Measurement aid: launches the arithmetic-rate probe (0: bf16 MFMA, 1 / 2: fp32 FMA with a literal / register multiplier,
+    3: fp16 x fp32 + fp32 FMA); returns its flop count."""
     flop = ctypes.c_double()
     _check(lib().delta_attn_rate_probe(int(kind), int(work_groups), int(iters), sink.data_ptr(), ctypes.byref(flop),
                                        _stream()), "delta_attn_rate_probe")

@@ -74,6 +74,30 @@ __global__ __launch_bounds__(256) void fma_rate_kernel(int iters, float *__restr
     for (int i = 0; i < 16; ++i) s += x[i];
     if (s == 12345.678f) *sink = s;
 }
+
+// The multiply-add of the prefill kernel's gather loop: fp16 multiplicand widened inside the instruction, fp32
+// multiplier and accumulator (v_fma_mix_f32).  Written as single instructions because the compiler would otherwise
+// widen the loop-invariant fp16 values once, outside the loop, and time plain fp32 multiply-adds.
+__global__ __launch_bounds__(256) void fma_mix_rate_kernel(int iters, float *__restrict__ sink) {
+    float x[16];
+    uint32_t qh[4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qh[i] = 0x34003400u + ((threadIdx.x + i) & 15);   // two fp16 values near 0.25
+    const float m = 0.999f + 1e-6f * (float)(threadIdx.x & 1);
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                asm volatile("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[1,0,0]" : "+v"(x[i]) : "v"(qh[i & 3]), "v"(m));
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += x[i];
+    if (s == 12345.678f) *sink = s;
+}
 }  // namespace
 
 extern "C" {
@@ -91,7 +115,7 @@ da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, 
 
 da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters, float *sink, double *flop,
                                 void *hip_stream) {
-    if (!sink || !flop || work_groups < 1 || iters < 1 || kind < 0 || kind > 2) return DA_ERR_INVALID_ARG;
+    if (!sink || !flop || work_groups < 1 || iters < 1 || kind < 0 || kind > 3) return DA_ERR_INVALID_ARG;
     (void)hipGetLastError();
     const double waves = 4.0 * work_groups;
     if (kind == 0) {
@@ -99,7 +123,10 @@ da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters
         *flop = waves * iters * 4.0 * (2.0 * 32 * 32 * 16);
     } else {
         iters = (iters + 7) / 8 * 8;
-        if (kind == 1)
+        if (kind == 3)
+            hipLaunchKernelGGL(fma_mix_rate_kernel, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters,
+                               sink);
+        else if (kind == 1)
             hipLaunchKernelGGL(fma_rate_kernel<true>, dim3(work_groups), dim3(256), 0, (hipStream_t)hip_stream, iters,
                                sink);
         else
