@@ -161,6 +161,14 @@ def test_c4_decode_llama_shape_sampled_batch():
     cache.close()
 
 
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 1), (64, 8, 2)])
+def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
+    """A long history: 32 768 cached tokens (512 sealed chunks per unit), then 70 steps, which cross a chunk seal."""
+    w = wl.Workload("L32K", 1, Hq, Hkv, d, 32768, 128, "bf16", seed=32, decode_steps=70, theta=0.11)
+    x = wl.generate(w)
+    run_decode(x["Q"], x["K"], x["V"], w.seq_len, w.decode_steps, 0.11, w.window, "bf16", W_prefill=512, check_every=23)
+
+
 @pytest.mark.parametrize("score_mode", [da.DA_SCORE_GATHER, da.DA_SCORE_REBASE])
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 @pytest.mark.parametrize("d,Hq,Hkv,W,Wd,chunks", [

@@ -121,8 +121,19 @@ def test_c2_llama_shape_full(mode):
     run_case(x["Q"], x["K"], x["V"], wl.theta_for(w), w.window, w.dtype, mode)
 
 
+_generated = {}
+
+
+def _inputs(w):
+    """Inputs of a workload, kept for the other parametrisations of the same test (one workload at a time)."""
+    if w not in _generated:
+        _generated.clear()
+        _generated[w] = wl.generate(w)
+    return _generated[w]
+
+
 def _sampled(w, mode, row_ranges, heads, window_mode=0):
-    x = wl.generate(w)
+    x = _inputs(w)
     d = w.head_dim
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     theta = wl.theta_for(w)
@@ -154,6 +165,15 @@ def test_c3_sliding_window_sampled(mode):
 @pytest.mark.parametrize("mode", MODES)
 def test_c5_long_context_sampled(mode):
     _sampled(wl.C5, mode, [(500, 530), (4090, 4110), (8170, 8192)], [3, 16])
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+def test_64k_tokens_sampled(mode, window_mode):
+    """A prompt of 65536 tokens (one KV head, four query heads, C5's head size and window): the running
+    Eq. 4 score of a late row is a sum over 65 000 columns, the softmax runs over as many keys."""
+    w = wl.Workload("L64K", 1, 4, 1, 128, 65536, 512, "bf16", seed=64, theta=0.11)
+    _sampled(w, mode, [(0, 8), (32760, 32776), (65528, 65536)], [0, 3], window_mode=window_mode)
 
 
 def test_c5_sweep_masks_and_sparsity():
