@@ -532,10 +532,15 @@ int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, v
         cus = 256;
     const int slots = c->plan_slots > 0 ? c->plan_slots : cus * (c->d == 64 ? 8 : 4);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
-    // one work group per unit whose waves split the unit's chunks and merge in LDS, if that fills at least half
-    // of the wave slots; the normalised output is written by this launch (returns 0: nothing left to merge)
+    // One work group per unit whose waves split the unit's chunks and merge in LDS (the normalised output is
+    // written by this launch; returns 0: nothing left to merge) pays when its waves fill the wave slots once:
+    // measured over 64..512 units, it wins from 3/4 of the slots at head_dim 64 and only with all of them at 128,
+    // and loses to single-wave work groups (which spread any unit count over every SIMD) below that and beyond
+    // one round.
     const int nw = c->d == 64 ? 8 : 4;
-    if (c->plan_merge == 1 || (c->plan_merge < 0 && (int64_t)units * nw * 2 >= slots)) {
+    const int64_t waves = (int64_t)units * nw;
+    const bool fills = waves <= slots && waves * (c->d == 64 ? 4 : 10) >= (int64_t)slots * (c->d == 64 ? 3 : 9);
+    if (c->plan_merge == 1 || (c->plan_merge < 0 && fills)) {
         const int nc = (nchunks + nw - 1) / nw;
         const dim3 grid(1, units), block(64 * nw);
         if (c->d == 64)
