@@ -244,6 +244,41 @@ def test_reruns_are_bit_identical_and_modes_agree():
     assert (outs[MODES[0]][0].float() - outs[MODES[1]][0].float()).abs().max().item() <= 2e-2
 
 
+def test_all_work_goes_to_the_callers_stream():
+    """Prefill with cache hand-off, chunked prefill and decode steps issued on a side stream, with inputs that are
+    produced on that stream right before: a launch or copy that went to another stream would read them too early.
+    Results must equal those of the default stream bit for bit."""
+    g = torch.Generator(device="cpu").manual_seed(77)
+    B, Hq, Hkv, n, d, W, theta = 2, 8, 2, 700, 64, 64, 0.1
+    host = [torch.cumsum(0.15 * torch.randn(B, h, n + 8, d, generator=g), 2).clamp(-3.5, 3.5).to(torch.bfloat16)
+            for h in (Hq, Hkv, Hkv)]
+
+    def run(stream):
+        with torch.cuda.stream(stream):
+            # big fill first, so that the copies below are still in flight when the library is called
+            junk = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)
+            Q, K, V = (x.cuda(non_blocking=False).clone() for x in host)
+            cache = da.Cache(B, Hq, Hkv, d, n + 8, 64, theta, torch.bfloat16)
+            outs = list(da.delta_attn_prefill(Q[:, :, :400].contiguous(), K[:, :, :400].contiguous(),
+                                              V[:, :, :400].contiguous(), theta, W, cache=cache))
+            outs += list(da.delta_attn_prefill_append(cache, Q[:, :, 400:n].contiguous(), K[:, :, 400:n].contiguous(),
+                                                      V[:, :, 400:n].contiguous(), theta, W))
+            for t in range(n, n + 8):
+                outs += list(da.delta_attn_decode(cache, Q[:, :, t].contiguous(), K[:, :, t].contiguous(),
+                                                  V[:, :, t].contiguous()))
+            outs.append(cache.nnz().clone())
+        torch.cuda.synchronize()
+        cache.close()
+        del junk
+        return outs
+
+    ref = run(torch.cuda.default_stream())
+    got = run(torch.cuda.Stream())
+    assert len(ref) == len(got)
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+
+
 def test_generic_kernel_matches_on_matrix_core_shapes():
     """The vector-ALU kernel (fp32 inputs, unusual head dims) and the matrix-core kernel implement the
     same path; run both on a bf16 d = 64 case through the fp32 route by widening the inputs."""
