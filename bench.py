@@ -282,6 +282,50 @@ def eq5_sweep(args, da, wl, torch, np):
     return rows
 
 
+def decode_sweep(args, da, wl, torch, np):
+    """Decode step time over head sizes and unit counts (batch x KV heads), 2048 cached tokens, decode window 128,
+    C4's generator at a fixed threshold: one work group per unit (waves merge on chip) against single-wave work
+    groups plus a merge launch - the measurements behind the default launch plan."""
+    rows = []
+    theta, n, steps, Wd = 0.11, 2048, 72, 128
+    for d in (64, 128):
+        for B, Hq, Hkv in ((8, 32, 8), (16, 32, 8), (32, 20, 5), (24, 32, 8), (32, 32, 8), (64, 32, 8)):
+            L = n + steps
+            Q, K, V = (torch.from_numpy(wl.round_to_dtype(
+                wl.ar1_jump(9, name, list(range(B)), H, L, d, 0.05, True), "bf16")).to(torch.bfloat16).cuda()
+                for name, H in (("Q", Hq), ("K", Hkv), ("V", Hkv)))
+            qs = [Q[:, :, t].contiguous() for t in range(n, L)]
+            ks = [K[:, :, t].contiguous() for t in range(n, L)]
+            vs = [V[:, :, t].contiguous() for t in range(n, L)]
+            Qp, Kp, Vp = Q[:, :, :n].contiguous(), K[:, :, :n].contiguous(), V[:, :, :n].contiguous()
+            row = {"head_dim": d, "units": B * Hkv}
+            for name, plan in (("one_group_per_unit_us", (1, 0)), ("single_wave_groups_us", (0, 0)), ("default_us", (-1, 0))):
+                cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
+                cache.set_launch_plan(*plan)
+                da.delta_attn_prefill(Qp, Kp, Vp, theta, 512, score_mode=da.DA_SCORE_REBASE, cache=cache)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for i in range(8):
+                    da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
+                e0.record()
+                for i in range(8, steps):
+                    da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
+                e1.record()
+                torch.cuda.synchronize()
+                row[name] = e0.elapsed_time(e1) / (steps - 8) * 1e3
+                if plan[0] < 0:
+                    s_m, _ = da.delta_attn_sparsity(cache.nnz(), L, d, Wd)
+                    t_avg = n + steps / 2
+                    row["algorithmic_mb_per_step"] = B * Hkv * t_avg * d * (2 + 1 / 8 + 2 * (1 - s_m)) / 1e6
+                    row["default_tb_per_s"] = row["algorithmic_mb_per_step"] / row[name]
+                cache.close()
+            rows.append(row)
+            sys.stderr.write(json.dumps(row) + "\n")
+            sys.stderr.flush()
+            del Q, K, V, qs, ks, vs, Qp, Kp, Vp
+            torch.cuda.empty_cache()
+    return rows
+
+
 def hbm_read_probe(da, torch):
     """What this GPU sustains: streaming-read rate on a buffer of the decode step's size and on 1 GiB, with the access
     shape of the decode kernel (delta_attn_stream_read); bf16 MFMA and unpacked fp32 FMA rates from register-only
@@ -348,6 +392,8 @@ def main():
     ap.add_argument("--gamma", type=float, default=0.05, help="Eq. 5 scaling factor for --eq5-sweep")
     ap.add_argument("--sweep", action="store_true",
                     help="only run the 12-point C5 sweep (threshold x jump rate), both score modes, and exit")
+    ap.add_argument("--decode-sweep", action="store_true",
+                    help="decode step time over head sizes and unit counts under both launch plans")
     ap.add_argument("--hbm-read-probe", action="store_true",
                     help="only measure the streaming-read rate of this GPU (context for the decode roofline) and exit")
     args = ap.parse_args()
@@ -364,6 +410,9 @@ def main():
     da.lib()
     if args.hbm_read_probe:
         print(json.dumps({"hbm_read_probe": hbm_read_probe(da, torch)}))
+        return
+    if args.decode_sweep:
+        print(json.dumps({"decode_sweep": decode_sweep(args, da, wl, torch, np)}))
         return
     if args.eq5_sweep:
         print(json.dumps({"eq5_sweep": eq5_sweep(args, da, wl, torch, np), "gamma": args.gamma, "w_max": 512,
