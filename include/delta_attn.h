@@ -180,9 +180,11 @@ const uint64_t *delta_attn_cache_nnz(const da_cache *c);           /* device [B,
 const uint32_t *delta_attn_cache_mask(const da_cache *c);
 /* How a decode step on this cache is laid out over the GPU (Sec. III-B decode stage; results do not
  * depend on it).  bf16 caches with head_dim 64 / 128 and decode_window >= 64 split the cached rows of a
- * (batch, KV head) unit into chunks of 64 rows; a wave walks `chunks per wave` consecutive chunks.
- *   merge_in_kernel  1: one work group per unit, its waves merge their partial results on chip;
- *                    0: single-wave work groups, partial results merged by a second launch;
+ * (batch, KV head) unit into chunks of 64 rows; a wave (head_dim 128: a pair of waves, 64 channels each) walks
+ * `chunks per wave` consecutive chunks.
+ *   merge_in_kernel  1: one work group per unit, its waves merge their partial results on chip (head_dim 64
+ *                       only; at head_dim 128 the value is accepted and ignored);
+ *                    0: one chunk walker per work group, partial results merged by a second launch;
  *                   -1: chosen per step from the unit count and the wave slots (default).
  *   wave_slots       resident waves the launch is sized for; 0 = derived from the device (default).
  * Other caches ignore the plan.  Returns DA_ERR_INVALID_ARG for NULL or values outside these ranges. */

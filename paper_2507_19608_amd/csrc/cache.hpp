@@ -21,15 +21,18 @@ struct da_cache {
                           //    head: the column-run layout below
     // per (batch, KV head) unit, all device memory:
     uint32_t *mask;       // [units][max_seq][d/32]   delta mask bits
-    // Surviving key values (the new reference values at the positions the mask marks), (kChunk + 1) * d
+    // Surviving key values (the new reference values at the positions the mask marks), run_room_stride(d)
     // elements of room per chunk.
     //   row layout (fast == 0): row after row, channels ascending inside a row, appended one row per step.
     //   column-run layout (fast == 1): written once per chunk, when its last row has arrived ("sealed"):
     //     for every channel in ascending order one run = the reference value held when the chunk starts,
     //     then the channel's surviving values in row order.  Rows of an unsealed chunk are always inside
-    //     the decode window (window >= kChunk), where raw keys are used, so they need no run.
-    void *surv;           // [units][max_chunks][(kChunk + 1) * d]
-    uint32_t *ccnt;       // [units][max_chunks]      elements stored in each chunk's room
+    //     the decode window (window >= kChunk), where raw keys are used, so they need no run.  At head_dim
+    //     128 the runs of channels 64.. start at the next multiple of 8 elements.
+    void *surv;           // [units][max_chunks][run_room_stride(d)]
+    uint32_t *ccnt;       // [units][max_chunks]      row layout: elements stored in the chunk's room; column-run
+                          //                          layout: that in the low half, the start of the runs of
+                          //                          channels 64.. (head_dim 64: the same number) in the high half
     void *ck;             // [units][nck][d]          ck[m] = reference key after row m*kChunk - 1 (m >= 1)
     void *khat;           // [units][d]               current reference key
     void *ring;           // [units][Wd][d]           raw key of position p at slot p % Wd
@@ -39,6 +42,10 @@ struct da_cache {
     uint64_t *nnz;        // [units]
     float *part;          // [B*Hq][max_chunks][d + 4] partial (o[d], m, l, 2 unused) rows of one decode step
 };
+
+// elements of room per chunk for the surviving values: one per key element, one carried-in value per channel, and
+// the alignment gap of the column-run layout
+__host__ __device__ inline size_t run_room_stride(int d) { return (size_t)(kChunk + 1) * d + 8; }
 
 // floats per partial row: o[d], running maximum, running sum, padded to a 16-byte multiple
 __host__ __device__ inline int part_stride(int d) { return d + 4; }

@@ -28,7 +28,7 @@ __device__ __forceinline__ size_t v_index(int unit, int vrows, int d, int t, int
 // surviving key values of one chunk of kChunk rows: row after row, channel order, room of (kChunk + 1) * d
 template <typename T>
 __device__ __forceinline__ T *surv_chunk(const da_cache &c, int unit, int chunk) {
-    return (T *)c.surv + ((size_t)unit * c.max_chunks + chunk) * ((size_t)(kChunk + 1) * c.d);
+    return (T *)c.surv + ((size_t)unit * c.max_chunks + chunk) * run_room_stride(c.d);
 }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -730,7 +730,7 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     const size_t units = (size_t)batch * n_kv_heads, es = elt_size(dtype), d = head_dim;
     bool ok = true;
     ok = ok && hipMalloc((void **)&c->mask, units * max_seq * (d / 32) * 4) == hipSuccess;
-    ok = ok && hipMalloc(&c->surv, units * (size_t)c->max_chunks * (kChunk + 1) * d * es) == hipSuccess;
+    ok = ok && hipMalloc(&c->surv, units * (size_t)c->max_chunks * run_room_stride(d) * es) == hipSuccess;
     ok = ok && hipMalloc((void **)&c->ccnt, units * (size_t)c->max_chunks * 4) == hipSuccess;
     ok = ok && hipMalloc(&c->ck, units * c->nck * d * es) == hipSuccess;
     ok = ok && hipMalloc(&c->khat, units * d * es) == hipSuccess;

@@ -29,8 +29,12 @@ __device__ __forceinline__ size_t v16_index(int unit, int vrows, int d, int t, i
 }
 
 __device__ __forceinline__ bf16_t *run_room(const da_cache &c, int unit, int chunk) {
-    return (bf16_t *)c.surv + ((size_t)unit * c.max_chunks + chunk) * ((size_t)(kChunk + 1) * c.d);
+    return (bf16_t *)c.surv + ((size_t)unit * c.max_chunks + chunk) * run_room_stride(c.d);
 }
+
+// The runs of channels 64.. (head_dim 128) start at a multiple of 8 elements, so that the decode step can copy
+// either half of a chunk's runs with 16-byte pieces.
+__device__ __forceinline__ uint32_t second_half_start(uint32_t first_half_elems) { return (first_half_elems + 7u) & ~7u; }
 
 // Seals chunk `chunk` of one unit (one wave): for every channel the run {reference value held when the
 // chunk starts, surviving values in row order}, runs stored one after another in channel order.
@@ -41,7 +45,7 @@ __device__ void seal_chunk(const da_cache &c, int unit, int chunk, int lane, con
                            RowFn rowp, HeldFn heldp) {
     const int d = c.d, wpr = d >> 5;
     bf16_t *room = run_room(c, unit, chunk);
-    uint32_t base = 0;
+    uint32_t base = 0, half = 0;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int ch = c0 + lane;
         uint64_t cm = 0;
@@ -53,8 +57,13 @@ __device__ void seal_chunk(const da_cache &c, int unit, int chunk, int lane, con
         for (int r = 0; r < kChunk; ++r)
             if ((cm >> r) & 1ull) room[p++] = rowp(r)[ch];
         base += total;
+        if (c0 == 0) {
+            half = base;                                     // elements of channels 0..63
+            if (d > kWave) base = second_half_start(base);
+        }
     }
-    if (lane == 0) c.ccnt[(size_t)unit * c.max_chunks + chunk] = base;
+    // low half: elements in the room (the gap included); high half: where the runs of channels 64.. start
+    if (lane == 0) c.ccnt[(size_t)unit * c.max_chunks + chunk] = base | ((d > kWave ? second_half_start(half) : base) << 16);
 }
 
 // Seal from the raw-key ring: runs right after the step that appended the chunk's last row.
@@ -165,6 +174,7 @@ __global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, in
             Vfull[o] = ((const bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)];
         }
         base += total;
+        if (c0 == 0 && d > kWave) base = second_half_start(base);
     }
 }
 
@@ -199,44 +209,50 @@ __device__ void append_row_runs(const da_cache &c, int unit, int lane, const bf1
     if (lane == 0) c.nnz[unit] = (t == 0 ? 0ull : c.nnz[unit]) + fired;
 }
 
-// One decode step: one wave per (run of `nc` consecutive chunks, unit), all query heads of the unit's group.
+// One decode step: per (run of `nc` consecutive chunks, unit) one wave at head_dim 64, two waves at head_dim
+// 128 that each take 64 of the channels (all query heads of the unit's group either way).
 // A wave walks its chunks in order with flash-style running (max, sum, output) in registers, and asks for
 // the next chunk's mask rows and runs while it works on the current one; a launch is sized so that all of
 // its waves are resident at once (work-group dispatch, not memory, bounds a launch of one chunk per wave).
 // Per chunk:
 //   0. the wave that owns the newest row appends it (D1);
-//   1. history chunks (rows left of the decode window): the chunk's runs are copied to LDS; lane = row j
-//      takes, for every channel c, element B_c + #{marked rows <= j of channel c} of the staged runs,
-//      which is the reference value k_hat(j)[c] (Eq. 3) - by telescoping Eq. 4 the history score of
+//   1. history chunks (rows left of the decode window): the runs of the wave's 64 channels are copied to LDS;
+//      lane = row j takes, for every channel c, element B_c + #{marked rows <= j of channel c} of the staged
+//      runs, which is the reference value k_hat(j)[c] (Eq. 3) - by telescoping Eq. 4 the history score of
 //      row j is q . k_hat(j).  The column mask of a channel is the wave ballot of that channel's bit in
 //      the lanes' mask rows; the count is one mbcnt pair, B_c a running scalar sum of the ballots'
 //      popcounts.  Reads of one instruction touch at most 65 consecutive elements: no bank conflicts.
 //      Window rows (lane = row again) are 128-bit loads from the raw-key ring, the newest from k_new.
-//   2. a lane now holds a whole key row; one permlane32 swap per register pair turns that into the
+//   2. a lane now holds 64 channels of a key row; one permlane32 swap per register pair turns that into the
 //      32x32x16 operand order (lane l: row l % 32, channels 16 s + 8 (l / 32)..+7 of contraction step s);
-//   3. scores S[row][head] on the matrix cores (heads padded to 32 columns); softmax update in the
-//      accumulator registers (lane = head, 32 rows per lane, the other 32 in lane + 32);
+//   3. scores S[row][head] on the matrix cores (heads padded to 32 columns); at head_dim 128 the two waves
+//      exchange their halves of the contraction through LDS and both hold the full scores; softmax update in
+//      the accumulator registers (lane = head, 32 rows per lane, the other 32 in lane + 32);
 //   4. the accumulator registers, rounded to bf16, are the B operand of O^T += V^T P^T as they stand, because
-//      the V cache stores each group of 16 rows in exactly that order; O^T keeps lane = head, so the
-//      running rescale needs no cross-lane traffic.
-// The wave's (o, m, l) goes to scratch; a second launch merges the partials of a head.
+//      the V cache stores each group of 16 rows in exactly that order; O^T (the wave's 64 channels) keeps
+//      lane = head, so the running rescale needs no cross-lane traffic.
+// The wave's (o, m, l) goes to scratch and a second launch merges the partials of a head - or, with NW > 1
+// (head_dim 64), the waves of the work group hold every row of the unit and merge in LDS.
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, const bf16_t *__restrict__ q_new,
-                                                                    const bf16_t *__restrict__ k_new,
-                                                                    const bf16_t *__restrict__ v_new,
-                                                                    bf16_t *__restrict__ o_out,
-                                                                    uint32_t *__restrict__ mask_row, int t,
-                                                                    float scale_log2, int nc) {
-    constexpr int WPR = D / 32, KS = D / 16, CT = D / 32, NK = D / 2;
-    constexpr int kRoom = (kChunk + 1) * D;                  // elements
-    constexpr int kPieces = (kRoom + 511) / 512;             // 1 KiB copies (16 bytes per lane) that cover the room
+__global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel(da_cache c, const bf16_t *__restrict__ q_new,
+                                                                              const bf16_t *__restrict__ k_new,
+                                                                              const bf16_t *__restrict__ v_new,
+                                                                              bf16_t *__restrict__ o_out,
+                                                                              uint32_t *__restrict__ mask_row, int t,
+                                                                              float scale_log2, int nc) {
+    constexpr int H = D / 64;                                // waves that share a chunk, 64 channels each
+    static_assert(H == 1 || NW == 1, "the on-chip merge is built for head_dim 64");
+    constexpr int WPR = D / 32;                              // mask words per row
+    constexpr int KS = 4, CT = 2, NK = 32;                   // per wave: contraction steps, output tiles, kreg pairs
+    constexpr int kPieces = ((kChunk + 1) * 64 + 511) / 512; // 1 KiB copies (16 bytes per lane) that cover 64 channels' runs
     // two staging areas for the runs of a chunk, used in turn: separate arrays, so that reads of one are known
     // not to touch the other while its copy is still in flight
-    __shared__ __attribute__((aligned(16))) bf16_t stage_a_all[NW][kPieces * 512];
-    __shared__ __attribute__((aligned(16))) bf16_t stage_b_all[NW][kPieces * 512];
+    __shared__ __attribute__((aligned(16))) bf16_t stage_a_all[NW * H][kPieces * 512];
+    __shared__ __attribute__((aligned(16))) bf16_t stage_b_all[NW * H][kPieces * 512];
     __shared__ float ml_all[NW][32][2];
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    bf16_t *stage_a = stage_a_all[wave], *stage_b = stage_b_all[wave];
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = wv / H, half = wv % H, coff = 64 * half;   // part inside the work group; channel half
+    bf16_t *stage_a = stage_a_all[wv], *stage_b = stage_b_all[wv];
     const int part_i = blockIdx.x * NW + wave, unit = blockIdx.y, lane = threadIdx.x & 63;
     const int nchunks = t / kChunk + 1;
     const int c_begin = part_i * nc, c_end = min(c_begin + nc, nchunks);
@@ -247,69 +263,73 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
     // rows of chunk ch left of the decode window (> 0 only for sealed chunks, because Wd >= kChunk)
     auto hist_of = [&](int ch) { return min(max(win_begin - ch * kChunk, 0), min(kChunk, t + 1 - ch * kChunk)); };
 
-    // q operands (B operand of the score contraction): lane l = head l % 32, channels 16 s + 8 (l / 32)..+7
+    // q operands (B operand of the score contraction): lane l = head l % 32, channels coff + 16 s + 8 (l / 32)..+7
     u32x4 qop[KS];
     {
-        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + min(n32, g - 1)) * D;
+        const bf16_t *qrow = q_new + ((size_t)b * c.Hq + hk * g + min(n32, g - 1)) * D + coff;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             qop[s] = *(const u32x4 *)(qrow + 16 * s + 8 * kap);
             if (n32 >= g) qop[s] = u32x4{0u, 0u, 0u, 0u};
         }
     }
-    // History chunk ch: its runs go straight from global memory to the LDS staging area (128-bit LDS-direct
-    // loads: lane i of a copy lands at base + 16 i), `total` elements of them; its mask rows, lane = row.
-    auto copy_runs = [&](int ch, uint32_t total, bf16_t *sv) {
-        const bf16_t *runs = run_room(c, unit, ch);
+    // History chunk ch: the runs of this wave's channels go straight from global memory to the LDS staging area
+    // (128-bit LDS-direct loads: lane i of a copy lands at base + 16 i); its mask rows, lane = row.
+    // cnt: the chunk's packed element counts (elements in the room | start of the runs of channels 64.. << 16).
+    auto copy_runs = [&](int ch, uint32_t cnt, bf16_t *sv) {
+        const uint32_t total = cnt & 0xffffu, second = cnt >> 16;
+        const uint32_t first = half ? second : 0u;                       // where this wave's runs start (a multiple of 8)
+        const uint32_t len = H == 1 ? total : (half ? total - second : second);
+        const bf16_t *runs = run_room(c, unit, ch) + first;
 #pragma unroll
         for (int p = 0; p < kPieces; ++p)
-            if ((uint32_t)p * 512u < total && p * 512 + lane * 8 + 8 <= kRoom)
+            if ((uint32_t)p * 512u < len && first + p * 512 + lane * 8 + 8 <= (uint32_t)run_room_stride(D))
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(runs + p * 512 + lane * 8),
                                                  (__attribute__((address_space(3))) void *)(sv + p * 512), 16, 0, 0);
     };
     auto total_of = [&](int ch) -> uint32_t {
         return hist_of(ch) > 0 ? __builtin_amdgcn_readfirstlane(c.ccnt[(size_t)unit * c.max_chunks + ch]) : 0u;
     };
-    uint32_t mk_n[WPR];
+    uint32_t mk_n[2];
     auto request_masks = [&](int ch) {
         if (hist_of(ch) > 0) {
-            const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + ch * kChunk + lane) * WPR;
+            const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + ch * kChunk + lane) * WPR + 2 * half;
 #pragma unroll
-            for (int w = 0; w < WPR; ++w) mk_n[w] = Mp[w];
+            for (int w = 0; w < 2; ++w) mk_n[w] = Mp[w];
         }
     };
     if (c_begin < c_end) {
         copy_runs(c_begin, total_of(c_begin), stage_a);
         request_masks(c_begin);
     }
-    uint32_t tot_v = 0;                                      // element count of the chunk after the next one's copy
+    uint32_t tot_v = 0;                                      // element counts of the chunk after the next one's copy
     if (c_begin + 1 < c_end && hist_of(c_begin + 1) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + c_begin + 1];
 
     f32x16 o[CT];                                            // O^T: lane = head, register r of tile ct =
-#pragma unroll                                               // channel 32 ct + 8 (r / 4) + 4 (l / 32) + r % 4
+#pragma unroll                                               // channel coff + 32 ct + 8 (r / 4) + 4 (l / 32) + r % 4
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;                    // l_run: this lane half's share of the sum
 
-    auto do_chunk = [&](int chunk, const bf16_t *sv, bf16_t *sv_next) {
+    auto do_chunk = [&](int chunk, bf16_t *sv, bf16_t *sv_next, const bf16_t *sv_partner) {
         const bool newest = chunk == nchunks - 1;            // this wave owns row t
         const int r0 = chunk * kChunk;
         const int nrows = min(kChunk, t + 1 - r0);
         const int hist_rows = hist_of(chunk);
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this chunk's runs have landed in LDS
         // the next chunk's runs and mask rows, and the element count of the one after it, fly in meanwhile
-        uint32_t mk[WPR];
+        uint32_t mk[2];
 #pragma unroll
-        for (int w = 0; w < WPR; ++w) mk[w] = mk_n[w];
+        for (int w = 0; w < 2; ++w) mk[w] = mk_n[w];
         if (chunk + 1 < c_end) {
             copy_runs(chunk + 1, __builtin_amdgcn_readfirstlane(tot_v), sv_next);
             request_masks(chunk + 1);
             tot_v = 0;
             if (chunk + 2 < c_end && hist_of(chunk + 2) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + chunk + 2];
         }
-        // V operands of the chunk (needed last, requested first): lane l = channel 32 ct + l % 32, rows of lane
-        // half l / 32 of each 16-row group; the newest row is patched in from v_new
+        // V operands of the chunk (needed last, requested first): lane l = channel coff + 32 ct + l % 32, rows of
+        // lane half l / 32 of each 16-row group; the newest row is patched in from v_new
         u32x4 vop[CT][2][2];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
@@ -317,7 +337,7 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
             for (int T = 0; T < 2; ++T)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
-                    const int row16 = r0 + 32 * T + 16 * s2, ch = 32 * ct + n32;
+                    const int row16 = r0 + 32 * T + 16 * s2, ch = coff + 32 * ct + n32;
                     vop[ct][T][s2] = *(const u32x4 *)((const bf16_t *)c.V +
                                                       (((size_t)unit * (c.vrows >> 4) + (row16 >> 4)) * D + ch) * 16 + 8 * kap);
                 }
@@ -327,7 +347,7 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
             const int Tn = (t >> 5) & 1, sn = (t >> 4) & 1;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const uint32_t vn = v_new[(size_t)unit * D + 32 * ct + n32];
+                const uint32_t vn = v_new[(size_t)unit * D + coff + 32 * ct + n32];
 #pragma unroll
                 for (int TT = 0; TT < 2; ++TT)
 #pragma unroll
@@ -341,16 +361,16 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
                         }
             }
             // 0. the new row goes into the cache (other waves of this launch never read what is written here)
-            append_row_runs(c, unit, lane, k_new, v_new, mask_row, t);
+            if (half == 0) append_row_runs(c, unit, lane, k_new, v_new, mask_row, t);
         }
 
-        // 1. one key row per lane
+        // 1. 64 channels of one key row per lane
         uint32_t kreg[NK];
         if (hist_rows > 0) {
             uint32_t run = 0;                                // uniform: survivors of the channels before this one
             const char *svb = (const char *)sv;
 #pragma unroll
-            for (int ch = 0; ch < D; ch += 2) {
+            for (int ch = 0; ch < 64; ch += 2) {
                 uint32_t val[2];
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
@@ -368,10 +388,10 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
             if (lane >= hist_rows) {
                 if (lane < nrows) {
                     const int row = r0 + lane;
-                    const bf16_t *src = row == t ? k_new + (size_t)unit * D
-                                                 : (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * D;
+                    const bf16_t *src = (row == t ? k_new + (size_t)unit * D
+                                                  : (const bf16_t *)c.ring + ((size_t)unit * c.Wd + row % c.Wd) * D) + coff;
 #pragma unroll
-                    for (int i = 0; i < D / 8; ++i) {
+                    for (int i = 0; i < 8; ++i) {
                         const u32x4 v = *(const u32x4 *)(src + 8 * i);
                         kreg[4 * i] = v[0];
                         kreg[4 * i + 1] = v[1];
@@ -387,7 +407,7 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
             // wait lands after the join and history chunks would drain their in-flight V and run copies there
             __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         }
-        // 2. operand order: kop[T][s] = rows 32 T + l % 32, channels 16 s + 8 (l / 32)..+7
+        // 2. operand order: kop[T][s] = rows 32 T + l % 32, channels coff + 16 s + 8 (l / 32)..+7
         u32x4 kop[2][KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s)
@@ -407,6 +427,27 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
             for (int s = 0; s < KS; ++s)
                 acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[T][s]),
                                                                  __builtin_bit_cast(bf16x8, qop[s]), acc[T], 0, 0, 0);
+        }
+        if (H == 2) {
+            // the other wave contracted the other 64 channels: the halves meet in the staging areas both waves have
+            // just finished reading (register r of lane l at float 64 r + l: conflict free), and are added in the
+            // same order by both, so both hold the same scores
+            float *mine = (float *)sv;
+            const float *theirs = (const float *)sv_partner;
+            lds_barrier();                                   // both waves are done gathering from these areas
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[(16 * T + r) * 64 + lane] = acc[T][r];
+            lds_barrier();
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = theirs[(16 * T + r) * 64 + lane];
+                    acc[T][r] = half ? x + acc[T][r] : acc[T][r] + x;
+                }
+            lds_barrier();                                   // the areas may be copied into again
         }
         if (nrows < kChunk) {                                // only the newest chunk has rows that do not exist yet
 #pragma unroll
@@ -449,22 +490,23 @@ __global__ __launch_bounds__(64 * NW) void decode_step_runs_kernel(da_cache c, c
                     o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[ct][T][s2]),
                                                                     __builtin_bit_cast(bf16x8, pa[T][s2]), o[ct], 0, 0, 0);
     };
+    const bf16_t *partner_a = stage_a_all[wv ^ (H - 1)], *partner_b = stage_b_all[wv ^ (H - 1)];
     for (int chunk = c_begin; chunk < c_end; chunk += 2) {
-        do_chunk(chunk, stage_a, stage_b);
-        if (chunk + 1 < c_end) do_chunk(chunk + 1, stage_b, stage_a);
+        do_chunk(chunk, stage_a, stage_b, partner_a);
+        if (chunk + 1 < c_end) do_chunk(chunk + 1, stage_b, stage_a, partner_b);
     }
     const float l_all = l_run + __shfl_xor(l_run, 32);
     if (NW == 1) {
-        // partial (o, m, l) of this wave's rows, merged by a second launch
+        // partial (o, m, l) of this wave's rows and channels, merged by a second launch
         if (n32 < g) {
             float *out = c.part + (((size_t)b * c.Hq + hk * g + n32) * c.max_chunks + part_i) * part_stride(D);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq)
-                    *(f32x4 *)(out + 32 * ct + 8 * rq + 4 * kap) =
+                    *(f32x4 *)(out + coff + 32 * ct + 8 * rq + 4 * kap) =
                         f32x4{o[ct][4 * rq], o[ct][4 * rq + 1], o[ct][4 * rq + 2], o[ct][4 * rq + 3]};
-            if (kap == 0) {
+            if (kap == 0 && half == 0) {
                 out[D] = m_run;
                 out[D + 1] = l_all;
             }
@@ -525,43 +567,40 @@ void expand_cache_runs(da_cache *c, int t0, int n_k, void *Kfull, void *Hfull, v
 int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,
                      float scale_log2, hipStream_t s) {
     const int units = c->B * c->Hkv, nchunks = t / kChunk + 1;
-    // A launch is sized so that all of its waves are resident at once (4 SIMDs per CU; the kernel's register
-    // budget allows 2 waves per SIMD at head_dim 64, 1 at 128).
+    // A launch is sized so that all of its waves are resident at once: 4 SIMDs per CU, 2 waves per SIMD by the
+    // kernel's registers and LDS.  At head_dim 128 two waves share every chunk, so half as many chunk walkers fit.
     static int cus = 0;
     if (!cus && (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1))
         cus = 256;
-    const int slots = c->plan_slots > 0 ? c->plan_slots : cus * (c->d == 64 ? 8 : 4);
+    const int slots = (c->plan_slots > 0 ? c->plan_slots : cus * 8) / (c->d == 64 ? 1 : 2);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
-    // One work group per unit whose waves split the unit's chunks and merge in LDS (the normalised output is
-    // written by this launch; returns 0: nothing left to merge) pays when its waves fill the wave slots once:
-    // measured over 64..512 units, it wins from 3/4 of the slots at head_dim 64 and only with all of them at 128,
-    // and loses to single-wave work groups (which spread any unit count over every SIMD) below that and beyond
-    // one round.
-    const int nw = c->d == 64 ? 8 : 4;
-    const int64_t waves = (int64_t)units * nw;
-    const bool fills = waves <= slots && waves * (c->d == 64 ? 4 : 10) >= (int64_t)slots * (c->d == 64 ? 3 : 9);
-    if (c->plan_merge == 1 || (c->plan_merge < 0 && fills)) {
-        const int nc = (nchunks + nw - 1) / nw;
-        const dim3 grid(1, units), block(64 * nw);
-        if (c->d == 64)
-            hipLaunchKernelGGL((decode_step_runs_kernel<64, 8>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row,
-                               t, scale_log2, nc);
-        else
-            hipLaunchKernelGGL((decode_step_runs_kernel<128, 4>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o,
-                               mask_row, t, scale_log2, nc);
-        return 0;
+    // head_dim 64: one 8-wave work group per unit whose waves split the unit's chunks and merge in LDS (the
+    // normalised output is written by this launch; returns 0: nothing left to merge) pays when its waves fill the
+    // wave slots once: measured over 64..512 units, it wins from 3/4 of the slots on, and loses to single-wave
+    // work groups (which spread any unit count over every SIMD) below that and beyond one round.
+    if (c->d == 64) {
+        const int nw = 8;
+        const int64_t waves = (int64_t)units * nw;
+        const bool fills = waves <= slots && waves * 4 >= (int64_t)slots * 3;
+        if (c->plan_merge == 1 || (c->plan_merge < 0 && fills)) {
+            const int nc = (nchunks + nw - 1) / nw;
+            hipLaunchKernelGGL((decode_step_runs_kernel<64, 8>), dim3(1, units), dim3(64 * nw), 0, s, *c, qq, kk, vv,
+                               (bf16_t *)o, mask_row, t, scale_log2, nc);
+            return 0;
+        }
     }
-    // otherwise single-wave work groups, as few chunks per wave as keep the launch resident; partial rows
-    int nc = (int)(((int64_t)units * nchunks + slots - 1) / slots);
+    // otherwise one chunk walker (1 or 2 waves) per work group, as few chunks each as keep the launch resident;
+    // partial rows
+    int nc = (int)(((int64_t)units * nchunks + slots - 1) / max(slots, 1));
     if (nc < 1) nc = 1;
     const int nparts = (nchunks + nc - 1) / nc;
-    const dim3 grid(nparts, units), block(64);
+    const dim3 grid(nparts, units);
     if (c->d == 64)
-        hipLaunchKernelGGL((decode_step_runs_kernel<64, 1>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row, t,
-                           scale_log2, nc);
-    else
-        hipLaunchKernelGGL((decode_step_runs_kernel<128, 1>), grid, block, 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row,
+        hipLaunchKernelGGL((decode_step_runs_kernel<64, 1>), grid, dim3(64), 0, s, *c, qq, kk, vv, (bf16_t *)o, mask_row,
                            t, scale_log2, nc);
+    else
+        hipLaunchKernelGGL((decode_step_runs_kernel<128, 1>), grid, dim3(128), 0, s, *c, qq, kk, vv, (bf16_t *)o,
+                           mask_row, t, scale_log2, nc);
     return nparts;
 }
 
