@@ -152,8 +152,9 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
  * p->window_mode), exactly as rows t0 .. t0 + m - 1 of one prefill over the whole sequence would, and the
  * new rows are appended to the cache.
  *   Q, O [B, Hq, m, d];  K, V [B, Hkv, m, d];  mask_bits [B, Hkv, m, d/32], nnz [B, Hkv]: the new rows only
- *   cache     bf16, head_dim 64 or 128, decode_window >= 64 (and >= p->window unless the cache is empty:
- *             the exact scores against cached keys are taken from the cache's ring of raw keys),
+ *   cache     bf16, head_dim 64 or 128, decode_window >= min(64, max_seq) (and >= min(p->window, t0 + m) unless the cache
+ *             is empty: the exact scores against cached keys are taken from the cache's ring of raw keys;
+ *             a decode_window above max_seq counts as max_seq),
  *             at most 32 query heads per KV head; otherwise DA_ERR_UNSUPPORTED
  *   workspace device scratch of at least delta_attn_prefill_append_workspace_bytes(p, cache), which
  *             depends on the cache length at the time of the call (0 if the arguments are invalid)
@@ -179,7 +180,7 @@ const uint64_t *delta_attn_cache_nnz(const da_cache *c);           /* device [B,
 /* mask bits of the cached rows: device [B, Hkv, max_seq, d/32] (rows >= length undefined) */
 const uint32_t *delta_attn_cache_mask(const da_cache *c);
 /* How a decode step on this cache is laid out over the GPU (Sec. III-B decode stage; results do not
- * depend on it).  bf16 caches with head_dim 64 / 128 and decode_window >= 64 split the cached rows of a
+ * depend on it).  bf16 caches with head_dim 64 / 128 and decode_window >= min(64, max_seq) split the cached rows of a
  * (batch, KV head) unit into chunks of 64 rows; a wave (head_dim 128: a pair of waves, 64 channels each) walks
  * `chunks per wave` consecutive chunks.
  *   merge_in_kernel  1: one work group per unit, its waves merge their partial results on chip (head_dim 64

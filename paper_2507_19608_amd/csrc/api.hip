@@ -247,7 +247,10 @@ da_status check_append(const da_prefill_params *p, const da_cache *c) {
         c->dtype != p->dtype || c->theta != p->theta)
         return DA_ERR_STATE;
     if (c->len + p->seq_len > c->max_seq) return DA_ERR_STATE;
-    if (c->len > 0 && p->window > c->Wd) return DA_ERR_UNSUPPORTED;   // raw keys of the window come from the ring
+    // raw keys of a window come from the ring of the decode_window newest rows; no window reaches back further
+    // than the sequence is long
+    const int64_t reach = p->window < c->len + p->seq_len ? p->window : c->len + p->seq_len;
+    if (c->len > 0 && reach > c->Wd) return DA_ERR_UNSUPPORTED;
     return DA_OK;
 }
 }  // namespace

@@ -17,7 +17,7 @@ struct da_cache {
     int vrows;            // max_seq rounded up to a whole chunk (row capacity of V)
     int plan_merge;       // launch plan of the column-run layout: -1 auto, 0 second launch, 1 merge in the kernel
     int plan_slots;       // wave slots a launch is sized for, 0 = from the device
-    int fast;             // 1: bf16, head_dim 64 or 128, decode window >= kChunk, <= 32 query heads per KV
+    int fast;             // 1: bf16, head_dim 64 or 128, decode window >= kChunk or >= max_seq, <= 32 query heads per KV
                           //    head: the column-run layout below
     // per (batch, KV head) unit, all device memory:
     uint32_t *mask;       // [units][max_seq][d/32]   delta mask bits
@@ -27,7 +27,7 @@ struct da_cache {
     //   column-run layout (fast == 1): written once per chunk, when its last row has arrived ("sealed"):
     //     for every channel in ascending order one run = the reference value held when the chunk starts,
     //     then the channel's surviving values in row order.  Rows of an unsealed chunk are always inside
-    //     the decode window (window >= kChunk), where raw keys are used, so they need no run.  At head_dim
+    //     the decode window (window >= kChunk, or the whole cache), where raw keys are used, so they need no run.  At head_dim
     //     128 the runs of channels 64.. start at the next multiple of 8 elements.
     void *surv;           // [units][max_chunks][run_room_stride(d)]
     uint32_t *ccnt;       // [units][max_chunks]      row layout: elements stored in the chunk's room; column-run

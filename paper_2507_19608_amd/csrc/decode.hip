@@ -721,7 +721,9 @@ da_status delta_attn_cache_create(da_cache **out, int32_t batch, int32_t n_q_hea
     c->vrows = (max_seq + kChunk - 1) / kChunk * kChunk;
     c->plan_merge = -1;
     c->plan_slots = 0;
-    c->fast = dtype == DA_BF16 && (head_dim == 64 || head_dim == 128) && c->Wd >= kChunk &&
+    // the column-run layout needs every row of an unsealed chunk inside the decode window: a window of at least
+    // one chunk, or one that covers the whole cache
+    c->fast = dtype == DA_BF16 && (head_dim == 64 || head_dim == 128) && (c->Wd >= kChunk || c->Wd == max_seq) &&
               n_q_heads / n_kv_heads <= 32;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;

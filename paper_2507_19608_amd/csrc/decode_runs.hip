@@ -1,5 +1,5 @@
 // Decode stage for bf16 caches in the column-run layout (Sec. III-B decode stage, Sec. III-C): head_dim 64
-// or 128, decode window of at least one chunk.  The compact delta cache keeps, per chunk of kChunk rows
+// or 128, decode window of at least one chunk (or of the whole cache).  The compact delta cache keeps, per chunk of kChunk rows
 // and per channel, the run of surviving key values; a chunk is sealed into that form once, when its last
 // row has arrived, while its rows are still inside the decode window.
 #include <math.h>
@@ -477,8 +477,11 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
             for (int r = 0; r < 16; r += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[T][r], scale_log2, -m));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[T][r + 1], scale_log2, -m));
-                l_run += p0 + p1;
-                pa[T][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
+                // the sum runs over the probabilities as rounded to bf16, the weights P V uses: their rounding
+                // then cannot bias the weighted mean
+                const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
+                pa[T][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
             }
         // 4. O^T += V^T P^T: channels x heads, contraction over the chunk's 64 rows in accumulator order
 #pragma unroll

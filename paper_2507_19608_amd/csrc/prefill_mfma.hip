@@ -213,14 +213,15 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
         }
         const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-        float psum = 0.f;
         float p[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < 16; ++r)
             p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], sc, neg_m));   // bare v_exp_f32: tiny results may flush to 0
-            psum += p[r];
-        }
-        l_run += psum;
+        // The row sum is taken over the probabilities as rounded to bf16, i.e. over the very weights that P V uses:
+        // the output is then an exact weighted mean of the value rows, and the rounding of the weights cannot bias it
+        // (summing the unrounded ones does, by up to 2^-9 relative when many weights are equal).
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        float psum = 0.f;
 #pragma unroll
         for (int ka = 0; ka < 2; ++ka) {
             u32x4 pb;
@@ -229,13 +230,16 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 f32x2 pr;
                 pr[0] = p[8 * ka + 2 * k];
                 pr[1] = p[8 * ka + 2 * k + 1];
-                pb[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);
+                pb[k] = __builtin_bit_cast(uint32_t, pk);
             }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
                 oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vreg[ka * MT + mt]), as_bf16x8(pb),
                                                                   oacc[mt], 0, 0, 0);
         }
+        l_run += psum;
     };
 
     // ---------------------------------------------------------------- far blocks: gather (Eq. 4)

@@ -72,6 +72,8 @@ def test_decode_small(n, steps, d, Wd, B, Hq, Hkv, theta, dtype):
     (0, 140, 64, 64, 1, 2, 1, 0.25),      # from an empty cache through two seals
     (128, 65, 64, 100, 1, 32, 1, 0.1),    # prefill ends on a chunk boundary; 32 heads share the KV head
     (191, 3, 128, 128, 1, 2, 2, 0.3),     # the prefill leaves an unsealed chunk one row short of full
+    (10, 12, 64, 96, 2, 4, 2, 0.2),       # a cache shorter than a chunk: the decode window is cut to its 22 rows
+    (0, 40, 128, 1000, 1, 4, 1, 0.1),     # the same at head_dim 128, from an empty cache
 ])
 def test_decode_column_run_layout(n, steps, d, Wd, B, Hq, Hkv, theta):
     """bf16 caches with head_dim 64 / 128 and a decode window of at least one chunk keep the compact
@@ -175,6 +177,8 @@ def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
     (64, 4, 2, 48, 64, (100, 37, 64, 91)),      # unaligned pieces: old partial chunks get completed and sealed
     (128, 4, 1, 20, 70, (64, 130, 1, 70)),      # a piece of one row; pieces that start on chunk boundaries
     (64, 8, 1, 64, 64, (10, 300)),              # a short first piece, then several chunks at once
+    (128, 1, 1, 16, 96, (10, 1)),               # a cache of 23 rows: shorter than a chunk
+    (64, 4, 2, 128, 128, (1, 64)),              # window above the cache's length
 ])
 def test_chunked_prefill_then_decode(score_mode, window_mode, d, Hq, Hkv, W, Wd, chunks):
     """Prefill in pieces onto a growing cache (Sec. III-C): every piece must equal the same rows of one prefill
