@@ -244,6 +244,29 @@ def test_reruns_are_bit_identical_and_modes_agree():
     assert (outs[MODES[0]][0].float() - outs[MODES[1]][0].float()).abs().max().item() <= 2e-2
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("d,n,dtype", [(64, 300, "bf16"), (128, 200, "bf16"), (64, 150, "f32")])
+def test_subnormal_keys(mode, d, n, dtype):
+    """Keys that are small multiples of the smallest bf16 subnormal (2^-133), thresholds of that size: the
+    binary32 threshold decision keeps subnormals (no flush to zero), so the masks still match bit for bit."""
+    rng = np.random.default_rng(5)
+    walk = np.cumsum(rng.integers(-1, 2, size=(1, 2, n, d)), axis=2).astype(np.float64)
+    K = wl.round_to_dtype(walk * 2.0 ** -133, dtype)
+    Q, V = rand_walk(1, 1, 4, n, d, dtype), rand_walk(2, 1, 2, n, d, dtype, clip=3.5)
+    for theta in (0.0, 2.0 ** -133, 3 * 2.0 ** -133):
+        run_case(Q, K, V, theta, 16, dtype, mode)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_large_scores(mode):
+    """Queries eight times larger than usual: scaled scores of several hundred, a softmax that is all but one-hot."""
+    n, d = 400, 64
+    Q = wl.round_to_dtype(rand_walk(3, 1, 4, n, d) * 8.0, "bf16")
+    K, V = rand_walk(4, 1, 2, n, d), rand_walk(5, 1, 2, n, d, clip=3.5)
+    for wm in (da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING):
+        run_case(Q, K, V, 0.1, 32, "bf16", mode, window_mode=wm)
+
+
 def test_all_work_goes_to_the_callers_stream():
     """Prefill with cache hand-off, chunked prefill and decode steps issued on a side stream, with inputs that are
     produced on that stream right before: a launch or copy that went to another stream would read them too early.
