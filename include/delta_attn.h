@@ -12,7 +12,9 @@
  *     last dimension fastest.  The library owns only da_cache objects.
  *   - hip_stream is a hipStream_t passed as void* (NULL = default stream).  All
  *     work is enqueued on it; only delta_attn_sparsity synchronises.
- *   - Every entry returns a da_status; on an error nothing has been enqueued.
+ *   - Every entry returns a da_status.  Arguments, workspace and cache state are checked before anything is
+ *     enqueued: after DA_ERR_INVALID_ARG / UNSUPPORTED / WORKSPACE / STATE no buffer has been touched.  After
+ *     DA_ERR_HIP (a launch or copy failed part-way) the outputs, and a cache that was passed, are undefined.
  *   - Grouped-query attention: n_q_heads % n_kv_heads == 0; query head h reads
  *     KV head h / (n_q_heads / n_kv_heads).  There is one delta matrix, mask and
  *     nnz per (batch, KV head).
