@@ -255,7 +255,11 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
     bf16_t *stage_a = stage_a_all[wv], *stage_b = stage_b_all[wv];
     const int part_i = blockIdx.x * NW + wave, unit = blockIdx.y, lane = threadIdx.x & 63;
     const int nchunks = t / kChunk + 1;
-    const int c_begin = part_i * nc, c_end = min(c_begin + nc, nchunks);
+    // the wave's chunks: c_begin, c_begin + c_step, ... below c_end.  Single walkers take nc consecutive chunks;
+    // the NW walkers of one work group take every NW-th chunk, which spreads an uneven chunk count (and the
+    // cheaper window chunks at the end) evenly over the waves and so over the SIMDs
+    const int c_step = NW > 1 ? NW : 1;
+    const int c_begin = NW > 1 ? wave : part_i * nc, c_end = NW > 1 ? nchunks : min(c_begin + nc, nchunks);
     const int g = c.Hq / c.Hkv;                              // <= 32 in this layout
     const int b = unit / c.Hkv, hk = unit % c.Hkv;
     const int n32 = lane & 31, kap = lane >> 5;
@@ -303,7 +307,8 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
         request_masks(c_begin);
     }
     uint32_t tot_v = 0;                                      // element counts of the chunk after the next one's copy
-    if (c_begin + 1 < c_end && hist_of(c_begin + 1) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + c_begin + 1];
+    if (c_begin + c_step < c_end && hist_of(c_begin + c_step) > 0)
+        tot_v = c.ccnt[(size_t)unit * c.max_chunks + c_begin + c_step];
 
     f32x16 o[CT];                                            // O^T: lane = head, register r of tile ct =
 #pragma unroll                                               // channel coff + 32 ct + 8 (r / 4) + 4 (l / 32) + r % 4
@@ -322,11 +327,12 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
         uint32_t mk[2];
 #pragma unroll
         for (int w = 0; w < 2; ++w) mk[w] = mk_n[w];
-        if (chunk + 1 < c_end) {
-            copy_runs(chunk + 1, __builtin_amdgcn_readfirstlane(tot_v), sv_next);
-            request_masks(chunk + 1);
+        if (chunk + c_step < c_end) {
+            copy_runs(chunk + c_step, __builtin_amdgcn_readfirstlane(tot_v), sv_next);
+            request_masks(chunk + c_step);
             tot_v = 0;
-            if (chunk + 2 < c_end && hist_of(chunk + 2) > 0) tot_v = c.ccnt[(size_t)unit * c.max_chunks + chunk + 2];
+            if (chunk + 2 * c_step < c_end && hist_of(chunk + 2 * c_step) > 0)
+                tot_v = c.ccnt[(size_t)unit * c.max_chunks + chunk + 2 * c_step];
         }
         // V operands of the chunk (needed last, requested first): lane l = channel coff + 32 ct + l % 32, rows of
         // lane half l / 32 of each 16-row group; the newest row is patched in from v_new
@@ -494,9 +500,9 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
                                                                     __builtin_bit_cast(bf16x8, pa[T][s2]), o[ct], 0, 0, 0);
     };
     const bf16_t *partner_a = stage_a_all[wv ^ (H - 1)], *partner_b = stage_b_all[wv ^ (H - 1)];
-    for (int chunk = c_begin; chunk < c_end; chunk += 2) {
+    for (int chunk = c_begin; chunk < c_end; chunk += 2 * c_step) {
         do_chunk(chunk, stage_a, stage_b, partner_a);
-        if (chunk + 1 < c_end) do_chunk(chunk + 1, stage_b, stage_a, partner_b);
+        if (chunk + c_step < c_end) do_chunk(chunk + c_step, stage_b, stage_a, partner_b);
     }
     const float l_all = l_run + __shfl_xor(l_run, 32);
     if (NW == 1) {
