@@ -299,7 +299,7 @@ def decode_sweep(args, da, wl, torch, np):
     C4's generator at a fixed threshold: one work group per unit (waves merge on chip) against single-wave work
     groups plus a merge launch - the measurements behind the default launch plan."""
     rows = []
-    theta, n, steps, Wd = 0.11, 2048, 72, 128
+    theta, n, steps, Wd = 0.11, 2048, 40, 128
     for d in (64, 128):
         for B, Hq, Hkv in ((8, 32, 8), (16, 32, 8), (32, 20, 5), (24, 32, 8), (32, 32, 8), (64, 32, 8)):
             L = n + steps
@@ -310,26 +310,33 @@ def decode_sweep(args, da, wl, torch, np):
             ks = [K[:, :, t].contiguous() for t in range(n, L)]
             vs = [V[:, :, t].contiguous() for t in range(n, L)]
             Qp, Kp, Vp = Q[:, :, :n].contiguous(), K[:, :, :n].contiguous(), V[:, :, :n].contiguous()
-            row = {"head_dim": d, "units": B * Hkv}
+            # copies of the cache stepped in turn: 0.6 GB between two steps of the same copy, so that the 256 MB
+            # last-level cache cannot serve them
+            ncopies = max(2, int(np.ceil(600e6 / (B * Hkv * n * d * 2.9))))
+            row = {"head_dim": d, "units": B * Hkv, "cache_copies": ncopies}
             for name, plan in (("one_group_per_unit_us", (1, 0)), ("single_wave_groups_us", (0, 0)), ("default_us", (-1, 0))):
-                cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
-                cache.set_launch_plan(*plan)
-                da.delta_attn_prefill(Qp, Kp, Vp, theta, 512, score_mode=da.DA_SCORE_REBASE, cache=cache)
+                caches = [da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16) for _ in range(ncopies)]
+                for cache in caches:
+                    cache.set_launch_plan(*plan)
+                    da.delta_attn_prefill(Qp, Kp, Vp, theta, 512, score_mode=da.DA_SCORE_REBASE, cache=cache)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 for i in range(8):
-                    da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
+                    for cache in caches:
+                        da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
                 e0.record()
                 for i in range(8, steps):
-                    da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
+                    for cache in caches:
+                        da.delta_attn_decode(cache, qs[i], ks[i], vs[i])
                 e1.record()
                 torch.cuda.synchronize()
-                row[name] = e0.elapsed_time(e1) / (steps - 8) * 1e3
+                row[name] = e0.elapsed_time(e1) / ((steps - 8) * ncopies) * 1e3
                 if plan[0] < 0:
-                    s_m, _ = da.delta_attn_sparsity(cache.nnz(), L, d, Wd)
+                    s_m, _ = da.delta_attn_sparsity(caches[0].nnz(), L, d, Wd)
                     t_avg = n + steps / 2
                     row["algorithmic_mb_per_step"] = B * Hkv * t_avg * d * (2 + 1 / 8 + 2 * (1 - s_m)) / 1e6
                     row["default_tb_per_s"] = row["algorithmic_mb_per_step"] / row[name]
-                cache.close()
+                for cache in caches:
+                    cache.close()
             rows.append(row)
             sys.stderr.write(json.dumps(row) + "\n")
             sys.stderr.flush()

@@ -585,12 +585,12 @@ int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, v
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     // head_dim 64: one 8-wave work group per unit whose waves split the unit's chunks and merge in LDS (the
     // normalised output is written by this launch; returns 0: nothing left to merge) pays when its waves fill the
-    // wave slots once: measured over 64..512 units, it wins from 3/4 of the slots on, and loses to single-wave
-    // work groups (which spread any unit count over every SIMD) below that and beyond one round.
+    // wave slots: measured over 64..512 units with the caches read from HBM, it wins from 3/4 of the slots on and
+    // loses to single-wave work groups (which spread any unit count over every SIMD) below that.
     if (c->d == 64) {
         const int nw = 8;
         const int64_t waves = (int64_t)units * nw;
-        const bool fills = waves <= slots && waves * 4 >= (int64_t)slots * 3;
+        const bool fills = waves * 4 >= (int64_t)slots * 3;
         if (c->plan_merge == 1 || (c->plan_merge < 0 && fills)) {
             const int nc = (nchunks + nw - 1) / nw;
             hipLaunchKernelGGL((decode_step_runs_kernel<64, 8>), dim3(1, units), dim3(64 * nw), 0, s, *c, qq, kk, vv,
