@@ -129,11 +129,16 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
         held = kFinal ? load_f32(guess_out, ((size_t)unit * nchunks + chunk - 1) * d + c)
                       : load_f32(Kp, (size_t)(t0 - 1) * d + c);
     }
+    // Rows in batches of U; two register sets alternate, the next batch is requested before the current one is
+    // worked on (loads past the chunk's end are clamped to its last row and never used), so that a batch's memory
+    // latency is hidden behind the previous batch's arithmetic instead of being paid once per batch.
     constexpr int U = 16;
-    for (; t + U <= t1; t += U) {
-        float k[U];
+    const int cs = active ? c : 0;
+    auto load_batch = [&](float (&k)[U], int tb) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) k[u] = active ? load_f32(Kp, (size_t)(t + u) * d + c) : 0.f;
+        for (int u = 0; u < U; ++u) k[u] = load_f32(Kp, (size_t)min(tb + u, t1 - 1) * d + cs);
+    };
+    auto work_batch = [&](const float (&k)[U], int tb) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float diff = k[u] - held;                  // Eq. 2 condition in binary32
@@ -141,10 +146,23 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
             held = fire ? k[u] : held;                        // Eq. 3
             if (kFinal) {
                 const uint64_t b = __ballot(fire);
-                if (writer) Mp[(size_t)(t + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
-                if (active) store_from_f32(Hp, (size_t)(t + u) * d + c, held);
+                if (writer) Mp[(size_t)(tb + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
+                if (active) store_from_f32(Hp, (size_t)(tb + u) * d + c, held);
                 cnt += __popcll(b);
             }
+        }
+    };
+    if (t + U <= t1) {
+        float ka[U], kb[U];
+        load_batch(ka, t);
+        while (t + U <= t1) {
+            load_batch(kb, t + U);
+            work_batch(ka, t);
+            t += U;
+            if (t + U > t1) break;
+            load_batch(ka, t + U);
+            work_batch(kb, t);
+            t += U;
         }
     }
     for (; t < t1; ++t) {
