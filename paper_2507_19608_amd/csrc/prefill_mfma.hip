@@ -534,9 +534,15 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
     constexpr int MT = D / 32;
     const int unit = blockIdx.y, blk = blockIdx.x, t0 = blk * kTB, tid = threadIdx.x;
     const bf16_t *Vp = V + (size_t)unit * n * D;
-    for (int idx = tid; idx < kTB * D; idx += 256) {
-        const int r = idx / D, c = idx % D;
-        tile[r][c] = (t0 + r < n) ? Vp[(size_t)(t0 + r) * D + c] : (bf16_t)0;
+    for (int idx = tid; idx < kTB * (D / 8); idx += 256) {       // 16-byte loads, 8 channels of one row each
+        const int r = idx / (D / 8), c = (idx % (D / 8)) * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (t0 + r < n) v = *(const u32x4 *)(Vp + (size_t)(t0 + r) * D + c);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tile[r][c + 2 * k] = (bf16_t)(v[k] & 0xffffu);
+            tile[r][c + 2 * k + 1] = (bf16_t)(v[k] >> 16);
+        }
     }
     __syncthreads();
     u32x4 *Op = (u32x4 *)(Vt + (size_t)unit * D * n_pad) + (size_t)blk * (2 * MT * 64);
