@@ -306,7 +306,7 @@ void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s) {
                        (unsigned long long)v, n);
 }
 
-int delta_scan_chunk_len(int n) { return n >= 4096 ? 128 : 64; }
+int delta_scan_chunk_len(int n) { return n >= 1024 ? 128 : 64; }
 int delta_scan_num_chunks(int n) { return (n + delta_scan_chunk_len(n) - 1) / delta_scan_chunk_len(n); }
 
 template <typename T>
