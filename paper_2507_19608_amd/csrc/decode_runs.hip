@@ -48,14 +48,27 @@ __device__ void seal_chunk(const da_cache &c, int unit, int chunk, int lane, con
     uint32_t base = 0, half = 0;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int ch = c0 + lane;
+        // rows in batches of 16: all loads of a batch are issued before anything is stored, so that their latency
+        // is paid once per batch, not once per row
         uint64_t cm = 0;
-        for (int r = 0; r < kChunk; ++r)
-            cm |= (uint64_t)((Mp[(size_t)r * wpr + (ch >> 5)] >> (ch & 31)) & 1u) << r;
+        for (int rb = 0; rb < kChunk; rb += 16) {
+            uint32_t w[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) w[u] = Mp[(size_t)(rb + u) * wpr + (ch >> 5)];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) cm |= (uint64_t)((w[u] >> (ch & 31)) & 1u) << (rb + u);
+        }
         uint32_t total;
         uint32_t p = base + wave_exclusive_scan((uint32_t)__popcll(cm) + 1u, &total);
         room[p++] = heldp(ch);
-        for (int r = 0; r < kChunk; ++r)
-            if ((cm >> r) & 1ull) room[p++] = rowp(r)[ch];
+        for (int rb = 0; rb < kChunk; rb += 16) {
+            bf16_t kv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kv[u] = rowp(rb + u)[ch];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if ((cm >> (rb + u)) & 1ull) room[p++] = kv[u];
+        }
         base += total;
         if (c0 == 0) {
             half = base;                                     // elements of channels 0..63
@@ -101,9 +114,17 @@ __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__res
     const bf16_t *Hp = Hfull + ((size_t)unit * n_k + r0) * d;
     const bf16_t *Vp = Vnew + (size_t)unit * m * d;
     for (int ch = lane; ch < d; ch += kWave) {
-        for (int row = ra; row < rb; ++row)
-            if (row >= n_k - c.Wd)
-                ((bf16_t *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = Kp[(size_t)(row - r0) * d + ch];
+        for (int rq = ra; rq < rb; rq += 16) {               // 16 rows at a time: loads first (clamped), then stores
+            bf16_t kk[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kk[u] = Kp[(size_t)(min(rq + u, rb - 1) - r0) * d + ch];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int row = rq + u;
+                if (row < rb && row >= n_k - c.Wd)
+                    ((bf16_t *)c.ring)[((size_t)unit * c.Wd + row % c.Wd) * d + ch] = kk[u];
+            }
+        }
         if (chunk > 0 && r0 >= t0) ((bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = Hp[ch - d];
         if (rb == n_k) ((bf16_t *)c.khat)[(size_t)unit * d + ch] = Hp[(size_t)(rb - 1 - r0) * d + ch];
         // V: 16 rows of one channel are contiguous.  A group that starts with a new row is written whole (32
@@ -118,7 +139,8 @@ __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__res
                 for (int slot = 0; slot < 16; ++slot) {
                     const int k = slot >> 3, i = slot & 7;
                     const int row = g0 + 8 * (i >> 2) + 4 * k + (i & 3);
-                    v16[slot] = row < rb ? Vp[(size_t)(row - t0) * d + ch] : (bf16_t)0;
+                    const bf16_t v = Vp[(size_t)(min(row, rb - 1) - t0) * d + ch];   // clamped: no conditional load
+                    v16[slot] = row < rb ? v : (bf16_t)0;
                 }
 #pragma unroll
                 for (int slot = 0; slot < 16; ++slot) dst[slot] = v16[slot];
@@ -153,8 +175,16 @@ __global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, in
     uint32_t base = 0;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int ch = c0 + lane;
+        // rows in batches of 16 (one group of the V layout): all loads of a batch are issued before anything is
+        // stored, so that their latency is paid once per batch, not once per row
         uint64_t cm = 0;
-        for (int r = 0; r < rows; ++r) cm |= (uint64_t)((Mp[(size_t)r * wpr + (ch >> 5)] >> (ch & 31)) & 1u) << r;
+        for (int rb = 0; rb < rows; rb += 16) {
+            uint32_t w[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) w[u] = Mp[(size_t)min(rb + u, rows - 1) * wpr + (ch >> 5)];   // clamped: branch-free
+#pragma unroll
+            for (int u = 0; u < 16; ++u) cm |= (uint64_t)(rb + u < rows ? (w[u] >> (ch & 31)) & 1u : 0u) << (rb + u);
+        }
         uint32_t total = 0, p = 0;
         bf16_t held = 0;
         if (sealed) {
@@ -163,15 +193,35 @@ __global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, in
         } else if (chunk > 0) {
             held = ((const bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch];
         }
-        for (int r = 0; r < rows; ++r) {
-            const int row = r0 + r;
-            const bool raw_here = row >= t0 - c.Wd;          // always true for an unsealed chunk (Wd >= kChunk)
-            const bf16_t kraw = raw_here ? ring[(size_t)(row % c.Wd) * d + ch] : (bf16_t)0;
-            if ((cm >> r) & 1ull) held = sealed ? room[++p] : kraw;
-            const size_t o = ((size_t)unit * n_k + row) * d + ch;
-            Hfull[o] = held;
-            Kfull[o] = raw_here ? kraw : held;
-            Vfull[o] = ((const bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)];
+        for (int rb = 0; rb < rows; rb += 16) {
+            bf16_t kraw[16], sv[16];
+            // the 16 values of this channel and row group are contiguous in the V cache, in slot order
+            const u32x4 *vp = (const u32x4 *)((const bf16_t *)c.V + (((size_t)unit * (c.vrows >> 4) + ((r0 + rb) >> 4)) * d + ch) * 16);
+            const u32x4 v0 = vp[0], v1 = vp[1];
+            const uint32_t bits = (uint32_t)(cm >> rb) & 0xffffu;      // the batch's mask bits of this channel
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int r = rb + u, row = r0 + r;
+                // every load is in bounds whatever the row (ring slot of any position; p stays inside the room), so
+                // none of them is conditional and all of a batch are in flight together
+                kraw[u] = ring[(size_t)(row % c.Wd) * d + ch];
+                p += (bits >> u) & 1u;                                      // p: position of the newest survivor
+                sv[u] = room[p];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int r = rb + u, row = r0 + r;
+                const bool raw_here = row >= t0 - c.Wd;                     // always true for an unsealed chunk
+                if ((bits >> u) & 1u) held = sealed ? sv[u] : kraw[u];
+                const int slot = 8 * ((u >> 2) & 1) + 4 * (u >> 3) + (u & 3);
+                const uint32_t vw = slot < 8 ? v0[slot >> 1] : v1[(slot - 8) >> 1];
+                const size_t o = ((size_t)unit * n_k + row) * d + ch;
+                if (r < rows) {
+                    Hfull[o] = held;
+                    Kfull[o] = raw_here ? kraw[u] : held;
+                    Vfull[o] = (bf16_t)((slot & 1) ? vw >> 16 : vw & 0xffffu);
+                }
+            }
         }
         base += total;
         if (c0 == 0 && d > kWave) base = second_half_start(base);
