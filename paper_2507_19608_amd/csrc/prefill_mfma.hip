@@ -65,7 +65,9 @@ typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 
 // kGather: Eq. 4 as written for the far blocks (DA_SCORE_GATHER); otherwise every block goes through the matrix
 // cores (DA_SCORE_REBASE) and neither the fp16 Q tile nor the gather loop exists in the instantiation.
-template <int D, bool kGather>
+// kAligned: the launcher has checked that every tile's rows share one window whose start is a multiple of the block
+// size; the K_hat tile of the near blocks, its loads and its branches then do not exist in the instantiation.
+template <int D, bool kGather, bool kAligned>
 __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     extern __shared__ char lds_raw[];
     constexpr size_t kQtBytes = kGather ? (size_t)D * kRows * 2 : 0;
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
     const int win_first = win_start(i0);         // smallest window start of the tile's rows
     const int win_last = win_start(i_last);      // largest
-    const bool aligned = (win_first % kTB == 0) && (win_first == win_last);
+    const bool aligned = kAligned || ((win_first % kTB == 0) && (win_first == win_last));
     const int far_blocks = kGather ? win_first / kTB : 0;
     const int nblocks = i_last / kTB + 1;
 
@@ -593,9 +595,13 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
     static bool attr_done = false;
     if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true>,
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true, false>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gather);
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false>,
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true, true>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gather);
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false, false>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_near);
+        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false, true>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_near);
         attr_done = true;
     }
@@ -607,10 +613,18 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
             if ((a.tiles * a.hgroups) % sp == 0 && sp < 8) a.xsplit = sp;
             break;
         }
-    if (p.rebase)
-        hipLaunchKernelGGL((prefill_mfma_kernel<D, false>), dim3((unsigned)blocks), dim3(512), lds_near, s, a);
+    // every tile's rows (RT consecutive positions from q_off on) lie in one window square whose start is a multiple
+    // of the block size
+    const bool all_aligned = !p.sliding && p.W % kTB == 0 && p.W % a.RT == 0 && p.q_off % a.RT == 0;
+    const dim3 grid((unsigned)blocks), block(512);
+    if (p.rebase && all_aligned)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, false, true>), grid, block, lds_near, s, a);
+    else if (p.rebase)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, false, false>), grid, block, lds_near, s, a);
+    else if (all_aligned)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, true, true>), grid, block, lds_gather, s, a);
     else
-        hipLaunchKernelGGL((prefill_mfma_kernel<D, true>), dim3((unsigned)blocks), dim3(512), lds_gather, s, a);
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, true, false>), grid, block, lds_gather, s, a);
 }
 
 int prefill_mfma_n_pad(int n) { return (n + 63) / 64 * 64; }
