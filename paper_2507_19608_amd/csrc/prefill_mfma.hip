@@ -403,11 +403,15 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         constexpr int kTileBytes = D * 64;                       // 32 keys x D channels, bf16
         constexpr int kPieces = kTileBytes / 16;                 // 16-byte pieces per tile (256 or 512)
         char *tiles = lds_raw + kQtBytes;                        // [3 buffers][K, K_hat, V]
-        const bool has_piece = tid < kPieces;
-        // K piece of thread tid: key row tid % 32, 8-channel segment tid / 32.  Its operand-order slot is then
-        // tid itself, so a wave's 64 LDS stores are contiguous (a row-major thread-to-piece map made 16 lanes
+        // Every thread loads a piece - at head_dim 64, where a tile has only 256, the upper half of the work group
+        // loads the lower half's pieces again and does not store them: loads that sit under a condition make the
+        // compiler wait for every load in flight before a piece is parked, the younger set's included.
+        const bool has_piece = kPieces == 512 || tid < kPieces;
+        const int ptid = tid & (kPieces - 1);
+        // K piece of thread ptid: key row ptid % 32, 8-channel segment ptid / 32.  Its operand-order slot is then
+        // ptid itself, so a wave's 64 LDS stores are contiguous (a row-major thread-to-piece map made 16 lanes
         // hit the same banks)
-        const int pr = tid & 31, pseg = tid >> 5;
+        const int pr = ptid & 31, pseg = ptid >> 5;
         const int kslot = ((pseg >> 1) * 64 + (pseg & 1) * 32 + pr) * 16;
         // operand X of a block: K_hat while every row has the block outside its window (rebase mode), else K
         auto first_src = [&](int jb) -> const bf16_t * { return (jb + kTB <= win_first) ? Hp : Kp; };
@@ -416,19 +420,17 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         };
         auto load_tiles = [&](Pieces &pc, int blk) {
             const int jb = blk * kTB;
-            if (has_piece) {
-                const size_t roff = (size_t)min(jb + pr, n - 1) * D + pseg * 8;
-                pc.k = *(const u32x4 *)(first_src(jb) + roff);
-                if (!aligned) pc.h = *(const u32x4 *)(Hp + roff);
-                pc.v = *((const u32x4 *)Vtp + (size_t)blk * kPieces + tid);
-            }
+            const size_t roff = (size_t)min(jb + pr, n - 1) * D + pseg * 8;
+            pc.k = *(const u32x4 *)(first_src(jb) + roff);
+            if (!kAligned) pc.h = *(const u32x4 *)(Hp + roff);   // unconditional unless the tile cannot exist
+            pc.v = *((const u32x4 *)Vtp + (size_t)blk * kPieces + ptid);
         };
         auto store_tiles = [&](const Pieces &pc, int buf) {
             char *base = tiles + buf * (3 * kTileBytes);
             if (has_piece) {
                 *(u32x4 *)(base + kslot) = pc.k;
                 if (!aligned) *(u32x4 *)(base + kTileBytes + kslot) = pc.h;
-                *(u32x4 *)(base + 2 * kTileBytes + tid * 16) = pc.v;
+                *(u32x4 *)(base + 2 * kTileBytes + ptid * 16) = pc.v;
             }
         };
         // transposed score tile S^T[key][score row] = X[jb + key] . q, X tile in operand order at xt (a per-lane
@@ -502,6 +504,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             softmax_pv(s_cur, a.scale_log2, vreg);
             buf = nbuf;
         };
+        // everything requested so far has landed before the loop is entered: the wait at its head then only has to
+        // cover what the previous trip left in flight (the compiler sizes it for the worse of both ways in)
+        __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
         for (int blk = far_blocks; blk < nblocks; blk += 2) {
             do_block(blk, pb, s_a, s_b);
             if (blk + 1 < nblocks) do_block(blk + 1, pa, s_b, s_a);
