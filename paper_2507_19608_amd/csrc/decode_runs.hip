@@ -398,12 +398,17 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
                                                       (((size_t)unit * (c.vrows >> 4) + (row16 >> 4)) * D + ch) * 16 + 8 * kap);
                 }
         if (newest) {
-            const int pt = t & 15;
+            // position, unit and lane are made opaque here so that the select conditions and the addresses of the
+            // append are worked out inside this branch, once per step, instead of being kept in registers across
+            // the whole chunk loop
+            int tt = t, uo = unit, ln = lane;
+            asm volatile("" : "+s"(tt), "+s"(uo), "+v"(ln));
+            const int pt = tt & 15;
             const int kap_t = (pt >> 2) & 1, i_t = 4 * (pt >> 3) + (pt & 3);
-            const int Tn = (t >> 5) & 1, sn = (t >> 4) & 1;
+            const int Tn = (tt >> 5) & 1, sn = (tt >> 4) & 1;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const uint32_t vn = v_new[(size_t)unit * D + coff + 32 * ct + n32];
+                const uint32_t vn = v_new[(size_t)uo * D + coff + 32 * ct + (ln & 31)];
 #pragma unroll
                 for (int TT = 0; TT < 2; ++TT)
 #pragma unroll
@@ -417,7 +422,7 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
                         }
             }
             // 0. the new row goes into the cache (other waves of this launch never read what is written here)
-            if (half == 0) append_row_runs(c, unit, lane, k_new, v_new, mask_row, t);
+            if (half == 0) append_row_runs(c, uo, ln, k_new, v_new, mask_row, tt);
         }
 
         // 1. 64 channels of one key row per lane
@@ -506,11 +511,12 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
             lds_barrier();                                   // the areas may be copied into again
         }
         if (nrows < kChunk) {                                // only the newest chunk has rows that do not exist yet
+            const int lim = nrows - 4 * kap;                     // compared with constants: nothing to keep in registers
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (32 * T + 8 * (r >> 2) + 4 * kap + (r & 3) >= nrows) acc[T][r] = -INFINITY;
+                    if (32 * T + 8 * (r >> 2) + (r & 3) >= lim) acc[T][r] = -INFINITY;
         }
         float mx = acc[0][0];
 #pragma unroll
