@@ -179,6 +179,8 @@ def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
     (64, 8, 1, 64, 64, (10, 300)),              # a short first piece, then several chunks at once
     (128, 1, 1, 16, 96, (10, 1)),               # a cache of 23 rows: shorter than a chunk
     (64, 4, 2, 128, 128, (1, 64)),              # window above the cache's length
+    (128, 4, 1, 64, 128, (256, 256, 128)),      # pieces and window squares on row-tile boundaries: the kernel
+    (64, 16, 2, 128, 128, (128, 64, 64, 192)),  # instantiation without a K_hat tile, entered with a row offset
 ])
 def test_chunked_prefill_then_decode(score_mode, window_mode, d, Hq, Hkv, W, Wd, chunks):
     """Prefill in pieces onto a growing cache (Sec. III-C): every piece must equal the same rows of one prefill
