@@ -249,7 +249,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // global memory -> registers (one 16-byte load per lane, a whole block ahead) -> a private LDS
     // ring where the block's chunks sit back to back -> uniform 16-byte LDS reads that every lane
     // sees.  No scalar memory load sits in the inner loop, so all its LDS traffic completes in order
-    // and the loop is software-pipelined two chunks deep (register sets A and B).
+    // and the loop is software-pipelined three chunks deep (three register sets that rotate).
     if (kGather && far_blocks > 0) {
         const char *qtb = (const char *)qt;
         const uint32_t lane_off = (uint32_t)lane * 8u;
