@@ -114,6 +114,35 @@ def test_reference_stays_within_theta(oracle, theta):
     assert np.abs(np.cumsum(dK, axis=0) - Khat).max() < 1e-12
 
 
+def test_scan_symmetries(oracle):
+    """Eq. 2-3 act per channel and compare magnitudes: (a) scaling keys and threshold by a power of two (exact in
+    binary32) leaves the mask alone and scales the deltas; (b) permuting channels permutes mask and deltas; (c)
+    negating the keys negates the deltas and keeps the mask.  A scan that mixed channels, used a signed comparison
+    or scaled the threshold differently would break one of them."""
+    _, K, _ = rand_qkv(5, 1, 1, 300, 24)
+    k, theta = K[0], 0.11
+    mask, dK, Khat, _ = oracle.delta_scan(k, theta)
+    m2, d2, h2, _ = oracle.delta_scan(k * 8.0, theta * 8.0)
+    assert (m2 == mask).all() and (d2 == 8.0 * dK).all() and (h2 == 8.0 * Khat).all()
+    perm = np.random.default_rng(0).permutation(k.shape[1])
+    m3, d3, _, _ = oracle.delta_scan(np.ascontiguousarray(k[:, perm]), theta)
+    assert (m3 == mask[:, perm]).all() and (d3 == dK[:, perm]).all()
+    m4, d4, _, _ = oracle.delta_scan(-k, theta)
+    assert (m4 == mask).all() and (d4 == -dK).all()
+    assert 0.2 < 1.0 - mask.mean() < 0.9                  # the case is neither dense nor frozen
+
+
+def test_scan_continues_from_a_carried_reference(oracle):
+    """Sec. III-C: a sequence processed in pieces, each starting from the reference key the previous piece ended
+    with, has the delta matrix of the sequence processed at once (the reference key is the whole state of Eq. 2-3)."""
+    _, K, _ = rand_qkv(6, 1, 1, 257, 16)
+    k, theta = K[0], 0.2
+    mask, dK, Khat, _ = oracle.delta_scan(k, theta)
+    for cut in (1, 64, 100, 256):
+        m2, d2, h2, _ = oracle.delta_scan(np.ascontiguousarray(k[cut:]), theta, state=Khat[cut - 1])
+        assert (m2 == mask[cut:]).all() and (d2 == dK[cut:]).all() and (h2 == Khat[cut:]).all()
+
+
 def test_raw_previous_key_reading_is_rejected():
     """Plant the other reading (delta against the previous raw key) on the CPU and show the
     bound of Eq. 2-3 catches it: a slow drift never fires, so the implied reference runs away."""
@@ -243,6 +272,22 @@ def test_special_inputs_reduce_to_dense(oracle):
     Kbig = np.cumsum(np.ones((1, n, d)), axis=1) * 0.75                                  # all steps fire
     r = oracle.prefill(Q[None], Kbig[None], V[None], 0.5, 8)
     assert np.abs(r["O"][0] - dense_causal(Q, Kbig, V)).max() < 1e-12 and r["s_m"] == 0.0
+
+
+def test_outputs_are_convex_combinations_and_shift_invariant(oracle):
+    """Eq. 1: every output row is a weighted mean of value rows (inside their per-channel range, equal to v when all
+    value rows are equal), whatever the approximate scores are; and adding one vector to every value row adds it to
+    every output row.  A softmax whose weights did not sum to one over the mixed (approximate + exact) row fails both."""
+    Q, K, V = rand_qkv(7, 2, 1, 96, 16)
+    theta, W = 0.25, 8
+    run = lambda v: oracle.prefill(Q[None], K[None], v[None], theta, W)["O"][0]
+    O = run(V)
+    lo = np.minimum.accumulate(V[0], axis=0)              # range of the value rows a query row may mix
+    hi = np.maximum.accumulate(V[0], axis=0)
+    assert (O >= lo[None] - 1e-12).all() and (O <= hi[None] + 1e-12).all()
+    shift = np.linspace(-1.0, 1.0, V.shape[-1])
+    assert np.abs(run(V + shift) - (O + shift)).max() < 1e-12
+    assert np.abs(run(np.broadcast_to(shift, V.shape).copy()) - shift).max() < 1e-12
 
 
 def test_theta_infinite_freezes_outside_scores(oracle):
