@@ -148,9 +148,18 @@ def test_c4_decode_llama_shape_sampled_batch():
     st = orc.DecodeState(theta, w.window)
     xs = {k: x[k][ids] for k in "QKV"}
     st.append(xs["K"][:, :, :n], xs["V"][:, :, :n])
+    # every output element of every batch entry and step (the oracle follows three entries): finite, and inside
+    # the per-channel range of the value rows cached so far (Eq. 1: weights that sum to one), up to output rounding
+    Vf = Vd.float()
+    lo_all = torch.cummin(Vf, dim=2).values.repeat_interleave(Hq // Hkv, dim=1)
+    hi_all = torch.cummax(Vf, dim=2).values.repeat_interleave(Hq // Hkv, dim=1)
+    tol = 2.0 ** -8 * Vf.abs().max().item()
     for t in range(n, n + steps):
         o, mrow = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(),
                                        Vd[:, :, t].contiguous())
+        of = o.float()
+        assert torch.isfinite(of).all()
+        assert (of >= lo_all[:, :, t] - tol).all() and (of <= hi_all[:, :, t] + tol).all()
         if (t - n) % 37 == 0 or t == n + steps - 1:
             o_ref, m_ref = st.step(xs["Q"][:, :, t], xs["K"][:, :, t], xs["V"][:, :, t])
             assert (unpack_mask(mrow, d)[ids] == m_ref).all()

@@ -167,6 +167,32 @@ def test_c5_long_context_sampled(mode):
     _sampled(wl.C5, mode, [(500, 530), (4090, 4110), (8170, 8192)], [3, 16])
 
 
+def test_c5_every_output_element():
+    """The benchmark's launch at full size, every output element (the sampled rows above are checked against the
+    oracle): finite; inside the per-channel range of the value rows its query row may mix (Eq. 1: a weighted mean
+    with weights that sum to one, whatever the approximate scores are), up to the rounding of the output; and the
+    two score modes, each within 2e-2 of the oracle, within 4e-2 of each other everywhere."""
+    w = wl.C5
+    x = _inputs(w)
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    theta = wl.theta_for(w)
+    outs = []
+    for mode in MODES:
+        O, _, _ = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+        outs.append(O)
+    torch.cuda.synchronize()
+    g = w.n_q_heads // w.n_kv_heads
+    Vf = Vd.float()
+    lo = torch.cummin(Vf, dim=2).values.repeat_interleave(g, dim=1)
+    hi = torch.cummax(Vf, dim=2).values.repeat_interleave(g, dim=1)
+    tol = 2.0 ** -8 * Vf.abs().max().item()                  # bf16 rounding of an output of that size
+    for O in outs:
+        Of = O.float()
+        assert torch.isfinite(Of).all()
+        assert (Of >= lo - tol).all() and (Of <= hi + tol).all()
+    assert (outs[0].float() - outs[1].float()).abs().max().item() <= 4e-2
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 def test_64k_tokens_sampled(mode, window_mode):
