@@ -193,6 +193,40 @@ def test_c5_every_output_element():
     assert (outs[0].float() - outs[1].float()).abs().max().item() <= 4e-2
 
 
+def test_c5_every_output_element_against_the_dense_form():
+    """Every output element of the benchmark's launch against the closed form the oracle is pinned to: outside a
+    row's window square the Eq. 4 score is q . k_hat(j) (the deltas up to column j sum to the held key), inside it
+    q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device, from the
+    inputs and the delta mask (itself compared bit for bit with the oracle above).  Tolerance as for the oracle."""
+    w = wl.C5
+    x = _inputs(w)
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    theta, n, d, W = wl.theta_for(w), w.seq_len, w.head_dim, w.window
+    g = w.n_q_heads // w.n_kv_heads
+    outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode) for mode in MODES]
+    torch.cuda.synchronize()
+    bits = outs[0][1]
+    sh = torch.arange(32, device="cuda", dtype=torch.int32)
+    mask = ((bits.unsqueeze(-1) >> sh) & 1).reshape(w.batch, w.n_kv_heads, n, d).bool()
+    rows = torch.arange(n, device="cuda")
+    inside = (rows[:, None] // W == rows[None, :] // W)
+    causal = rows[None, :] <= rows[:, None]
+    worst = 0.0
+    for b in range(w.batch):
+        for hk in range(w.n_kv_heads):
+            K, V = Kd[b, hk].double(), Vd[b, hk].double()
+            last = torch.where(mask[b, hk], rows[:, None], torch.zeros_like(rows[:, None])).cummax(dim=0).values
+            Khat = torch.gather(K, 0, last)                  # the key row each channel last fired at
+            for h in range(hk * g, (hk + 1) * g):
+                Q = Qd[b, h].double()
+                S = torch.where(inside, Q @ K.T, Q @ Khat.T) / d ** 0.5
+                S = S.masked_fill(~causal, float("-inf"))
+                ref = torch.softmax(S, dim=-1) @ V
+                for O, _, _ in outs:
+                    worst = max(worst, (O[b, h].double() - ref).abs().max().item())
+    assert worst <= 2e-2, worst
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 def test_64k_tokens_sampled(mode, window_mode):
