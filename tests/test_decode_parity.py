@@ -172,6 +172,45 @@ def test_c4_decode_llama_shape_sampled_batch():
     cache.close()
 
 
+def test_c4_every_output_element_against_the_dense_form():
+    """Config 4 at full size, every output element of every step and batch entry against the closed form the oracle
+    is pinned to - q . k_hat(j) for keys left of the decode window, q . k_j inside it, Eq. 1 on top - in fp64 with
+    library products on the device.  k_hat comes from Eq. 2-3 written out with tensor operations over all units at
+    once (binary32 decision, as the oracle takes it).  Tolerance as for the oracle."""
+    w = wl.C4
+    x = wl.generate(w)
+    theta = wl.theta_for(w)
+    B, Hq, Hkv, d, n, steps = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.decode_steps
+    g = Hq // Hkv
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    cache = da.Cache(B, Hq, Hkv, d, n + steps, w.window, theta, torch.bfloat16)
+    da.delta_attn_prefill(Qd[:, :, :n].contiguous(), Kd[:, :, :n].contiguous(), Vd[:, :, :n].contiguous(), theta,
+                          w.window, cache=cache)
+    K64, V64 = Kd.double(), Vd.double()
+    Khat64 = torch.empty_like(K64)
+    held = Kd[:, :, 0].float()
+    Khat64[:, :, 0] = held.double()
+    th32 = torch.tensor(theta, dtype=torch.float32, device="cuda")
+    for t in range(1, n + steps):
+        kt = Kd[:, :, t].float()
+        held = torch.where((kt - held).abs() > th32, kt, held)
+        Khat64[:, :, t] = held.double()
+    worst = 0.0
+    for t in range(n, n + steps):
+        o, _ = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(),
+                                    Vd[:, :, t].contiguous())
+        q = Qd[:, :, t].double().reshape(B, Hkv, g, d)
+        s_hist = torch.einsum("bkgd,bktd->bkgt", q, Khat64[:, :, :t + 1])
+        s_win = torch.einsum("bkgd,bktd->bkgt", q, K64[:, :, :t + 1])
+        in_window = torch.arange(t + 1, device="cuda") > t - w.window
+        p = torch.softmax(torch.where(in_window, s_win, s_hist) / d ** 0.5, dim=-1)
+        ref = torch.einsum("bkgt,bktd->bkgd", p, V64[:, :, :t + 1]).reshape(B, Hq, d)
+        assert torch.isfinite(o.float()).all()
+        worst = max(worst, (o.double() - ref).abs().max().item())
+    cache.close()
+    assert worst <= 2e-2, worst
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 1), (64, 8, 2)])
 def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
     """A long history: 32 768 cached tokens (512 sealed chunks per unit), then 70 steps, which cross a chunk seal."""
