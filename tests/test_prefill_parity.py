@@ -193,23 +193,41 @@ def test_c5_every_output_element():
     assert (outs[0].float() - outs[1].float()).abs().max().item() <= 4e-2
 
 
-def test_c5_every_output_element_against_the_dense_form():
+@pytest.mark.parametrize("how", ["one call", "sliding window", "four pieces onto a cache"])
+def test_c5_every_output_element_against_the_dense_form(how):
     """Every output element of the benchmark's launch against the closed form the oracle is pinned to: outside a
-    row's window square the Eq. 4 score is q . k_hat(j) (the deltas up to column j sum to the held key), inside it
-    q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device, from the
-    inputs and the delta mask (itself compared bit for bit with the oracle above).  Tolerance as for the oracle."""
+    row's window (square, or band) the Eq. 4 score is q . k_hat(j) (the deltas up to column j sum to the held key),
+    inside it q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device, from
+    the inputs and the delta mask (itself compared bit for bit with the oracle above).  Tolerance as for the oracle.
+    Also for the prompt fed in four pieces through the chunked entry point, as `bench.py --chunks 4` times it."""
     w = wl.C5
     x = _inputs(w)
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     theta, n, d, W = wl.theta_for(w), w.seq_len, w.head_dim, w.window
     g = w.n_q_heads // w.n_kv_heads
-    outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode) for mode in MODES]
+    rows = torch.arange(n, device="cuda")
+    if how == "one call":
+        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode) for mode in MODES]
+        inside = (rows[:, None] // W == rows[None, :] // W)
+    elif how == "sliding window":
+        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=da.DA_WINDOW_SLIDING)
+                for mode in MODES]
+        inside = (rows[:, None] - rows[None, :] < W)
+    else:
+        outs = []
+        for mode in MODES:
+            cache = da.Cache(w.batch, w.n_q_heads, w.n_kv_heads, d, n, W, theta, torch.bfloat16)
+            parts = [da.delta_attn_prefill_append(cache, Qd[:, :, a:a + n // 4].contiguous(),
+                                                  Kd[:, :, a:a + n // 4].contiguous(),
+                                                  Vd[:, :, a:a + n // 4].contiguous(), theta, W, score_mode=mode)
+                     for a in range(0, n, n // 4)]
+            outs.append(tuple(torch.cat([p[k] for p in parts], dim=2) for k in range(2)) + (None,))
+            cache.close()
+        inside = (rows[:, None] // W == rows[None, :] // W)
     torch.cuda.synchronize()
     bits = outs[0][1]
     sh = torch.arange(32, device="cuda", dtype=torch.int32)
     mask = ((bits.unsqueeze(-1) >> sh) & 1).reshape(w.batch, w.n_kv_heads, n, d).bool()
-    rows = torch.arange(n, device="cuda")
-    inside = (rows[:, None] // W == rows[None, :] // W)
     causal = rows[None, :] <= rows[:, None]
     worst = 0.0
     for b in range(w.batch):
@@ -224,6 +242,37 @@ def test_c5_every_output_element_against_the_dense_form():
                 ref = torch.softmax(S, dim=-1) @ V
                 for O, _, _ in outs:
                     worst = max(worst, (O[b, h].double() - ref).abs().max().item())
+    assert worst <= 2e-2, worst
+
+
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+def test_64k_tokens_every_output_element_against_the_dense_form(window_mode):
+    """The 65536-token prompt of the test below, every output element of both score modes against the same closed
+    form, 2048 query rows at a time (the delta mask is compared with the oracle's below)."""
+    w = wl.Workload("L64K", 1, 4, 1, 128, 65536, 512, "bf16", seed=64, theta=0.11)
+    x = _inputs(w)
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    n, d, W = w.seq_len, w.head_dim, w.window
+    outs = [da.delta_attn_prefill(Qd, Kd, Vd, w.theta, W, score_mode=mode, window_mode=window_mode) for mode in MODES]
+    torch.cuda.synchronize()
+    sh = torch.arange(32, device="cuda", dtype=torch.int32)
+    mask = ((outs[0][1].unsqueeze(-1) >> sh) & 1).reshape(n, d).bool()
+    rows = torch.arange(n, device="cuda")
+    K, V = Kd[0, 0].double(), Vd[0, 0].double()
+    last = torch.where(mask, rows[:, None], torch.zeros_like(rows[:, None])).cummax(dim=0).values
+    Khat = torch.gather(K, 0, last)
+    worst = 0.0
+    for r0 in range(0, n, 2048):
+        i = rows[r0:r0 + 2048, None]
+        j = rows[None, :r0 + 2048]
+        inside = (i - j < W) if window_mode == da.DA_WINDOW_SLIDING else (i // W == j // W)
+        for h in range(w.n_q_heads):
+            Q = Qd[0, h, r0:r0 + 2048].double()
+            S = torch.where(inside, Q @ K[:r0 + 2048].T, Q @ Khat[:r0 + 2048].T) / d ** 0.5
+            S = S.masked_fill(j > i, float("-inf"))
+            ref = torch.softmax(S, dim=-1) @ V[:r0 + 2048]
+            for O, _, _ in outs:
+                worst = max(worst, (O[0, h, r0:r0 + 2048].double() - ref).abs().max().item())
     assert worst <= 2e-2, worst
 
 
