@@ -193,20 +193,22 @@ def test_c5_every_output_element():
     assert (outs[0].float() - outs[1].float()).abs().max().item() <= 4e-2
 
 
-@pytest.mark.parametrize("how", ["one call", "sliding window", "four pieces onto a cache"])
+@pytest.mark.parametrize("how", ["one call", "sliding window", "four pieces onto a cache", "theta 0",
+                                 "80 % sparsity, 20 % jumps"])
 def test_c5_every_output_element_against_the_dense_form(how):
     """Every output element of the benchmark's launch against the closed form the oracle is pinned to: outside a
     row's window (square, or band) the Eq. 4 score is q . k_hat(j) (the deltas up to column j sum to the held key),
     inside it q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device, from
     the inputs and the delta mask (itself compared bit for bit with the oracle above).  Tolerance as for the oracle.
-    Also for the prompt fed in four pieces through the chunked entry point, as `bench.py --chunks 4` times it."""
-    w = wl.C5
+    Also for the prompt fed in four pieces through the chunked entry point, as `bench.py --chunks 4` times it, and
+    at the two ends of the sparsity sweep (every delta kept: the longest entry lists; 80 % zeroed with bursts)."""
+    w = wl.c5(0.0, 0.05) if how == "theta 0" else wl.c5(0.80, 0.20) if how.startswith("80") else wl.C5
     x = _inputs(w)
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     theta, n, d, W = wl.theta_for(w), w.seq_len, w.head_dim, w.window
     g = w.n_q_heads // w.n_kv_heads
     rows = torch.arange(n, device="cuda")
-    if how == "one call":
+    if how in ("one call", "theta 0") or how.startswith("80"):
         outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode) for mode in MODES]
         inside = (rows[:, None] // W == rows[None, :] // W)
     elif how == "sliding window":
