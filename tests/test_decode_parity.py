@@ -172,12 +172,15 @@ def test_c4_decode_llama_shape_sampled_batch():
     cache.close()
 
 
-def test_c4_every_output_element_against_the_dense_form():
+@pytest.mark.parametrize("shape", ["C4", "head_dim 128"])
+def test_c4_every_output_element_against_the_dense_form(shape):
     """Config 4 at full size, every output element of every step and batch entry against the closed form the oracle
     is pinned to - q . k_hat(j) for keys left of the decode window, q . k_j inside it, Eq. 1 on top - in fp64 with
     library products on the device.  k_hat comes from Eq. 2-3 written out with tensor operations over all units at
-    once (binary32 decision, as the oracle takes it).  Tolerance as for the oracle."""
-    w = wl.C4
+    once (binary32 decision, as the oracle takes it).  Tolerance as for the oracle.  Also at batch 32 with config 3's
+    heads (20 / 5 of 128 channels: a pair of waves per chunk), 130 steps that cross two chunk seals."""
+    w = wl.C4 if shape == "C4" else wl.Workload("D128", 32, 20, 5, 128, 2048, 128, "bf16", seed=44, decode_steps=130,
+                                                theta=0.11)
     x = wl.generate(w)
     theta = wl.theta_for(w)
     B, Hq, Hkv, d, n, steps = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.decode_steps
