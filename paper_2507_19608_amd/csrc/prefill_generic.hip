@@ -59,7 +59,10 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
 #pragma unroll
     for (int c = 0; c < D; ++c) o[c] = 0.f;
     float m = -INFINITY, l = 0.f;
-    float r = 0.f;   // Eq. 4 running score of this row (unscaled)
+    // Eq. 4 running score of this row (unscaled).  A column's update is summed in binary32, the running score over
+    // the columns in binary64: one add per column, and its rounding then does not grow with the prompt length
+    // (in binary32 it reached 1e-4 of the output scale at ~1500 columns with fp32 inputs).
+    double r = 0.0;
 
     constexpr int TB = 16;
     for (int jb = 0; jb <= i_last; jb += TB) {
@@ -77,12 +80,14 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
                     } else {
                         const uint32_t cnt = Cp[j];
                         const EntryChunk *e = Ep + (size_t)j * (D / kGroup);
+                        float upd = 0.f;
                         for (uint32_t k = 0; k < cnt; k += kGroup) {
                             const EntryChunk ch = e[k / kGroup];
 #pragma unroll
-                            for (int u = 0; u < kGroup; ++u) r = fmaf(qt[ch.chan[u] * 64 + lane], ch.delta[u], r);
+                            for (int u = 0; u < kGroup; ++u) upd = fmaf(qt[ch.chan[u] * 64 + lane], ch.delta[u], upd);
                         }
-                        approx = r;
+                        r += (double)upd;
+                        approx = (float)r;
                     }
                 }
                 float exact = 0.f;

@@ -247,6 +247,36 @@ def test_c5_every_output_element_against_the_dense_form(how):
     assert worst <= 2e-2, worst
 
 
+@pytest.mark.parametrize("dtype,d,n,W", [("f32", 64, 1536, 96), ("f32", 256, 700, 33), ("bf16", 96, 2048, 128),
+                                         ("bf16", 32, 3000, 7)])
+def test_generic_kernel_every_output_element_against_the_dense_form(dtype, d, n, W):
+    """The vector-ALU kernel (fp32 inputs; head sizes other than 64 / 128) at sizes of a few thousand rows, every
+    output element of both score modes and both window modes against the same closed form in fp64."""
+    B, Hq, Hkv, theta = 2, 6, 2, 0.12
+    Q, K, V = rand_walk(71, B, Hq, n, d, dtype), rand_walk(72, B, Hkv, n, d, dtype), rand_walk(73, B, Hkv, n, d, dtype, clip=3.5)
+    Qd, Kd, Vd = to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype)
+    rows = torch.arange(n, device="cuda")
+    causal = rows[None, :] <= rows[:, None]
+    sh = torch.arange(32, device="cuda", dtype=torch.int32)
+    for window_mode in (da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING):
+        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=window_mode) for mode in MODES]
+        torch.cuda.synchronize()
+        mask = ((outs[0][1].unsqueeze(-1) >> sh) & 1).reshape(B, Hkv, n, d).bool()
+        assert (unpack_mask(outs[0][1], d) == np.stack([[orc.delta_scan(K[b, h], theta)[0] for h in range(Hkv)]
+                                                       for b in range(B)])).all()
+        inside = (rows[:, None] - rows[None, :] < W) if window_mode == da.DA_WINDOW_SLIDING \
+            else (rows[:, None] // W == rows[None, :] // W)
+        for b in range(B):
+            for h in range(Hq):
+                hk = h // (Hq // Hkv)
+                Kx, Vx, Qx = Kd[b, hk].double(), Vd[b, hk].double(), Qd[b, h].double()
+                last = torch.where(mask[b, hk], rows[:, None], torch.zeros_like(rows[:, None])).cummax(dim=0).values
+                S = torch.where(inside, Qx @ Kx.T, Qx @ torch.gather(Kx, 0, last).T) / d ** 0.5
+                ref = torch.softmax(S.masked_fill(~causal, float("-inf")), dim=-1) @ Vx
+                for O, _, _ in outs:
+                    check_output(O[b, h], ref.cpu().numpy(), dtype)
+
+
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 def test_64k_tokens_every_output_element_against_the_dense_form(window_mode):
     """The 65536-token prompt of the test below, every output element of both score modes against the same closed
