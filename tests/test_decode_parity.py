@@ -218,6 +218,45 @@ def test_c4_every_output_element_against_the_dense_form(shape):
     assert worst <= (2e-2 if w.dtype == "bf16" else 1e-4 * V64.abs().max().item()), worst
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_decode_runs_against_the_dense_form(seed):
+    """Seeded random decode runs (batch 1-24, group sizes up to 32, prompts of 0-3000 rows through the prefill or in
+    two pieces through the chunked entry point, 3-200 steps, decode windows 64-512, every launch plan): every output
+    element of every step within tolerance of the dense form."""
+    import random
+    import dense_form as df
+    rng = random.Random(2000 + seed)
+    d, Hkv, g = rng.choice([64, 128]), rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 5, 8, 16, 32])
+    B, n0 = rng.choice([1, 2, 8, 24]), rng.choice([0, 1, 63, 64, 200, 700, 1500, 2047, 2048, 3000])
+    steps, Wd, theta = rng.choice([3, 65, 70, 130, 200]), rng.choice([64, 100, 128, 256, 512]), rng.choice([0.0, 0.05, 0.11, 0.3])
+    plan = rng.choice([None, None, (1, 0), (0, 0), (0, 5), (-1, 64)])
+    Hq, L = Hkv * g, n0 + steps
+    if B * Hq * L * d > 4e8:
+        B = 1
+    Qd, Kd, Vd = (to_dev(rand_walk(7000 + 3 * seed + k, B, H, L, d, clip=c), "bf16")
+                  for k, (H, c) in enumerate(((Hq, None), (Hkv, None), (Hkv, 3.5))))
+    cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
+    if plan is not None:
+        cache.set_launch_plan(*plan)
+    if n0 > 0:
+        Wp = rng.choice([16, 64, min(Wd, 128)])
+        cuts = [0, n0] if (rng.random() < 0.5 or n0 < 3) else [0, rng.randrange(1, n0), n0]
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            args = (Qd[:, :, a:b].contiguous(), Kd[:, :, a:b].contiguous(), Vd[:, :, a:b].contiguous(), theta, Wp)
+            if len(cuts) == 2:
+                da.delta_attn_prefill(*args, score_mode=da.DA_SCORE_REBASE, cache=cache)
+            else:
+                da.delta_attn_prefill_append(cache, *args, score_mode=da.DA_SCORE_REBASE)
+    khat, _ = df.reference_keys(Kd, theta)
+    K64, V64 = Kd.double(), Vd.double()
+    worst = 0.0
+    for t in range(n0, L):
+        o, _ = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        worst = max(worst, (o.double() - df.decode_reference(Qd[:, :, t], K64, V64, khat, t, Wd)).abs().max().item())
+    cache.close()
+    assert worst <= 2e-2, worst
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 1), (64, 8, 2)])
 def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
     """A long history: 32 768 cached tokens (512 sealed chunks per unit), then 70 steps, which cross a chunk seal."""

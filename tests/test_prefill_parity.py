@@ -277,6 +277,39 @@ def test_generic_kernel_every_output_element_against_the_dense_form(dtype, d, n,
                     check_output(O[b, h], ref.cpu().numpy(), dtype)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_mid_size_shapes_against_the_dense_form(seed):
+    """Seeded random shapes of 700-4100 rows (head sizes 64 / 128, group sizes 1-8, windows 1-1024, both window
+    modes, one call or 2-5 ragged pieces through the chunked entry point): masks equal Eq. 2-3 written out with
+    tensor operations, every output element of both score modes within tolerance of the dense form."""
+    import random
+    import dense_form as df
+    rng = random.Random(1000 + seed)
+    d, Hkv, g, B = rng.choice([64, 128]), rng.choice([1, 2, 3]), rng.choice([1, 2, 3, 4, 6, 8]), rng.choice([1, 2])
+    n = rng.choice([700, 1024, 1500, 2048, 2500, 3000, 4096]) + rng.choice([0, 0, 1, 31, 33])
+    W = rng.choice([1, 5, 32, 64, 100, 128, 256, 300, 512, 1024])
+    theta, wm, pieces = rng.choice([0.0, 0.05, 0.11, 0.2, 0.5]), rng.choice([0, 1]), rng.choice([1, 1, 2, 3, 5])
+    Hq = Hkv * g
+    Qd, Kd, Vd = (to_dev(rand_walk(5000 + 3 * seed + k, B, H, n, d, clip=c), "bf16")
+                  for k, (H, c) in enumerate(((Hq, None), (Hkv, None), (Hkv, 3.5))))
+    outs = []
+    for mode in MODES:
+        if pieces == 1:
+            O, bits, _ = da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=wm)
+        else:
+            cache = da.Cache(B, Hq, Hkv, d, n, max(64, min(W, n)), theta, torch.bfloat16)
+            cuts = sorted(set([0, n] + [rng.randrange(1, n) for _ in range(pieces - 1)]))
+            parts = [da.delta_attn_prefill_append(cache, Qd[:, :, a:b].contiguous(), Kd[:, :, a:b].contiguous(),
+                                                  Vd[:, :, a:b].contiguous(), theta, W, score_mode=mode, window_mode=wm)
+                     for a, b in zip(cuts[:-1], cuts[1:])]
+            O, bits = (torch.cat([p[k] for p in parts], dim=2) for k in range(2))
+            cache.close()
+        outs.append(O)
+        khat, mask = df.reference_keys(Kd, theta)
+        assert (df.unpack_bits(bits, d) == mask).all()
+    assert df.prefill_worst_error(Qd, Kd, Vd, khat, W, wm == 1, outs) <= 2e-2
+
+
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 def test_64k_tokens_every_output_element_against_the_dense_form(window_mode):
     """The 65536-token prompt of the test below, every output element of both score modes against the same closed
