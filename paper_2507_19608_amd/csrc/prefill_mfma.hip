@@ -176,7 +176,11 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[mt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f, r_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    // Eq. 4 running score of this lane's score row at the end of the previous block.  Inside a block the column updates
+    // are added up in binary32; across blocks the total is kept in binary64 (one add per block), so that the rounding
+    // of the one long sum does not grow with the prompt length (in binary32 it showed at ~130 000 columns).
+    double r_run = 0.0;
 
     const int win_first = win_start(i0);         // smallest window start of the tile's rows
     const int win_last = win_start(i_last);      // largest
@@ -378,15 +382,16 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
             float s[16];
-            float base = r_run;
+            const float r0 = (float)r_run;
+            float rel = 0.f;                                     // sum of this block's updates so far
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float mine = half ? base + t_oth[q] : base;
+                const float mine = r0 + (half ? rel + t_oth[q] : rel);
 #pragma unroll
                 for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = mine + w[4 * q + bb];
-                base += t_own[q] + t_oth[q];
+                rel += t_own[q] + t_oth[q];
             }
-            r_run = base;
+            r_run += (double)rel;
             softmax_pv(s, far_scale, vreg);
         }
     }
