@@ -341,6 +341,47 @@ def test_64k_tokens_every_output_element_against_the_dense_form(window_mode):
     assert worst <= 2e-2, worst
 
 
+def test_two_to_the_31_query_elements():
+    """Maximum sizes: batch 4, 32 / 8 heads of 128, 131072 tokens - Q and O hold 2^31 elements each (4 GiB), so element
+    offsets leave 32 bits and byte offsets 33; the running Eq. 4 score of a late row is a sum over 130 000 columns.
+    Inputs are drawn on the device (random walks like the workloads'); the masks of three units and 1024-row blocks at
+    the start, middle and end of three heads (the last head of the last batch entry among them) are compared with
+    the oracle's Eq. 2-3 and the dense form in fp64, in both score modes."""
+    import dense_form as df
+    B, Hq, Hkv, n, d, W, theta = 4, 32, 8, 131072, 128, 512, 0.11
+    gen = torch.Generator(device="cuda").manual_seed(31)
+
+    def walk(H, clip=None):
+        x = torch.cumsum(0.15 * torch.randn(B, H, n, d, device="cuda", generator=gen), dim=2)
+        x += torch.randn(B, H, 1, d, device="cuda", generator=gen)
+        return (x.clamp(-clip, clip) if clip else x).to(torch.bfloat16)
+
+    Qd, Kd, Vd = walk(Hq), walk(Hkv), walk(Hkv, 3.5)
+    assert Qd.numel() == 2 ** 31
+    rows = torch.arange(n, device="cuda")
+    heads = ((B - 1, Hq - 1), (0, 0), (2, 17))
+    scans = {}                                                # Eq. 2-3 of the three units, from the oracle
+    for b, h in heads:
+        m, _, kh, knife = orc.delta_scan(Kd[b, h // (Hq // Hkv)].double().cpu().numpy(), theta)
+        assert knife == 0
+        scans[b, h] = (torch.from_numpy(m).cuda().bool(), torch.from_numpy(kh).cuda())
+    for mode in MODES:
+        O, bits, _ = da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode)
+        for b, h in heads:
+            hk = h // (Hq // Hkv)
+            mask, khat = scans[b, h]
+            assert (df.unpack_bits(bits[b, hk], d) == mask).all()
+            for r0 in (0, n // 2 - 512, n - 1024):
+                r1 = r0 + 1024
+                i, j = rows[r0:r1, None], rows[None, :r1]
+                K, V, H = Kd[b, hk, :r1].double(), Vd[b, hk, :r1].double(), khat[:r1]
+                Q = Qd[b, h, r0:r1].double()
+                S = torch.where(i // W == j // W, Q @ K.T, Q @ H.T) / d ** 0.5
+                ref = torch.softmax(S.masked_fill(j > i, float("-inf")), dim=-1) @ V
+                assert (O[b, h, r0:r1].double() - ref).abs().max().item() <= 2e-2
+        del O, bits
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
 def test_64k_tokens_sampled(mode, window_mode):
