@@ -257,6 +257,36 @@ def test_random_decode_runs_against_the_dense_form(seed):
     assert worst <= 2e-2, worst
 
 
+def test_decode_on_a_cache_beyond_4_gib():
+    """Maximum sizes: batch 16, 32 / 8 heads of 128, 131072 cached tokens - the cache's V array alone is 4 GiB, its
+    offsets leave 32 bits - filled by one prefill (telescoped mode), then three decode steps; three batch entries
+    (first, middle, last) are compared with the dense form in fp64, with k_hat from the oracle's Eq. 2-3."""
+    import dense_form as df
+    B, Hq, Hkv, n, d, Wd, theta, steps = 16, 32, 8, 131072, 128, 128, 0.11, 3
+    L = n + steps
+    gen = torch.Generator(device="cuda").manual_seed(32)
+
+    def walk(H, clip=None):
+        x = torch.cumsum(0.15 * torch.randn(B, H, L, d, device="cuda", generator=gen), dim=2)
+        x += torch.randn(B, H, 1, d, device="cuda", generator=gen)
+        return (x.clamp(-clip, clip) if clip else x).to(torch.bfloat16)
+
+    Kd, Vd, Qd = walk(Hkv), walk(Hkv, 3.5), walk(Hq)
+    assert B * Hkv * L * d * 2 > 2 ** 32
+    cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
+    da.delta_attn_prefill(Qd[:, :, :n].contiguous(), Kd[:, :, :n].contiguous(), Vd[:, :, :n].contiguous(), theta, 512,
+                          score_mode=da.DA_SCORE_REBASE, cache=cache)
+    ids = (0, 7, B - 1)
+    khat = {b: torch.stack([torch.from_numpy(orc.delta_scan(Kd[b, hk].double().cpu().numpy(), theta)[2])
+                            for hk in range(Hkv)]).cuda() for b in ids}
+    for t in range(n, L):
+        o, _ = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        for b in ids:
+            ref = df.decode_reference(Qd[b:b + 1, :, t], Kd[b:b + 1].double(), Vd[b:b + 1].double(), khat[b][None], t, Wd)
+            assert (o[b:b + 1].double() - ref).abs().max().item() <= 2e-2
+    cache.close()
+
+
 @pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 1), (64, 8, 2)])
 def test_decode_after_a_32k_token_prompt(d, Hq, Hkv):
     """A long history: 32 768 cached tokens (512 sealed chunks per unit), then 70 steps, which cross a chunk seal."""
