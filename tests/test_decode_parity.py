@@ -257,6 +257,23 @@ def test_random_decode_runs_against_the_dense_form(seed):
     assert worst <= 2e-2, worst
 
 
+@pytest.mark.parametrize("d,dtype,Wd", [(64, "bf16", 64), (128, "bf16", 100), (64, "f32", 16), (96, "bf16", 32)])
+def test_decode_awkward_numbers(d, dtype, Wd):
+    """Both cache layouts on inputs at the edges of the number range: keys that are small multiples of the smallest
+    bf16 subnormal with thresholds of that size (masks must still match bit for bit: no flush to zero in the
+    binary32 decision), and queries eight times larger than usual (scaled scores of several hundred, a softmax that
+    is all but one-hot)."""
+    rng = np.random.default_rng(9)
+    n, steps = 150, 80
+    L = n + steps
+    tiny = wl.round_to_dtype(np.cumsum(rng.integers(-1, 2, size=(1, 2, L, d)), axis=2).astype(np.float64) * 2.0 ** -133, dtype)
+    Q, V = rand_walk(1, 1, 4, L, d, dtype), rand_walk(2, 1, 2, L, d, dtype, clip=3.5)
+    for theta in (0.0, 2.0 ** -133, 3 * 2.0 ** -133):
+        run_decode(Q, tiny, V, n, steps, theta, Wd, dtype, W_prefill=16, check_every=7)
+    big = wl.round_to_dtype(rand_walk(3, 1, 4, L, d, dtype) * 8.0, dtype)
+    run_decode(big, rand_walk(4, 1, 2, L, d, dtype), V, n, steps, 0.1, Wd, dtype, W_prefill=16, check_every=7)
+
+
 def test_decode_on_a_cache_beyond_4_gib():
     """Maximum sizes: batch 16, 32 / 8 heads of 128, 131072 cached tokens - the cache's V array alone is 4 GiB, its
     offsets leave 32 bits - filled by one prefill (telescoped mode), then three decode steps; three batch entries
