@@ -310,15 +310,29 @@ def test_random_mid_size_shapes_against_the_dense_form(seed):
     assert df.prefill_worst_error(Qd, Kd, Vd, khat, W, wm == 1, outs) <= 2e-2
 
 
-@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
-def test_64k_tokens_every_output_element_against_the_dense_form(window_mode):
+@pytest.mark.parametrize("window_mode,pieces", [(da.DA_WINDOW_BLOCK, 1), (da.DA_WINDOW_SLIDING, 1),
+                                                (da.DA_WINDOW_BLOCK, 8), (da.DA_WINDOW_SLIDING, 5)])
+def test_64k_tokens_every_output_element_against_the_dense_form(window_mode, pieces):
     """The 65536-token prompt of the test below, every output element of both score modes against the same closed
-    form, 2048 query rows at a time (the delta mask is compared with the oracle's below)."""
+    form, 2048 query rows at a time (the delta mask is compared with the oracle's below) - in one call, and fed in
+    equal pieces through the chunked entry point (the last pieces continue a cache of more than 50 000 rows)."""
     w = wl.Workload("L64K", 1, 4, 1, 128, 65536, 512, "bf16", seed=64, theta=0.11)
     x = _inputs(w)
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     n, d, W = w.seq_len, w.head_dim, w.window
-    outs = [da.delta_attn_prefill(Qd, Kd, Vd, w.theta, W, score_mode=mode, window_mode=window_mode) for mode in MODES]
+    if pieces == 1:
+        outs = [da.delta_attn_prefill(Qd, Kd, Vd, w.theta, W, score_mode=mode, window_mode=window_mode)
+                for mode in MODES]
+    else:
+        outs = []
+        cuts = [n * k // pieces for k in range(pieces + 1)]
+        for mode in MODES:
+            cache = da.Cache(1, 4, 1, d, n, W, w.theta, torch.bfloat16)
+            parts = [da.delta_attn_prefill_append(cache, Qd[:, :, a:b].contiguous(), Kd[:, :, a:b].contiguous(),
+                                                  Vd[:, :, a:b].contiguous(), w.theta, W, score_mode=mode,
+                                                  window_mode=window_mode) for a, b in zip(cuts[:-1], cuts[1:])]
+            outs.append(tuple(torch.cat([p[k] for p in parts], dim=2) for k in range(2)) + (None,))
+            cache.close()
     torch.cuda.synchronize()
     sh = torch.arange(32, device="cuda", dtype=torch.int32)
     mask = ((outs[0][1].unsqueeze(-1) >> sh) & 1).reshape(n, d).bool()
