@@ -169,7 +169,7 @@ def test_c5_long_context_sampled(mode):
 
 def test_c5_every_output_element():
     """The benchmark's launch at full size, every output element (the sampled rows above are checked against the
-    oracle): finite; inside the per-channel range of the value rows its query row may mix (Eq. 1: a weighted mean
+    oracle): the same bits on a second run; finite; inside the per-channel range of the value rows its query row may mix (Eq. 1: a weighted mean
     with weights that sum to one, whatever the approximate scores are), up to the rounding of the output; and the
     two score modes, each within 2e-2 of the oracle, within 4e-2 of each other everywhere."""
     w = wl.C5
@@ -178,7 +178,9 @@ def test_c5_every_output_element():
     theta = wl.theta_for(w)
     outs = []
     for mode in MODES:
-        O, _, _ = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+        O, bits, nnz = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+        O2, bits2, nnz2 = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+        assert torch.equal(O, O2) and torch.equal(bits, bits2) and torch.equal(nnz, nnz2)   # bitwise reproducible
         outs.append(O)
     torch.cuda.synchronize()
     g = w.n_q_heads // w.n_kv_heads
