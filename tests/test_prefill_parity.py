@@ -407,6 +407,25 @@ def test_64k_tokens_sampled(mode, window_mode):
     _sampled(w, mode, [(0, 8), (32760, 32776), (65528, 65536)], [0, 3], window_mode=window_mode)
 
 
+@pytest.mark.parametrize("dtype,n,d", [("bf16", 8192, 128), ("bf16", 30000, 64), ("f32", 5000, 96), ("bf16", 1000, 256)])
+def test_delta_scan_every_reference_key(dtype, n, d):
+    """delta_attn_delta_scan with its k_hat output at sizes of many time chunks: masks, nnz and every reference key
+    (Eq. 3) equal Eq. 2-3 written out row by row with tensor operations (binary32 decision), for thresholds from
+    dense to frozen; two units also against the oracle."""
+    import dense_form as df
+    B, Hkv = 3, 4
+    Kd = to_dev(rand_walk(11, B, Hkv, n, d, dtype), dtype)
+    for theta in (0.0, 0.05, 0.2, 3.0):
+        bits, nnz, khat = da.delta_attn_delta_scan(Kd, theta, want_khat=True)
+        ref_khat, ref_mask = df.reference_keys(Kd, theta)
+        assert (df.unpack_bits(bits, d) == ref_mask).all()
+        assert (nnz == ref_mask.sum(dim=(2, 3))).all()
+        assert (khat.double() == ref_khat).all()
+        for b, hk in ((0, 0), (B - 1, Hkv - 1)):
+            m, _, kh, _ = orc.delta_scan(Kd[b, hk].double().cpu().numpy(), theta)
+            assert (ref_mask[b, hk].cpu().numpy() == m).all() and (ref_khat[b, hk].cpu().numpy() == kh).all()
+
+
 def test_c5_sweep_masks_and_sparsity():
     """Delta masks over the compaction-density sweep (theta x jump rate): bit-exact, one unit each."""
     for w in wl.C5_SWEEP:
