@@ -18,7 +18,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, chunk_out, ents, counts, nch8, vt, total;
+    size_t khat, chunk_out, ents, counts, nch8, plan, vt, total;
 };
 
 da_status check_params(const da_prefill_params *p) {
@@ -52,6 +52,8 @@ WsLayout layout(const da_prefill_params *p) {
     off += align_up(rows * sizeof(uint32_t));
     w.nch8 = off;
     off += align_up(units * (size_t)prefill_mfma_n_pad(p->seq_len));
+    w.plan = off;
+    off += align_up(units * (size_t)prefill_mfma_n_pad(p->seq_len) * 2);   // 8 waves x 8 bytes per block of 32 columns
     w.vt = off;
     off += align_up(units * (size_t)p->head_dim * prefill_mfma_n_pad(p->seq_len) * 2);
     w.total = off;
@@ -185,6 +187,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.ents = ents;
     a.counts = counts;
     a.nch8 = nch8;
+    a.plan = ws + w.plan;
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a) && !force_generic())
@@ -206,7 +209,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
 namespace {
 // workspace of delta_attn_prefill_append: whole-sequence arrays of n_k = cached + new rows
 struct AppendLayout {
-    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, vt, total;
+    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, plan, vt, total;
 };
 
 AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
@@ -232,6 +235,8 @@ AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
     off += align_up(units * nk * sizeof(uint32_t));
     w.nch8 = off;
     off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk));
+    w.plan = off;
+    off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk) * 2);
     w.vt = off;
     off += align_up(units * d * (size_t)prefill_mfma_n_pad((int)nk) * 2);
     w.total = off;
@@ -330,6 +335,7 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.ents = ws + w.ents;
     a.counts = (const uint32_t *)(ws + w.counts);
     a.nch8 = (const uint8_t *)(ws + w.nch8);
+    a.plan = ws + w.plan;
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a) && !force_generic())

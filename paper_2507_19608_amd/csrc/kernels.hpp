@@ -30,6 +30,7 @@ struct PrefillArgs {
     const void *ents;     // EntryChunk lists, column (unit, j) at chunk (unit * n + j) * d / 8
     const uint32_t *counts;
     const uint8_t *nch8;  // chunks per column, stride prefill_mfma_n_pad(n) per unit
+    void *plan;           // scratch of the matrix-core path in gather mode: units * prefill_mfma_n_pad(n) * 2 bytes
 };
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);

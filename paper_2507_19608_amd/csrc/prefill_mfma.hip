@@ -47,7 +47,7 @@ struct MfmaArgs {
     const bf16_t *__restrict__ Vt;      // per unit: V in matrix-core operand order, D * n_pad elements
     bf16_t *__restrict__ O;
     const EntryChunk *__restrict__ ents;
-    const uint8_t *__restrict__ nch8;
+    const uint8_t *__restrict__ plan;   // per unit and block of kTB columns: kWaves x 8 bytes (pair_columns_kernel)
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const bf16_t *Hp = a.Khat + (size_t)unit * n * D;
     const bf16_t *Vtp = a.Vt + (size_t)unit * D * a.n_pad;
     const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
-    const uint8_t *Np = a.nch8 + (size_t)unit * a.n_pad;
+    const uint8_t *Pp = a.plan + (size_t)unit * (a.n_pad / kTB) * (kWaves * 8);
 
     // score row sr = hh * RT + r  ->  query row i0 + r of head head0 + hh
     auto q_row_ptr = [&](int sr) -> const bf16_t * {
@@ -249,11 +249,13 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     };
 
     // ---------------------------------------------------------------- far blocks: gather (Eq. 4)
-    // Wave w owns columns 4w .. 4w+3 of every block.  The entry chunks of those columns travel
+    // A wave takes four columns of every block, as two pairs of columns with (nearly) equal numbers of entry
+    // chunks, dealt out beforehand (pair_columns_kernel).  The entry chunks of those columns travel
     // global memory -> registers (one 16-byte load per lane, a whole block ahead) -> a private LDS
-    // ring where the block's chunks sit back to back -> uniform 16-byte LDS reads that every lane
-    // sees.  No scalar memory load sits in the inner loop, so all its LDS traffic completes in order
-    // and the loop is software-pipelined three chunks deep (three register sets that rotate).
+    // ring where the block's chunks sit back to back.  The two halves of the wave then work on the two columns of
+    // a pair at the same time, a lane on 8 score rows: one two-address 16-byte LDS read fetches a piece of a chunk
+    // of either column, one 16-byte q read per entry feeds 8 multiply-adds.  No scalar memory load sits in the
+    // inner loop, so all its LDS traffic completes in order; the loop is software-pipelined two chunks deep.
     if (kGather && far_blocks > 0) {
         const char *qtb = (const char *)qt;
         const uint32_t lane_off = (uint32_t)lane * 8u;
@@ -261,100 +263,116 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         char *ring = lds_raw + kQtBytes + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
         for (int o = lane * 16; o < kRingBytes; o += 64 * 16) *(u32x4 *)(ring + o) = u32x4{0u, 0u, 0u, 0u};
 
-        auto pack_of = [&](int blk) -> uint32_t {   // chunk counts of this wave's 4 columns, one byte each
-            return blk < far_blocks ? *(const_u32_ptr)(uintptr_t)(Np + blk * kTB + 4 * wave) : 0u;
+        // this wave's columns of a block: .x = their indices inside the block, .y = their chunk counts, one byte each;
+        // bytes 0, 1 are the first pair (longer column first), bytes 2, 3 the second
+        auto pack_of = [&](int blk) -> u32x2 {
+            if (blk >= far_blocks) return u32x2{0u, 0u};
+            const const_u32_ptr pp = (const_u32_ptr)(uintptr_t)(Pp + ((size_t)blk * kWaves + wave) * 8);
+            return u32x2{pp[0], pp[1]};
         };
-        auto g_issue = [&](u32x4 (&st)[4], int blk, uint32_t pk) {
+        auto g_issue = [&](u32x4 (&st)[4], int blk, u32x2 pk) {
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const uint32_t nch = (pk >> (8 * cc)) & 0xffu;
+                const uint32_t nch = (pk[1] >> (8 * cc)) & 0xffu, col = (pk[0] >> (8 * cc)) & 0xffu;
                 st[cc] = u32x4{0u, 0u, 0u, 0u};
                 if ((uint32_t)lane < 4u * nch)
-                    st[cc] = *(const u32x4 *)((const char *)(Ep + (size_t)(blk * kTB + 4 * wave + cc) * (D / kGroup)) +
-                                              lane * 16);
+                    st[cc] = *(const u32x4 *)((const char *)(Ep + (size_t)(blk * kTB + col) * (D / kGroup)) + lane * 16);
             }
         };
-        auto w_store = [&](const u32x4 (&st)[4], uint32_t pk) {
+        auto w_store = [&](const u32x4 (&st)[4], u32x2 pk) {
             uint32_t base = 0;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const uint32_t nch = (pk >> (8 * cc)) & 0xffu;
+                const uint32_t nch = (pk[1] >> (8 * cc)) & 0xffu;
                 if ((uint32_t)lane < 4u * nch) *(u32x4 *)(ring + base * 64 + lane * 16) = st[cc];
                 base += nch;
             }
         };
 
+        typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+        typedef const half8 __attribute__((address_space(3))) *lds_half8_ptr;
+        typedef const u32x4 __attribute__((address_space(3))) *lds_u32x4_ptr;
+        typedef const f32x4 __attribute__((address_space(3))) *lds_f32x4_ptr;
         struct Set {
-            half4 q[8];     // q values of 4 score rows at the chunk's 8 channels
+            half8 q[8];     // q values of 8 score rows at the chunk's 8 channels
             f32x4 d[2];     // the chunk's 8 deltas
-            u32x4 ch[2];    // the chunk's 8 channel indices
         };
-        auto rd_ch = [&](Set &x, uint32_t t) {
-            x.ch[0] = *(const u32x4 *)(ring + t * 64);
-            x.ch[1] = *(const u32x4 *)(ring + t * 64 + 16);
-        };
-        auto rd_d = [&](Set &x, uint32_t t) {
-            x.d[0] = *(const f32x4 *)(ring + t * 64 + 32);
-            x.d[1] = *(const f32x4 *)(ring + t * 64 + 48);
-        };
-        auto issue_q = [&](Set &x) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                x.q[i] = *(const half4 *)(qtb + (x.ch[i >> 2][i & 3] * (uint32_t)(kRows * 2) + lane_off));
-        };
+        constexpr uint32_t kZeroChunk = 4 * (D / kGroup);       // first chunk of the ring's zero pad, never written
+        const uint32_t ring_lds = (uint32_t)(uintptr_t)(char __attribute__((address_space(3))) *)ring;
+        const uint32_t q_lane = (uint32_t)(uintptr_t)(const char __attribute__((address_space(3))) *)qtb +
+                                (uint32_t)(lane & 31) * 16u;
+        const uint32_t zero_addr = ring_lds + kZeroChunk * 64u;
 
-        uint32_t pk_cur = pack_of(0), pk_nxt = pack_of(1);
+        u32x2 pk_cur = pack_of(0), pk_nxt = pack_of(1);
         u32x4 st[4];
         g_issue(st, 0, pk_cur);
 
-        auto gather_block = [&](uint32_t pk) {
-            const uint32_t total = (pk & 0xffu) + ((pk >> 8) & 0xffu) + ((pk >> 16) & 0xffu) + (pk >> 24);
-            uint32_t cend = pk & 0xffu;
-            int cc = 0;
-            float u[4] = {0.f, 0.f, 0.f, 0.f};
-            Set S0, S1, S2;
-            rd_ch(S0, 0);
-            rd_ch(S1, 1);
-            rd_ch(S2, 2);
-            issue_q(S0);
-            rd_d(S0, 0);
-            issue_q(S1);
-            rd_d(S1, 1);
-            // consume chunk t (set x) while the q / delta reads of chunks t+1 (in flight since the previous
-            // step) and t+2 (set y, issued here) and the channel reads of chunk t+3 are in flight
-            auto step = [&](Set &x, Set &y, uint32_t t) {
-                rd_ch(x, t + 3);
-                issue_q(y);
-                rd_d(y, t + 2);
+        auto gather_block = [&](u32x2 pk) {
+            uint32_t first = 0;                                  // first ring chunk of the pair's longer column
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float dl = x.d[i >> 2][i & 3];
+            for (int pair = 0; pair < 2; ++pair) {
+                const uint32_t na = (pk[1] >> (16 * pair)) & 0xffu, nb = (pk[1] >> (16 * pair + 8)) & 0xffu;
+                const uint32_t ca = (pk[0] >> (16 * pair)) & 0xffu, cb = (pk[0] >> (16 * pair + 8)) & 0xffu;
+                const uint32_t steps = na;                       // na >= nb
+                const uint32_t my_n = half ? nb : na, my_col = half ? cb : ca;
+                const uint32_t my_first = ring_lds + (half ? first + na : first) * 64u;
+                first += na + nb;
+                auto chunk_addr = [&](uint32_t t) { return t < my_n ? my_first + t * 64u : zero_addr; };
+                float u[8];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) u[r] = fmaf((float)x.q[i][r], dl, u[r]);
+                for (int r = 0; r < 8; ++r) u[r] = 0.f;
+                Set S0, S1;
+                u32x4 chn[2];                                    // channel indices of the chunk whose q reads come next
+                auto rd_ch = [&](uint32_t a) {
+                    chn[0] = *(lds_u32x4_ptr)(a);
+                    chn[1] = *(lds_u32x4_ptr)(a + 16u);
+                };
+                auto rd_d = [&](Set &x, uint32_t a) {
+                    x.d[0] = *(lds_f32x4_ptr)(a + 32u);
+                    x.d[1] = *(lds_f32x4_ptr)(a + 48u);
+                };
+                auto issue_q = [&](Set &x) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        x.q[i] = *(lds_half8_ptr)(chn[i >> 2][i & 3] * (uint32_t)(kRows * 2) + q_lane);
+                };
+                uint32_t a_next = chunk_addr(0);
+                rd_ch(a_next);
+                issue_q(S0);
+                rd_d(S0, a_next);
+                a_next = chunk_addr(1);
+                rd_ch(a_next);
+                // consume chunk t (set x) while the q / delta reads of chunk t+1 (set y, issued here) and the channel
+                // reads of chunk t+2 are in flight
+                auto step = [&](Set &x, Set &y, uint32_t t) {
+                    issue_q(y);
+                    rd_d(y, a_next);
+                    a_next = chunk_addr(t + 2);
+                    rd_ch(a_next);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float dl = x.d[i >> 2][i & 3];
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) u[r] = fmaf((float)x.q[i][r], dl, u[r]);
+                    }
+                };
+                uint32_t t = 0;
+                for (; t + 1 < steps; t += 2) {
+                    step(S0, S1, t);
+                    step(S1, S0, t + 1);
                 }
-                if (t + 1 == cend) {   // column finished: hand its update vector to the score-row owners
-                    f32x4 uv;
-                    uv[0] = u[0]; uv[1] = u[1]; uv[2] = u[2]; uv[3] = u[3];
-                    *(f32x4 *)(ubuf + (4 * wave + cc) * kRows + lane * 4) = uv;
-                    u[0] = u[1] = u[2] = u[3] = 0.f;
-                    ++cc;
-                    cend += (pk >> (8 * cc)) & 0xffu;
-                }
-            };
-            uint32_t t = 0;
-            for (; t + 2 < total; t += 3) {
-                step(S0, S2, t);
-                step(S1, S0, t + 1);
-                step(S2, S1, t + 2);
+                if (t < steps) step(S0, S1, t);
+                // both columns of the pair are done: hand their update vectors to the score-row owners
+                float *dst = ubuf + my_col * kRows + (lane & 31) * 8;
+                *(f32x4 *)dst = f32x4{u[0], u[1], u[2], u[3]};
+                *(f32x4 *)(dst + 4) = f32x4{u[4], u[5], u[6], u[7]};
             }
-            if (t < total) step(S0, S2, t);
-            if (t + 1 < total) step(S1, S0, t + 1);
         };
 
         // per block: gather -> (all waves) -> owners read the updates -> (all waves) -> softmax and PV
         for (int blk = 0; blk < far_blocks; ++blk) {
             w_store(st, pk_cur);                                 // this block's chunks into the ring
-            const uint32_t pk = pk_cur;
+            const u32x2 pk = pk_cur;
             pk_cur = pk_nxt;
             g_issue(st, blk + 1, pk_cur);                        // next block's chunks into registers
             pk_nxt = pack_of(blk + 2);
@@ -535,6 +553,54 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     }
 }
 
+// Far blocks of the gather mode: which key columns each of the 8 waves takes, and in which pairs.  One thread per
+// (unit, block of kTB columns): the columns are ranked by chunk count (ties: lower index first), neighbours in that
+// order form the 16 pairs (so the two columns of a pair have nearly the same length), and wave w takes pairs w and
+// 15 - w (long with short).  A wave's 8 bytes: the four column indices (first pair, longer column first; second pair),
+// then their chunk counts.  Blocks that reach past row n get zero counts (the kernel only gathers in blocks left of
+// every row's window).  Which wave sums a column does not change the sum.
+__global__ __launch_bounds__(64) void pair_columns_kernel(const uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan,
+                                                         int n, int n_pad) {
+    const int nblk = n_pad / kTB;
+    const int blk = blockIdx.x * 64 + threadIdx.x, unit = blockIdx.y;
+    if (blk >= nblk) return;
+    uint32_t *out = (uint32_t *)(plan + ((size_t)unit * nblk + blk) * (kWaves * 8));
+    if ((blk + 1) * kTB > n) {
+#pragma unroll
+        for (int k = 0; k < 2 * kWaves; ++k) out[k] = 0u;
+        return;
+    }
+    const uint32_t *cp = (const uint32_t *)(nch8 + (size_t)unit * n_pad + (size_t)blk * kTB);
+    uint32_t cnt[kTB];
+#pragma unroll
+    for (int k = 0; k < kTB / 4; ++k) {
+        const uint32_t w = cp[k];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cnt[4 * k + j] = (w >> (8 * j)) & 0xffu;
+    }
+    uint32_t ids[kWaves] = {}, cnts[kWaves] = {};
+#pragma unroll
+    for (int c = 0; c < kTB; ++c) {
+        uint32_t rank = 0;
+#pragma unroll
+        for (int o = 0; o < kTB; ++o) rank += (cnt[o] > cnt[c] || (cnt[o] == cnt[c] && o < c)) ? 1u : 0u;
+        const uint32_t pair = rank >> 1;
+        const uint32_t wv = pair < (uint32_t)kWaves ? pair : 15u - pair;       // pairs w and 15 - w go to wave w
+        const uint32_t slot = (pair < (uint32_t)kWaves ? 0u : 2u) + (rank & 1u); // longer column of a pair first
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+            if ((uint32_t)w == wv) {
+                ids[w] |= (uint32_t)c << (8 * slot);
+                cnts[w] |= cnt[c] << (8 * slot);
+            }
+    }
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        out[2 * w] = ids[w];
+        out[2 * w + 1] = cnts[w];
+    }
+}
+
 // V [unit][n][D] -> matrix-core operand order [unit][block of 32 keys][k-step ka][channel tile mt][lane][8]:
 // lane l of operand (ka, mt) holds channel 32 mt + l % 32 at keys 16 ka + 4 (l / 32) + {0..3} and
 // 16 ka + 8 + 4 (l / 32) + {0..3} of the block (the key order of the score tile's D registers).
@@ -584,7 +650,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.Vt = (const bf16_t *)vt;
     a.O = (bf16_t *)p.O;
     a.ents = (const EntryChunk *)p.ents;
-    a.nch8 = p.nch8;
+    a.plan = (const uint8_t *)p.plan;
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.n = p.n;
@@ -600,6 +666,9 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.nq + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
+    if (!p.rebase)
+        hipLaunchKernelGGL(pair_columns_kernel, dim3((n_pad / kTB + 63) / 64, units), dim3(64), 0, s, p.nch8,
+                           (uint8_t *)p.plan, p.n, n_pad);
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
     const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
