@@ -4,13 +4,13 @@
 // one KV head (they share K, V and the delta matrix).  Key columns are walked left to right in blocks
 // of 32.  A row's window is its square of side W on the diagonal, or the band of the W newest keys.
 //
-//   far blocks   (every row of the tile has the column outside its window): Eq. 4 as written.  Wave w
-//                takes columns 4w .. 4w+3 of the block; a lane owns 4 score rows and adds
-//                q[c] * delta for each surviving (channel, delta) entry of the column.  The entry list is
-//                wave-uniform and arrives as uniform LDS reads from a per-wave ring; q comes from a transposed
-//                fp16 copy of the Q tile in LDS (one 8-byte read feeds 4 multiply-adds).  The per-column updates u are
-//                exchanged through LDS; the owner of a score row adds them up in column order (its running
-//                Eq. 4 score).
+//   far blocks   (every row of the tile has the column outside its window): Eq. 4 as written.  A wave
+//                takes four columns of the block as two pairs of (nearly) equally long columns; its two halves
+//                work on the two columns of a pair at once, a lane on 8 score rows, adding q[c] * delta for each
+//                surviving (channel, delta) entry of its column.  The entry lists arrive as two-address LDS reads
+//                from a per-wave ring; q comes from a transposed fp16 copy of the Q tile in LDS (one 16-byte read
+//                feeds 8 multiply-adds).  The per-column updates u are exchanged through LDS; the owner of a score
+//                row adds them up in column order (its running Eq. 4 score).
 //   near blocks  (some row has the column inside its window): exact scores K Q^T on the matrix cores;
 //                where a tile straddles window squares, the not-yet-exact entries come from K_hat Q^T
 //                (Eq. 4 telescoped: sum of the deltas up to column j is the held key k_hat(j)).
