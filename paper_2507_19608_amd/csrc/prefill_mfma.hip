@@ -258,7 +258,6 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // inner loop, so all its LDS traffic completes in order; the loop is software-pipelined two chunks deep.
     if (kGather && far_blocks > 0) {
         const char *qtb = (const char *)qt;
-        const uint32_t lane_off = (uint32_t)lane * 8u;
         constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 4 * 64;
         char *ring = lds_raw + kQtBytes + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
         for (int o = lane * 16; o < kRingBytes; o += 64 * 16) *(u32x4 *)(ring + o) = u32x4{0u, 0u, 0u, 0u};
@@ -324,17 +323,17 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 Set S0, S1;
                 u32x4 chn[2];                                    // channel indices of the chunk whose q reads come next
                 auto rd_ch = [&](uint32_t a) {
-                    chn[0] = *(lds_u32x4_ptr)(a);
-                    chn[1] = *(lds_u32x4_ptr)(a + 16u);
+                    chn[0] = *(lds_u32x4_ptr)(uintptr_t)(a);
+                    chn[1] = *(lds_u32x4_ptr)(uintptr_t)(a + 16u);
                 };
                 auto rd_d = [&](Set &x, uint32_t a) {
-                    x.d[0] = *(lds_f32x4_ptr)(a + 32u);
-                    x.d[1] = *(lds_f32x4_ptr)(a + 48u);
+                    x.d[0] = *(lds_f32x4_ptr)(uintptr_t)(a + 32u);
+                    x.d[1] = *(lds_f32x4_ptr)(uintptr_t)(a + 48u);
                 };
                 auto issue_q = [&](Set &x) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
-                        x.q[i] = *(lds_half8_ptr)(chn[i >> 2][i & 3] * (uint32_t)(kRows * 2) + q_lane);
+                        x.q[i] = *(lds_half8_ptr)(uintptr_t)(chn[i >> 2][i & 3] * (uint32_t)(kRows * 2) + q_lane);
                 };
                 uint32_t a_next = chunk_addr(0);
                 rd_ch(a_next);
