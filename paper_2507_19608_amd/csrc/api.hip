@@ -160,7 +160,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
     if (p->score_mode == DA_SCORE_GATHER || cache) {
         stage_begin(kStageEmit, s);
-        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, units, p->seq_len,
+        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, ws + w.plan, units, p->seq_len,
                             prefill_mfma_n_pad(p->seq_len), p->head_dim, s);
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
@@ -308,8 +308,8 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     if (p->score_mode == DA_SCORE_GATHER) {
         stage_begin(kStageEmit, s);
         launch_emit_entries(p->dtype, ws + w.kfull, ws + w.hfull, (const uint32_t *)(ws + w.mfull), ws + w.ents,
-                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), units, nk, prefill_mfma_n_pad(nk), d,
-                            s);
+                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), ws + w.plan, units, nk,
+                            prefill_mfma_n_pad(nk), d, s);
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
     }

@@ -244,19 +244,61 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
     if (lane == 0 && adjust != 0) atomicAdd(nnz + unit, (unsigned long long)adjust);
 }
 
-// One wave per key column: ballot + prefix count turn the mask row into a dense list of
-// (channel, delta) pairs in EntryChunk form, padded with (0, 0.0f) to whole chunks and to at
+template <typename T>
+__device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__restrict__ Khat,
+                                            const uint32_t *__restrict__ mask_bits, EntryChunk *__restrict__ ents,
+                                            uint32_t *__restrict__ counts, uint8_t *__restrict__ nch8, uint32_t *blk_cnt,
+                                            int n, int n_pad, int d, int unit, int lane, int j, int slot_in_block);
+
+// One work group per block of 32 key columns, a wave per column at a time: ballot + prefix count turn the mask row into
+// a dense list of (channel, delta) pairs in EntryChunk form, padded with (0, 0.0f) to whole chunks and to at
 // least one chunk.  The chunks of column j of a unit start at chunk (unit * n + j) * d / 8;
 // counts holds the unpadded length, nch8 (stride n_pad per unit) the number of chunks.
+// plan (may be NULL): which of the block's columns each of the 8 waves of the matrix-core prefill kernel takes in its
+// gather loop, and in which pairs.  The columns are ranked by chunk count (ties: lower index first), neighbours in
+// that order form the 16 pairs (so the two columns of a pair have nearly the same length), and wave w takes pairs w
+// and 15 - w (long with short).  A wave's 8 bytes: the four column indices (first pair, longer column first; second
+// pair), then their chunk counts; blocks that reach past row n get zero counts (that kernel only gathers in blocks
+// left of every row's window).  Which wave sums a column does not change the sum.
 template <typename T>
 __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__ K, const T *__restrict__ Khat,
                                                            const uint32_t *__restrict__ mask_bits,
                                                            EntryChunk *__restrict__ ents, uint32_t *__restrict__ counts,
-                                                           uint8_t *__restrict__ nch8, int n, int n_pad, int d) {
+                                                           uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan, int n,
+                                                           int n_pad, int d) {
+    constexpr int kCols = 32, kPlanWaves = 8;                // columns per work group = the prefill kernel's key block
+    __shared__ uint32_t blk_cnt[kCols];
     const int unit = blockIdx.y;
     const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= n) return;
+    for (int k = 0; k < kCols / 4; ++k) emit_column(K, Khat, mask_bits, ents, counts, nch8, blk_cnt, n, n_pad, d, unit, lane,
+                                                    blockIdx.x * kCols + 4 * k + (threadIdx.x >> 6), 4 * k + (threadIdx.x >> 6));
+    if (!plan) return;
+    __syncthreads();
+    if (threadIdx.x < kCols) {
+        const int c = threadIdx.x;
+        const bool whole = (blockIdx.x + 1) * kCols <= n;
+        const uint32_t mine = blk_cnt[c];
+        uint32_t rank = 0;
+        for (int o = 0; o < kCols; ++o) rank += (blk_cnt[o] > mine || (blk_cnt[o] == mine && o < c)) ? 1u : 0u;
+        if (!whole) rank = (uint32_t)c;
+        const uint32_t pair = rank >> 1;
+        const uint32_t wv = pair < (uint32_t)kPlanWaves ? pair : 15u - pair;
+        const uint32_t slot = (pair < (uint32_t)kPlanWaves ? 0u : 2u) + (rank & 1u);
+        uint8_t *out = plan + (((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves + wv) * 8;
+        out[slot] = (uint8_t)c;
+        out[4 + slot] = whole ? (uint8_t)mine : (uint8_t)0;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__restrict__ Khat,
+                                            const uint32_t *__restrict__ mask_bits, EntryChunk *__restrict__ ents,
+                                            uint32_t *__restrict__ counts, uint8_t *__restrict__ nch8, uint32_t *blk_cnt,
+                                            int n, int n_pad, int d, int unit, int lane, int j, int slot_in_block) {
+    if (j >= n) {
+        if (lane == 0) blk_cnt[slot_in_block] = 0u;
+        return;
+    }
     const int wpr = d >> 5;
     const size_t row = (size_t)unit * n + j;
     const T *Kp = K + row * d;
@@ -292,6 +334,7 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
     if (lane == 0) {
         counts[row] = off;
         nch8[(size_t)unit * n_pad + j] = (uint8_t)(padded / kGroup);
+        blk_cnt[slot_in_block] = padded / kGroup;
     }
 }
 
@@ -341,14 +384,14 @@ void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits
 }
 
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s) {
-    dim3 grid((n + 3) / 4, units), block(256);
+                         uint32_t *counts, uint8_t *nch8, void *plan, int units, int n, int n_pad, int d, hipStream_t s) {
+    dim3 grid(n_pad / 32, units), block(256);
     if (dtype == 0)
         hipLaunchKernelGGL(emit_entries_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)Khat,
-                           mask_bits, (EntryChunk *)ents, counts, nch8, n, n_pad, d);
+                           mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, n, n_pad, d);
     else
         hipLaunchKernelGGL(emit_entries_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K,
-                           (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, n, n_pad, d);
+                           (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, n, n_pad, d);
 }
 
 }  // namespace da

@@ -30,15 +30,16 @@ struct PrefillArgs {
     const void *ents;     // EntryChunk lists, column (unit, j) at chunk (unit * n + j) * d / 8
     const uint32_t *counts;
     const uint8_t *nch8;  // chunks per column, stride prefill_mfma_n_pad(n) per unit
-    void *plan;           // scratch of the matrix-core path in gather mode: units * prefill_mfma_n_pad(n) * 2 bytes
+    const void *plan;     // gather mode: the column plan written by launch_emit_entries
 };
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 int delta_scan_num_chunks(int n);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr);
+// plan: NULL, or room for units * n_pad * 2 bytes: the gather loop's column plan (see emit_entries_kernel)
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, uint8_t *nch8, int units, int n, int n_pad, int d, hipStream_t s);
+                         uint32_t *counts, uint8_t *nch8, void *plan, int units, int n, int n_pad, int d, hipStream_t s);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if
 // the head_dim has no instantiation.
 bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);

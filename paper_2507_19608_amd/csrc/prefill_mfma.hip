@@ -47,7 +47,7 @@ struct MfmaArgs {
     const bf16_t *__restrict__ Vt;      // per unit: V in matrix-core operand order, D * n_pad elements
     bf16_t *__restrict__ O;
     const EntryChunk *__restrict__ ents;
-    const uint8_t *__restrict__ plan;   // per unit and block of kTB columns: kWaves x 8 bytes (pair_columns_kernel)
+    const uint8_t *__restrict__ plan;   // per unit and block of kTB columns: kWaves x 8 bytes (emit_entries_kernel)
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
     // ---------------------------------------------------------------- far blocks: gather (Eq. 4)
     // A wave takes four columns of every block, as two pairs of columns with (nearly) equal numbers of entry
-    // chunks, dealt out beforehand (pair_columns_kernel).  The entry chunks of those columns travel
+    // chunks, dealt out beforehand (emit_entries_kernel).  The entry chunks of those columns travel
     // global memory -> registers (one 16-byte load per lane, a whole block ahead) -> a private LDS
     // ring where the block's chunks sit back to back.  The two halves of the wave then work on the two columns of
     // a pair at the same time, a lane on 8 score rows: one two-address 16-byte LDS read fetches a piece of a chunk
@@ -552,54 +552,6 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     }
 }
 
-// Far blocks of the gather mode: which key columns each of the 8 waves takes, and in which pairs.  One thread per
-// (unit, block of kTB columns): the columns are ranked by chunk count (ties: lower index first), neighbours in that
-// order form the 16 pairs (so the two columns of a pair have nearly the same length), and wave w takes pairs w and
-// 15 - w (long with short).  A wave's 8 bytes: the four column indices (first pair, longer column first; second pair),
-// then their chunk counts.  Blocks that reach past row n get zero counts (the kernel only gathers in blocks left of
-// every row's window).  Which wave sums a column does not change the sum.
-__global__ __launch_bounds__(64) void pair_columns_kernel(const uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan,
-                                                         int n, int n_pad) {
-    const int nblk = n_pad / kTB;
-    const int blk = blockIdx.x * 64 + threadIdx.x, unit = blockIdx.y;
-    if (blk >= nblk) return;
-    uint32_t *out = (uint32_t *)(plan + ((size_t)unit * nblk + blk) * (kWaves * 8));
-    if ((blk + 1) * kTB > n) {
-#pragma unroll
-        for (int k = 0; k < 2 * kWaves; ++k) out[k] = 0u;
-        return;
-    }
-    const uint32_t *cp = (const uint32_t *)(nch8 + (size_t)unit * n_pad + (size_t)blk * kTB);
-    uint32_t cnt[kTB];
-#pragma unroll
-    for (int k = 0; k < kTB / 4; ++k) {
-        const uint32_t w = cp[k];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cnt[4 * k + j] = (w >> (8 * j)) & 0xffu;
-    }
-    uint32_t ids[kWaves] = {}, cnts[kWaves] = {};
-#pragma unroll
-    for (int c = 0; c < kTB; ++c) {
-        uint32_t rank = 0;
-#pragma unroll
-        for (int o = 0; o < kTB; ++o) rank += (cnt[o] > cnt[c] || (cnt[o] == cnt[c] && o < c)) ? 1u : 0u;
-        const uint32_t pair = rank >> 1;
-        const uint32_t wv = pair < (uint32_t)kWaves ? pair : 15u - pair;       // pairs w and 15 - w go to wave w
-        const uint32_t slot = (pair < (uint32_t)kWaves ? 0u : 2u) + (rank & 1u); // longer column of a pair first
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-            if ((uint32_t)w == wv) {
-                ids[w] |= (uint32_t)c << (8 * slot);
-                cnts[w] |= cnt[c] << (8 * slot);
-            }
-    }
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        out[2 * w] = ids[w];
-        out[2 * w + 1] = cnts[w];
-    }
-}
-
 // V [unit][n][D] -> matrix-core operand order [unit][block of 32 keys][k-step ka][channel tile mt][lane][8]:
 // lane l of operand (ka, mt) holds channel 32 mt + l % 32 at keys 16 ka + 4 (l / 32) + {0..3} and
 // 16 ka + 8 + 4 (l / 32) + {0..3} of the block (the key order of the score tile's D registers).
@@ -665,9 +617,6 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.nq + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
-    if (!p.rebase)
-        hipLaunchKernelGGL(pair_columns_kernel, dim3((n_pad / kTB + 63) / 64, units), dim3(64), 0, s, p.nch8,
-                           (uint8_t *)p.plan, p.n, n_pad);
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
     const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
