@@ -30,8 +30,8 @@ MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 71.3
 # WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
 # Counters cannot be read from inside this process, so other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("C5/p05/s60", "gather"): (760.3 + 160.0) * 2 ** 20,
-    ("C5/p05/s60", "rebase"): (451.4 + 160.0) * 2 ** 20,
+    ("C5/p05/s60", "gather"): (761.5 + 160.0) * 2 ** 20,
+    ("C5/p05/s60", "rebase"): (451.2 + 160.0) * 2 ** 20,
     ("C4/p05/s57", "decode"): (111.16 + 0.71) * 2 ** 20,
 }
 
