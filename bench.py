@@ -345,46 +345,6 @@ def decode_sweep(args, da, wl, torch, np):
     return rows
 
 
-def hbm_read_probe(da, torch):
-    """What this GPU sustains: streaming-read rate on a buffer of the decode step's size and on 1 GiB, with the access
-    shape of the decode kernel (delta_attn_stream_read); bf16 MFMA and unpacked fp32 FMA rates from register-only
-    loops at 2 and 8 waves per SIMD (delta_attn_rate_probe).  Context for the roofline fractions, which use published peaks."""
-    out = {}
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    for name, nbytes, nbuf in (("108_MiB", 108 << 20, 4), ("1_GiB", 1 << 30, 2)):
-        xs = [torch.ones(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(nbuf)]   # rotate: no cache reuse
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        best, launches = float("inf"), 16   # back to back, so that host launch latency is not in the figure
-        for rep in range(4):
-            e0.record()
-            for i in range(launches):
-                da.delta_attn_stream_read(xs[i % nbuf], sink)
-            e1.record()
-            torch.cuda.synchronize()
-            if rep >= 1:
-                best = min(best, e0.elapsed_time(e1) / launches)
-        out[name] = {"ms": best, "GB/s": nbytes / (best * 1e-3) / 1e9}
-        del xs
-    # arithmetic rates: register-only chains, work groups of 4 waves (one per SIMD)
-    fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    for name, kind, iters in (("mfma_bf16_32x32x16", 0, 20000), ("fma_fp32_literal_multiplier", 1, 20000),
-                              ("fma_fp32_three_registers", 2, 20000), ("fma_mixed_fp16_fp32", 3, 20000)):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        out[name] = {}
-        for waves_per_simd in (2, 8):                    # the prefill kernel's occupancy, and a well-filled chip
-            best = float("inf")
-            for rep in range(4):
-                e0.record()
-                flop = da.delta_attn_rate_probe(kind, cus * waves_per_simd, iters, fsink)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep >= 1:
-                    best = min(best, e0.elapsed_time(e1))
-            out[name][f"TFLOP/s_at_{waves_per_simd}_waves_per_simd"] = flop / (best * 1e-3) / 1e12
-    return out
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -413,8 +373,6 @@ def main():
                     help="only run the 12-point C5 sweep (threshold x jump rate), both score modes, and exit")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="decode step time over head sizes and unit counts under both launch plans")
-    ap.add_argument("--hbm-read-probe", action="store_true",
-                    help="only measure the streaming-read rate of this GPU (context for the decode roofline) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build is a single-GPU kernel library; run with --gpus 1\n")
@@ -427,9 +385,6 @@ def main():
         sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
         sys.exit(1)
     da.lib()
-    if args.hbm_read_probe:
-        print(json.dumps({"hbm_read_probe": hbm_read_probe(da, torch)}))
-        return
     if args.decode_sweep:
         print(json.dumps({"decode_sweep": decode_sweep(args, da, wl, torch, np)}))
         return

@@ -36,8 +36,9 @@ typedef enum {
     DA_OK = 0,
     DA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, Hq % Hkv != 0, window < 1, theta < 0 or NaN */
     DA_ERR_UNSUPPORTED = 2,   /* head_dim not a multiple of 32 or > 256, unknown dtype or mode */
-    DA_ERR_WORKSPACE = 3,     /* workspace pointer null or smaller than *_workspace_bytes() */
-    DA_ERR_STATE = 4,         /* cache full, prefill into a non-empty cache, cache/params mismatch */
+    DA_ERR_WORKSPACE = 3,     /* workspace pointer null, not 256-byte aligned, or smaller than *_workspace_bytes() */
+    DA_ERR_STATE = 4,         /* cache full, prefill into a non-empty cache, cache/params mismatch (shape, dtype,
+                                 theta, or a score scale other than the cache's) */
     DA_ERR_HIP = 5            /* a HIP runtime call failed */
 } da_status;
 
@@ -84,29 +85,13 @@ const char *delta_attn_last_error(void);
  * delta_attn_stage_timing_read, called after the caller has synchronised those streams, sums the
  * elapsed milliseconds and the number of launches per stage since the previous read and returns
  * the number of brackets read (-1 on a null pointer).  Both arrays have DA_NUM_STAGES entries.
- * Not thread-safe; meant for a single benchmarking thread.
+ * A benchmarking aid, off by default: the switch and the event pool are process-wide (guarded by a mutex), so
+ * with timing on, calls from several threads are bracketed into one common pool.
  */
 enum { DA_STAGE_SCAN = 0, DA_STAGE_EMIT = 1, DA_STAGE_ATTN = 2, DA_STAGE_CACHE_FILL = 3,
        DA_STAGE_APPEND = 4, DA_STAGE_CHUNK = 5, DA_STAGE_COMBINE = 6, DA_NUM_STAGES = 7 };
 void delta_attn_stage_timing_enable(int32_t on);
 int32_t delta_attn_stage_timing_read(double *ms_per_stage, int32_t *calls_per_stage);
-
-/* Measurement aid for the decode roofline (no part of the method): one launch that reads `bytes` (a
- * multiple of 1024) of device memory at `src` once, with the access shape of the decode kernel's streams
- * (single-wave work groups, 16 KiB each, 128-bit loads), and writes one word to `sink` (device, may equal
- * nothing else in use).  Timed by the caller, it gives the streaming-read rate this GPU reaches on a buffer
- * of that size, which is below the published HBM peak. */
-da_status delta_attn_stream_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
-
-/* Measurement aid, like delta_attn_stream_read: one launch of `work_groups` x 256 threads in which every wave
- * runs `iters` rounds of independent register-only chains - kind 0: four 32x32x16 bf16 MFMA accumulations per
- * round; kind 1: sixteen fp32 fused multiply-adds per lane per round whose multiplier is an instruction literal
- * (two register sources each); kind 2: the same with all three operands in registers (compiled like the rest of the
- * library, i.e. without packed-fp32 instructions); kind 3: the same count of multiply-adds in the mixed form of the
- * prefill kernel's gather loop (fp16 multiplicand widened by the instruction, fp32 multiplier and sum).  *flop receives the floating-point operations of the launch (host);
- * timed by the caller it gives the arithmetic rates this GPU sustains, to set beside the published peaks. */
-da_status delta_attn_rate_probe(int32_t kind, int32_t work_groups, int32_t iters, float *sink, double *flop,
-                                void *hip_stream);
 
 /* Eq. 5: min(floor(gamma * n), w_max), clamped to >= 1.  Host only. */
 int32_t delta_attn_window_from_gamma(int32_t n, double gamma, int32_t w_max);
@@ -140,7 +125,7 @@ da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint3
  *   mask_bits, nnz as in delta_attn_delta_scan
  *   cache     NULL, or an EMPTY cache with matching batch/heads/head_dim/theta/dtype and
  *             max_seq >= n: left holding the n rows, ready for delta_attn_decode at position n
- *   workspace device scratch of at least delta_attn_prefill_workspace_bytes(p)
+ *   workspace device scratch of at least delta_attn_prefill_workspace_bytes(p), 256-byte aligned
  */
 da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const void *K, const void *V,
                              void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache,
@@ -197,7 +182,8 @@ da_status delta_attn_cache_set_launch_plan(da_cache *c, int32_t merge_in_kernel,
  * One decode step at position t = cache length (Sec. III-B decode stage, Sec. III-C): appends
  * the delta row of k_new and v_new to the cache, then attends q_new over keys 0..t with exact
  * scores for the decode_window most recent keys (the new one included) and Eq. 4 scores for
- * older keys.
+ * older keys.  The cache length advances when the step has been enqueued without error (the call does not wait for
+ * the GPU).
  *   q_new [B, Hq, d], k_new, v_new [B, Hkv, d] in;  o [B, Hq, d] out
  *   mask_row [B, Hkv, d/32] out or NULL: mask of the appended row
  */

@@ -9,7 +9,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("DELTA_ATTN_LIB", os.path.join(HERE, "libdelta_attn.so"))   # override: load another build
+LIB_PATH = os.path.join(HERE, "libdelta_attn.so")
 
 DA_OK = 0
 DA_F32, DA_BF16 = 0, 1
@@ -18,7 +18,7 @@ DA_WINDOW_BLOCK, DA_WINDOW_SLIDING = 0, 1
 
 EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
-    "delta_attn_stream_read", "delta_attn_rate_probe", "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
+    "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
     "delta_attn_prefill_append_workspace_bytes", "delta_attn_prefill_append", "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_set_launch_plan", "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
@@ -55,10 +55,6 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_status_string.restype = ctypes.c_char_p
         L.delta_attn_status_string.argtypes = [ctypes.c_int]
         L.delta_attn_last_error.restype = ctypes.c_char_p
-        L.delta_attn_stream_read.restype = ctypes.c_int
-        L.delta_attn_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
-        L.delta_attn_rate_probe.restype = ctypes.c_int
-        L.delta_attn_rate_probe.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.delta_attn_stage_timing_enable.restype = None
         L.delta_attn_stage_timing_enable.argtypes = [i32]
         L.delta_attn_stage_timing_read.restype = i32
@@ -112,22 +108,6 @@ def delta_attn_window_from_gamma(n: int, gamma: float, w_max: int) -> int:
 
 
 STAGES = ("scan", "emit", "attn", "cache_fill", "append", "chunk", "combine")
-
-
-def delta_attn_stream_read(buf, sink):
-    """Measurement aid: one streaming read of the device tensor `buf` (byte size a multiple of 1024)."""
-    _dev(buf, "buf")
-    _check(lib().delta_attn_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()),
-           "delta_attn_stream_read")
-
-
-def delta_attn_rate_probe(kind: int, work_groups: int, iters: int, sink) -> float:
-    """Measurement aid: launches the arithmetic-rate probe (0: bf16 MFMA, 1 / 2: fp32 FMA with a literal / register multiplier,
-    3: fp16 x fp32 + fp32 FMA); returns its flop count."""
-    flop = ctypes.c_double()
-    _check(lib().delta_attn_rate_probe(int(kind), int(work_groups), int(iters), sink.data_ptr(), ctypes.byref(flop),
-                                       _stream()), "delta_attn_rate_probe")
-    return flop.value
 
 
 def delta_attn_stage_timing_enable(on: bool):

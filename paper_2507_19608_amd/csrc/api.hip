@@ -60,16 +60,13 @@ WsLayout layout(const da_prefill_params *p) {
     return w;
 }
 
-// DELTA_ATTN_FORCE_GENERIC=1 routes every prefill through the generic vector-ALU kernel (testing aid)
-inline bool force_generic() {
-    static const bool v = [] {
-        const char *e = getenv("DELTA_ATTN_FORCE_GENERIC");
-        return e && e[0] == '1';
-    }();
-    return v;
-}
+inline float score_scale(float scale, int d) { return resolved_scale(scale, d); }
 
-inline float score_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f / sqrtf((float)d); }
+da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const void *Q, const void *K, const void *V,
+                          void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace, hipStream_t s);
+
+// the kernels read the workspace with 16-byte loads and 64-byte entry chunks; regions are carved at multiples of 256
+inline bool ws_aligned(const void *ws) { return ((uintptr_t)ws & (kAlign - 1)) == 0; }
 
 }  // namespace
 
@@ -123,7 +120,7 @@ da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint3
     if (st != DA_OK) return st;
     if (!K || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     const WsLayout w = layout(p);
-    if (!workspace || workspace_bytes < w.ents) return DA_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < w.ents || !ws_aligned(workspace)) return DA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     (void)hipGetLastError();
@@ -139,12 +136,21 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     if (st != DA_OK) return st;
     if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     const WsLayout w = layout(p);
-    if (!workspace || workspace_bytes < w.total) return DA_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < w.total || !ws_aligned(workspace)) return DA_ERR_WORKSPACE;
     if (cache) {
         st = cache_check_for_prefill(cache, p);
         if (st != DA_OK) return st;
     }
-    hipStream_t s = (hipStream_t)hip_stream;
+    return prefill_checked(p, w, Q, K, V, O, mask_bits, nnz, cache, workspace, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+// the body of delta_attn_prefill; arguments, workspace and cache have been checked
+da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const void *Q, const void *K, const void *V,
+                          void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace,
+                          hipStream_t s) {
     char *ws = (char *)workspace;
     void *khat = ws + w.khat;
     void *ents = ws + w.ents;
@@ -190,7 +196,7 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     a.plan = ws + w.plan;
     stage_begin(kStageAttn, s);
     bool launched = true;
-    if (prefill_mfma_supported(a) && !force_generic())
+    if (prefill_mfma_supported(a))
         launch_prefill_mfma(a, ws + w.vt, s);
     else
         launched = launch_prefill_generic(a, s);
@@ -206,7 +212,6 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     return DA_OK;
 }
 
-namespace {
 // workspace of delta_attn_prefill_append: whole-sequence arrays of n_k = cached + new rows
 struct AppendLayout {
     size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, plan, vt, total;
@@ -251,6 +256,7 @@ da_status check_append(const da_prefill_params *p, const da_cache *c) {
     if (c->B != p->batch || c->Hq != p->n_q_heads || c->Hkv != p->n_kv_heads || c->d != p->head_dim ||
         c->dtype != p->dtype || c->theta != p->theta)
         return DA_ERR_STATE;
+    if (!cache_scale_matches(c, p->scale)) return DA_ERR_STATE;   // one score scale for prefill and decode (Eq. 1)
     if (c->len + p->seq_len > c->max_seq) return DA_ERR_STATE;
     // raw keys of a window come from the ring of the decode_window newest rows; no window reaches back further
     // than the sequence is long
@@ -259,6 +265,8 @@ da_status check_append(const da_prefill_params *p, const da_cache *c) {
     return DA_OK;
 }
 }  // namespace
+
+extern "C" {
 
 size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache) {
     if (check_append(p, cache) != DA_OK) return 0;
@@ -273,7 +281,7 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     const int t0 = (int)cache->len, m = p->seq_len, nk = t0 + m, d = p->head_dim;
     const AppendLayout w = append_layout(p, t0);
-    if (!workspace || workspace_bytes < w.total) return DA_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < w.total || !ws_aligned(workspace)) return DA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     const int units = p->batch * p->n_kv_heads;
@@ -338,7 +346,7 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.plan = ws + w.plan;
     stage_begin(kStageAttn, s);
     bool launched = true;
-    if (prefill_mfma_supported(a) && !force_generic())
+    if (prefill_mfma_supported(a))
         launch_prefill_mfma(a, ws + w.vt, s);
     else
         launched = launch_prefill_generic(a, s);

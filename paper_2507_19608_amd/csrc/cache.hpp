@@ -1,6 +1,7 @@
 // Decode-time cache object (Sec. III-A last paragraph, Sec. III-C).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "../../include/delta_attn.h"
@@ -12,6 +13,7 @@ struct da_cache {
     float theta, scale;
     int64_t len;          // rows held (all sequences of the batch advance together)
     int device;
+    int cus;              // compute units of `device` (0 until the first decode step has asked)
     int nck;              // checkpoints per unit: max_seq / kChunk + 1
     int max_chunks;       // (max_seq + kChunk - 1) / kChunk
     int vrows;            // max_seq rounded up to a whole chunk (row capacity of V)
@@ -51,6 +53,11 @@ __host__ __device__ inline size_t run_room_stride(int d) { return (size_t)(kChun
 __host__ __device__ inline int part_stride(int d) { return d + 4; }
 
 namespace da {
+// the scale a params value stands for: 0 selects 1 / sqrt(head_dim) (Eq. 1)
+inline float resolved_scale(float scale, int d) { return scale > 0.f ? scale : 1.0f / sqrtf((float)d); }
+inline bool cache_scale_matches(const da_cache *c, float scale) {
+    return resolved_scale(scale, c->d) == resolved_scale(c->scale, c->d);
+}
 da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p);
 void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void *K, const void *V,
                              const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,

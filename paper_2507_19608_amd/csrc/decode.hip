@@ -604,13 +604,9 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     }
     if (c->dtype == DA_BF16) {
         const size_t lds = ((size_t)16 * (c->d + 8) + (size_t)kChunk * c->d + 16) * 2 + 16 * (kChunk + 8) * 2;
-        static bool attr_done = false;   // d = 256 needs more than 64 KiB
-        if (!attr_done) {
-            (void)hipFuncSetAttribute((const void *)decode_step_bf16_kernel<0>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)(((size_t)16 * 264 + (size_t)kChunk * 256 + 16) * 2 + 16 * (kChunk + 8) * 2));
-            attr_done = true;
-        }
+        static std::atomic<uint64_t> lds_set;   // d = 256 needs more than 64 KiB; one bit per device
+        ensure_dynamic_lds((const void *)decode_step_bf16_kernel<0>,
+                           (int)(((size_t)16 * 264 + (size_t)kChunk * 256 + 16) * 2 + 16 * (kChunk + 8) * 2), lds_set);
         stage_begin(kStageChunk, s);
         const dim3 grid(nchunks, units), block(64);
         if (c->d == 64)
@@ -635,12 +631,9 @@ void decode_launch(da_cache *c, const void *q, const void *k, const void *v, voi
     stage_begin(kStageChunk, s);
     {
         const size_t lds = ((size_t)kChunk * (c->d + 1) + kChunk) * sizeof(float);
-        static bool attr_done = false;   // d = 256 needs slightly more than 64 KiB
-        if (!attr_done) {
-            (void)hipFuncSetAttribute((const void *)decode_chunk_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)));
-            attr_done = true;
-        }
+        static std::atomic<uint64_t> lds_set;   // d = 256 needs slightly more than 64 KiB; one bit per device
+        ensure_dynamic_lds((const void *)decode_chunk_kernel<T>, (int)(((size_t)kChunk * 257 + kChunk) * sizeof(float)),
+                           lds_set);
         hipLaunchKernelGGL(decode_chunk_kernel<T>, dim3(nchunks, units), dim3(64), lds, s, *c, (const T *)q, t, sc);
     }
     stage_end(kStageChunk, s);
@@ -664,6 +657,7 @@ da_status cache_check_for_prefill(const da_cache *c, const da_prefill_params *p)
     if (c->B != p->batch || c->Hq != p->n_q_heads || c->Hkv != p->n_kv_heads || c->d != p->head_dim ||
         c->dtype != p->dtype || c->theta != p->theta || c->max_seq < p->seq_len)
         return DA_ERR_STATE;
+    if (!cache_scale_matches(c, p->scale)) return DA_ERR_STATE;   // one score scale for prefill and decode (Eq. 1)
     return DA_OK;
 }
 

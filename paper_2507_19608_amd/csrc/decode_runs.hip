@@ -634,9 +634,10 @@ int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, v
     const int units = c->B * c->Hkv, nchunks = t / kChunk + 1;
     // A launch is sized so that all of its waves are resident at once: 4 SIMDs per CU, 2 waves per SIMD by the
     // kernel's registers and LDS.  At head_dim 128 two waves share every chunk, so half as many chunk walkers fit.
-    static int cus = 0;
-    if (!cus && (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1))
-        cus = 256;
+    if (c->cus < 1 &&
+        (hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->cus < 1))
+        c->cus = 256;
+    const int cus = c->cus;
     const int slots = (c->plan_slots > 0 ? c->plan_slots : cus * 8) / (c->d == 64 ? 1 : 2);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     // head_dim 64: one 8-wave work group per unit whose waves split the unit's chunks and merge in LDS (the

@@ -3,7 +3,10 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <stdarg.h>
 #include <stdio.h>
+
+#include <mutex>
 
 namespace da {
 
@@ -18,6 +21,22 @@ bool launch_ok(const char *stage) {
 
 const char *last_error_text() { return g_last_error; }
 
+void set_last_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+    va_end(ap);
+}
+
+void ensure_dynamic_lds(const void *fn, int bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;   // ordinals past 62 share a bit: set every time
+    const uint64_t bit = (uint64_t)1 << dev;
+    if (dev < 63 && (done.load(std::memory_order_acquire) & bit)) return;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess)
+        done.fetch_or(bit, std::memory_order_release);
+}
+
 // ---- stage timing: a pool of event pairs, filled in call order, summed and recycled by the reader
 namespace {
 constexpr int kMaxPairs = 8192;
@@ -25,13 +44,16 @@ struct Pair {
     hipEvent_t a, b;
     int stage;
 };
-bool g_timing = false;
+std::mutex g_timing_mutex;   // the pool is process-wide: a benchmarking aid, serialised rather than per call
+std::atomic<bool> g_timing{false};
 Pair g_pairs[kMaxPairs];
 int g_created = 0, g_used = 0, g_open[kNumStages];
 }  // namespace
 
 void stage_begin(int stage, hipStream_t s) {
-    if (!g_timing || g_used >= kMaxPairs) return;
+    if (!g_timing.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (g_used >= kMaxPairs) return;
     if (g_used >= g_created) {
         if (hipEventCreate(&g_pairs[g_created].a) != hipSuccess) return;
         if (hipEventCreate(&g_pairs[g_created].b) != hipSuccess) return;
@@ -44,13 +66,16 @@ void stage_begin(int stage, hipStream_t s) {
 }
 
 void stage_end(int stage, hipStream_t s) {
-    if (!g_timing || g_open[stage] < 0) return;
+    if (!g_timing.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (g_open[stage] < 0) return;
     (void)hipEventRecord(g_pairs[g_open[stage]].b, s);
     g_open[stage] = -1;
 }
 
 void timing_enable(bool on) {
-    g_timing = on;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    g_timing.store(on);
     g_used = 0;
     for (int i = 0; i < kNumStages; ++i) g_open[i] = -1;
 }
@@ -58,6 +83,7 @@ void timing_enable(bool on) {
 // Sums elapsed ms per stage over everything recorded since the last read; the caller has
 // synchronised the streams involved.  Returns the number of event pairs read.
 int timing_collect(double *ms_per_stage, int *calls_per_stage) {
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
     for (int i = 0; i < kNumStages; ++i) {
         ms_per_stage[i] = 0.0;
         calls_per_stage[i] = 0;

@@ -3,12 +3,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace da {
+
+// Raises the dynamic-LDS limit of kernel `fn` to `bytes` on the current device, once per device (`done` holds one bit
+// per device ordinal; safe to call from several threads).  On failure the error is left for launch_ok() to report
+// and the next call tries again.
+void ensure_dynamic_lds(const void *fn, int bytes, std::atomic<uint64_t> &done);
 
 // Checks hipGetLastError(); on failure records "<stage>: <hip error>" for delta_attn_last_error()
 // and returns false.
 bool launch_ok(const char *stage);
 const char *last_error_text();
+// records a printf-style message as the calling thread's last error text
+void set_last_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 
 // Optional per-stage timing with HIP events recorded on the caller's stream (off by default).
 enum Stage { kStageScan = 0, kStageEmit, kStageAttn, kStageCacheFill, kStageAppend, kStageChunk, kStageCombine,

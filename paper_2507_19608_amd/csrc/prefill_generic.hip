@@ -150,12 +150,8 @@ static void launch_one(const PrefillArgs &p, hipStream_t s) {
     a.rebase = p.rebase;
     a.scale_log2 = p.scale_log2;
     const size_t lds = (size_t)D * 64 * sizeof(float);
-    static bool attr_done = false;   // per instantiation
-    if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)prefill_generic_kernel<T, D>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set;   // per instantiation, one bit per device
+    ensure_dynamic_lds((const void *)prefill_generic_kernel<T, D>, (int)lds, lds_set);
     dim3 grid((p.nq + 63) / 64, p.Hq, p.B), block(64);
     hipLaunchKernelGGL((prefill_generic_kernel<T, D>), grid, block, lds, s, a);
 }

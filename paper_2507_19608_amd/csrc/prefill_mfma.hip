@@ -620,18 +620,11 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
     const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true, false>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gather);
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, true, true>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gather);
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false, false>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_near);
-        (void)hipFuncSetAttribute((const void *)prefill_mfma_kernel<D, false, true>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_near);
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set[4];                     // per instantiation of launch_d, one bit per device
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, false>, (int)lds_gather, lds_set[0]);
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, true>, (int)lds_gather, lds_set[1]);
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, false>, (int)lds_near, lds_set[2]);
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, true>, (int)lds_near, lds_set[3]);
     const size_t blocks = (size_t)units * a.tiles * a.hgroups;
     // XCD-aware order needs units * xsplit parts to deal out evenly over 8 XCDs and a unit to split evenly
     a.xsplit = 0;

@@ -17,13 +17,36 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(delta_attn_\w+)\s*\(", text)))
 
 
+# the boundary: the calls the method needs (prefill, decode, delta scan, sparsity, Eq. 5 window, cache life cycle,
+# workspace sizes, status / error text) plus the documented extensions (chunked prefill, launch plan, stage timing for
+# benchmarks)
+BOUNDARY = sorted([
+    "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
+    "delta_attn_window_from_gamma", "delta_attn_sparsity",
+    "delta_attn_prefill_workspace_bytes", "delta_attn_prefill",
+    "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan",
+    "delta_attn_prefill_append_workspace_bytes", "delta_attn_prefill_append",
+    "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset", "delta_attn_cache_length",
+    "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_cache_set_launch_plan", "delta_attn_decode",
+    "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read",
+])
+
+
+def exported_symbols():
+    """Dynamic symbols of the built library that carry the boundary's prefix (read with nm)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True)
+    return sorted({ln.split()[-1] for ln in out.stdout.splitlines() if ln.split()[-1].startswith("delta_attn_")})
+
+
 def test_header_symbols_are_exported():
     names = declared_symbols()
-    assert len(names) >= 23
+    assert names == BOUNDARY
     L = binding.lib()
     for n in names:
         assert hasattr(L, n), n
     assert sorted(binding.EXPORTS) == names
+    assert exported_symbols() == names          # nothing beyond the header leaves the library (no probes, no tools)
 
 
 def test_host_only_entry_points():
@@ -60,7 +83,9 @@ def test_workspace_size_and_argument_checks():
     assert st == 2
     st = L.delta_attn_prefill(ctypes.byref(p), None, 1, 1, 1, 1, 1, None, 1, 1 << 40, None)
     assert st == 1
-    st = L.delta_attn_prefill(ctypes.byref(p), 1, 1, 1, 1, 1, 1, None, 1, need - 1, None)
+    st = L.delta_attn_prefill(ctypes.byref(p), 1, 1, 1, 1, 1, 1, None, 256, need - 1, None)
+    assert st == 3
+    st = L.delta_attn_prefill(ctypes.byref(p), 1, 1, 1, 1, 1, 1, None, 256 + 64, need, None)   # not 256-byte aligned
     assert st == 3
     assert L.delta_attn_decode(None, 1, 1, 1, 1, None, None) == 1
     assert L.delta_attn_cache_length(None) == -1

@@ -169,6 +169,32 @@ def test_strict_inequality_and_binary32_decision(oracle):
     assert oracle.delta_scan(K, 0.1)[0].ravel().tolist() == [1, 1]
 
 
+def test_knife_edge_counter_counts_binary32_roundings(oracle):
+    """The scan's fourth result counts entries whose threshold decision would differ if the subtraction of Eq. 2 were
+    made in binary64 instead of binary32.  Hand-made fp32 keys, theta = 1 + 2^-23 (a binary32 value; one ulp there is
+    2^-23, so a residue of 2^-30 is rounded away by the binary32 subtraction):
+      channel 0: held -2^-30 (basis).  Row 1: k = 1 + 2^-23: the exact difference 1 + 2^-23 + 2^-30 exceeds theta, the
+                 binary32 difference rounds to theta itself and does not (strict >): no fire, one knife edge.
+                 Row 2: k = 1 + 2^-22: fires either way.  Row 3: k unchanged: difference 0.
+      channel 1: held 2^-30.  Row 1: k = 1 + 2^-23: exact difference 1 + 2^-23 - 2^-30 is below theta, binary32 gives
+                 theta: no fire either way.  Row 2: unchanged.  Row 3: k = -(1 + 2^-23): exact |difference| is
+                 1 + 2^-23 + 2^-30 > theta, binary32 gives theta: no fire, a second knife edge.
+    Rounding to nearest is monotone, so binary32 can only turn a binary64 'fire' into 'hold', never the reverse."""
+    e = 2.0 ** -30
+    a, b = 1.0 + 2.0 ** -23, 1.0 + 2.0 ** -22
+    theta = np.float32(a)
+    K = np.array([[-e, e], [a, a], [b, a], [b, -a]])
+    assert (K.astype(np.float32).astype(np.float64) == K).all()         # every entry is a binary32 value
+    mask, dK, Khat, knife = oracle.delta_scan(K, theta)
+    assert mask.tolist() == [[1, 1], [0, 0], [1, 0], [0, 0]]
+    assert Khat.tolist() == [[-e, e], [-e, e], [b, e], [b, e]]
+    assert dK[2, 0] == b + e and dK[1].tolist() == [0.0, 0.0]
+    assert knife == 2
+    # the same keys with a threshold one ulp lower: every decision is clear of the edge
+    mask, _, _, knife = oracle.delta_scan(K, np.float32(1.0))
+    assert mask.tolist() == [[1, 1], [1, 1], [0, 0], [0, 1]] and knife == 0
+
+
 def test_closed_forms_of_the_delta_matrix(oracle):
     n, d = 64, 8
     # constant keys: only the basis row survives -> S_m = (n-1)/n

@@ -200,24 +200,20 @@ def test_c5_every_output_element():
 def test_c5_every_output_element_against_the_dense_form(how):
     """Every output element of the benchmark's launch against the closed form the oracle is pinned to: outside a
     row's window (square, or band) the Eq. 4 score is q . k_hat(j) (the deltas up to column j sum to the held key),
-    inside it q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device, from
-    the inputs and the delta mask (itself compared bit for bit with the oracle above).  Tolerance as for the oracle.
+    inside it q . k_j; Eq. 1 on top.  Evaluated head by head with library matrix products in fp64 on the device
+    (tests/dense_form.py, pinned to the oracle on the CPU).  The reference keys and the delta mask are worked out from
+    the inputs alone (Eq. 2-3 written out with tensor operations); the masks and nnz that the library returns, in
+    either score mode, must equal them bit for bit, and two units of them are also held against the oracle's scan.
+    Tolerance as for the oracle.
     Also for the prompt fed in four pieces through the chunked entry point, as `bench.py --chunks 4` times it, and
     at the two ends of the sparsity sweep (every delta kept: the longest entry lists; 80 % zeroed with bursts)."""
+    import dense_form as df
     w = wl.c5(0.0, 0.05) if how == "theta 0" else wl.c5(0.80, 0.20) if how.startswith("80") else wl.C5
     x = _inputs(w)
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
     theta, n, d, W = wl.theta_for(w), w.seq_len, w.head_dim, w.window
-    g = w.n_q_heads // w.n_kv_heads
-    rows = torch.arange(n, device="cuda")
-    if how in ("one call", "theta 0") or how.startswith("80"):
-        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode) for mode in MODES]
-        inside = (rows[:, None] // W == rows[None, :] // W)
-    elif how == "sliding window":
-        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=da.DA_WINDOW_SLIDING)
-                for mode in MODES]
-        inside = (rows[:, None] - rows[None, :] < W)
-    else:
+    sliding = how == "sliding window"
+    if how == "four pieces onto a cache":
         outs = []
         for mode in MODES:
             cache = da.Cache(w.batch, w.n_q_heads, w.n_kv_heads, d, n, W, theta, torch.bfloat16)
@@ -225,27 +221,22 @@ def test_c5_every_output_element_against_the_dense_form(how):
                                                   Kd[:, :, a:a + n // 4].contiguous(),
                                                   Vd[:, :, a:a + n // 4].contiguous(), theta, W, score_mode=mode)
                      for a in range(0, n, n // 4)]
-            outs.append(tuple(torch.cat([p[k] for p in parts], dim=2) for k in range(2)) + (None,))
+            outs.append(tuple(torch.cat([p[k] for p in parts], dim=2) for k in range(2)) + (cache.nnz().clone(),))
             cache.close()
-        inside = (rows[:, None] // W == rows[None, :] // W)
+    else:
+        outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode,
+                                      window_mode=da.DA_WINDOW_SLIDING if sliding else da.DA_WINDOW_BLOCK)
+                for mode in MODES]
     torch.cuda.synchronize()
-    bits = outs[0][1]
-    sh = torch.arange(32, device="cuda", dtype=torch.int32)
-    mask = ((bits.unsqueeze(-1) >> sh) & 1).reshape(w.batch, w.n_kv_heads, n, d).bool()
-    causal = rows[None, :] <= rows[:, None]
-    worst = 0.0
-    for b in range(w.batch):
-        for hk in range(w.n_kv_heads):
-            K, V = Kd[b, hk].double(), Vd[b, hk].double()
-            last = torch.where(mask[b, hk], rows[:, None], torch.zeros_like(rows[:, None])).cummax(dim=0).values
-            Khat = torch.gather(K, 0, last)                  # the key row each channel last fired at
-            for h in range(hk * g, (hk + 1) * g):
-                Q = Qd[b, h].double()
-                S = torch.where(inside, Q @ K.T, Q @ Khat.T) / d ** 0.5
-                S = S.masked_fill(~causal, float("-inf"))
-                ref = torch.softmax(S, dim=-1) @ V
-                for O, _, _ in outs:
-                    worst = max(worst, (O[b, h].double() - ref).abs().max().item())
+    khat, mask = df.reference_keys(Kd, theta)                # from the inputs, not from the library's output
+    for b, hk in ((0, 0), (w.batch - 1, w.n_kv_heads - 1)):
+        m, _, kh, knife = orc.delta_scan(x["K"][b, hk], theta)
+        assert knife == 0
+        assert (mask[b, hk].cpu().numpy() == m.astype(bool)).all() and (khat[b, hk].cpu().numpy() == kh).all()
+    for O, bits, nnz in outs:
+        assert (df.unpack_bits(bits, d) == mask).all()
+        assert (nnz == mask.sum(dim=(2, 3))).all()
+    worst = df.prefill_worst_error(Qd, Kd, Vd, khat, W, sliding, [o[0] for o in outs])
     assert worst <= 2e-2, worst
 
 
@@ -254,6 +245,7 @@ def test_c5_every_output_element_against_the_dense_form(how):
 def test_generic_kernel_every_output_element_against_the_dense_form(dtype, d, n, W):
     """The vector-ALU kernel (fp32 inputs; head sizes other than 64 / 128) at sizes of a few thousand rows, every
     output element of both score modes and both window modes against the same closed form in fp64."""
+    import dense_form as df
     B, Hq, Hkv, theta = 2, 6, 2, 0.12
     Q, K, V = rand_walk(71, B, Hq, n, d, dtype), rand_walk(72, B, Hkv, n, d, dtype), rand_walk(73, B, Hkv, n, d, dtype, clip=3.5)
     Qd, Kd, Vd = to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype)
@@ -263,9 +255,11 @@ def test_generic_kernel_every_output_element_against_the_dense_form(dtype, d, n,
     for window_mode in (da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING):
         outs = [da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode, window_mode=window_mode) for mode in MODES]
         torch.cuda.synchronize()
-        mask = ((outs[0][1].unsqueeze(-1) >> sh) & 1).reshape(B, Hkv, n, d).bool()
-        assert (unpack_mask(outs[0][1], d) == np.stack([[orc.delta_scan(K[b, h], theta)[0] for h in range(Hkv)]
-                                                       for b in range(B)])).all()
+        _, mask = df.reference_keys(Kd, theta)               # from the inputs; the library's masks must equal it
+        for _, bits, _ in outs:
+            assert (df.unpack_bits(bits, d) == mask).all()
+        assert (mask.cpu().numpy() == np.stack([[orc.delta_scan(K[b, h], theta)[0] for h in range(Hkv)]
+                                                for b in range(B)]).astype(bool)).all()
         inside = (rows[:, None] - rows[None, :] < W) if window_mode == da.DA_WINDOW_SLIDING \
             else (rows[:, None] // W == rows[None, :] // W)
         for b in range(B):
@@ -316,8 +310,9 @@ def test_random_mid_size_shapes_against_the_dense_form(seed):
                                                 (da.DA_WINDOW_BLOCK, 8), (da.DA_WINDOW_SLIDING, 5)])
 def test_64k_tokens_every_output_element_against_the_dense_form(window_mode, pieces):
     """The 65536-token prompt of the test below, every output element of both score modes against the same closed
-    form, 2048 query rows at a time (the delta mask is compared with the oracle's below) - in one call, and fed in
-    equal pieces through the chunked entry point (the last pieces continue a cache of more than 50 000 rows)."""
+    form, 2048 query rows at a time (reference keys and mask from the inputs; the library's masks must equal them, and
+    they equal the oracle's scan) - in one call, and fed in equal pieces through the chunked entry point (the last
+    pieces continue a cache of more than 50 000 rows)."""
     w = wl.Workload("L64K", 1, 4, 1, 128, 65536, 512, "bf16", seed=64, theta=0.11)
     x = _inputs(w)
     Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
@@ -336,24 +331,13 @@ def test_64k_tokens_every_output_element_against_the_dense_form(window_mode, pie
             outs.append(tuple(torch.cat([p[k] for p in parts], dim=2) for k in range(2)) + (None,))
             cache.close()
     torch.cuda.synchronize()
-    sh = torch.arange(32, device="cuda", dtype=torch.int32)
-    mask = ((outs[0][1].unsqueeze(-1) >> sh) & 1).reshape(n, d).bool()
-    rows = torch.arange(n, device="cuda")
-    K, V = Kd[0, 0].double(), Vd[0, 0].double()
-    last = torch.where(mask, rows[:, None], torch.zeros_like(rows[:, None])).cummax(dim=0).values
-    Khat = torch.gather(K, 0, last)
-    worst = 0.0
-    for r0 in range(0, n, 2048):
-        i = rows[r0:r0 + 2048, None]
-        j = rows[None, :r0 + 2048]
-        inside = (i - j < W) if window_mode == da.DA_WINDOW_SLIDING else (i // W == j // W)
-        for h in range(w.n_q_heads):
-            Q = Qd[0, h, r0:r0 + 2048].double()
-            S = torch.where(inside, Q @ K[:r0 + 2048].T, Q @ Khat[:r0 + 2048].T) / d ** 0.5
-            S = S.masked_fill(j > i, float("-inf"))
-            ref = torch.softmax(S, dim=-1) @ V[:r0 + 2048]
-            for O, _, _ in outs:
-                worst = max(worst, (O[0, h, r0:r0 + 2048].double() - ref).abs().max().item())
+    import dense_form as df
+    khat, mask = df.reference_keys(Kd, w.theta)              # from the inputs; the library's masks must equal it
+    m, _, kh, knife = orc.delta_scan(x["K"][0, 0], w.theta)
+    assert knife == 0 and (mask[0, 0].cpu().numpy() == m.astype(bool)).all() and (khat[0, 0].cpu().numpy() == kh).all()
+    for _, bits, _ in outs:
+        assert (df.unpack_bits(bits, d) == mask).all()
+    worst = df.prefill_worst_error(Qd, Kd, Vd, khat, W, window_mode == da.DA_WINDOW_SLIDING, [o[0] for o in outs])
     assert worst <= 2e-2, worst
 
 
@@ -426,17 +410,61 @@ def test_delta_scan_every_reference_key(dtype, n, d):
             assert (ref_mask[b, hk].cpu().numpy() == m).all() and (ref_khat[b, hk].cpu().numpy() == kh).all()
 
 
-def test_c5_sweep_masks_and_sparsity():
-    """Delta masks over the compaction-density sweep (theta x jump rate): bit-exact, one unit each."""
-    for w in wl.C5_SWEEP:
-        K = wl.generate(w, ("K",), batch_ids=[1])["K"][:, 2:3]
-        theta = wl.theta_for(w)
-        maskg, nnzg, khat = da.delta_attn_delta_scan(to_dev(K, "bf16"), theta, want_khat=True)
-        m, _, Kh, knife = orc.delta_scan(K[0, 0], theta)
-        assert knife == 0
-        assert (unpack_mask(maskg, w.head_dim)[0, 0] == m).all()
-        assert int(nnzg[0, 0]) == int(m.sum())
-        assert (khat.double().cpu().numpy()[0, 0] == Kh).all()
+_sweep_inputs = {}
+
+
+@pytest.mark.parametrize("w", wl.C5_SWEEP, ids=lambda w: w.key())
+def test_c5_sweep_point_masks_sparsity_and_outputs(w):
+    """Config 5 is a family: threshold in {0, theta_40, theta_60, theta_80} x jump rate in {1, 5, 20} %.  At every one
+    of the 12 points, at full size and in both score modes: the delta masks and nnz of all 20 (batch, KV head) units
+    equal the oracle's Eq. 2-3 scan bit for bit, S_m equals the oracle's, and three row ranges (start, middle, end
+    of the prompt; the middle one straddles a window square's edge) of two query heads match the oracle's outputs
+    within the bf16 tolerance."""
+    key = (w.seed, w.p_jump)                                  # the inputs depend on the jump rate, not on the threshold
+    if key not in _sweep_inputs:
+        _sweep_inputs.clear()
+        _sweep_inputs[key] = wl.generate(w)
+    x = _sweep_inputs[key]
+    theta, d = wl.theta_for(w), w.head_dim
+    Qd, Kd, Vd = (to_dev(x[k], w.dtype) for k in "QKV")
+    heads, row_ranges = [2, 17], [(0, 24), (4084, 4108), (8176, 8192)]
+    refs = [orc.prefill(x["Q"], x["K"], x["V"], theta, w.window, rows=rows, q_heads=heads) for rows in row_ranges]
+    assert refs[0]["knife"] == 0
+    for mode in MODES:
+        Og, maskg, nnzg = da.delta_attn_prefill(Qd, Kd, Vd, theta, w.window, score_mode=mode)
+        torch.cuda.synchronize()
+        assert (unpack_mask(maskg, d) == refs[0]["mask"]).all()          # all 20 units, all 8192 rows
+        assert (nnzg.cpu().numpy() == refs[0]["nnz"]).all()
+        s_m, s_c = da.delta_attn_sparsity(nnzg, w.seq_len, d, w.window)
+        assert s_m == refs[0]["s_m"] and s_c == pytest.approx(refs[0]["s_c"], abs=1e-15)
+        if w.target_sparsity:
+            assert abs(s_m - w.target_sparsity) < 0.015
+        for rows, ref in zip(row_ranges, refs):
+            for h in heads:
+                check_output(Og[:, h, rows[0]:rows[1]], ref["O"][:, h], w.dtype)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("n,d,W,Hq,Hkv", [(700, 128, 64, 4, 1), (450, 64, 32, 4, 2)])
+def test_values_up_to_eight(mode, n, d, W, Hq, Hkv):
+    """Value rows that are not clipped to |v| < 4 (the other random cases clip them so that the bf16 rounding of the
+    output alone, half an ulp = 2^-9 relative to the next power of two below |o|, stays well inside 2e-2).  Here |v|
+    reaches 8 and outputs pass 4, where half an ulp is 2^-6 = 0.0156: the absolute 2e-2 is kept for |o| <= 4 and scaled
+    with the output's bf16 grid above it - per element, |error| <= 2e-2 * max(1, |o| / 4) - which is the same
+    5e-3 relative bound that 2e-2 is at |o| = 4."""
+    Q, K = rand_walk(101, 2, Hq, n, d), rand_walk(102, 2, Hkv, n, d)
+    V = rand_walk(103, 2, Hkv, n, d, step=0.5, clip=8.0)
+    assert np.abs(V).max() == 8.0
+    theta = 0.15
+    Og, maskg, nnzg = da.delta_attn_prefill(to_dev(Q, "bf16"), to_dev(K, "bf16"), to_dev(V, "bf16"), theta, W,
+                                            score_mode=mode)
+    torch.cuda.synchronize()
+    ref = orc.prefill(Q, K, V, theta, W)
+    assert (unpack_mask(maskg, d) == ref["mask"]).all() and (nnzg.cpu().numpy() == ref["nnz"]).all()
+    got = Og.double().cpu().numpy()
+    assert np.abs(ref["O"]).max() > 4.5                       # the case does reach past the clipped range
+    tol = 2e-2 * np.maximum(1.0, np.abs(ref["O"]) / 4.0)
+    assert (np.abs(got - ref["O"]) <= tol).all(), float((np.abs(got - ref["O"]) / tol).max())
 
 
 @pytest.mark.parametrize("n,d", [(5000, 96), (4097, 64), (130, 32), (63, 128), (1, 64)])
