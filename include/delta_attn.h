@@ -75,8 +75,9 @@ typedef struct da_cache da_cache;   /* decode-time cache (Sec. III-C), opaque */
 
 const char *delta_attn_version(void);
 const char *delta_attn_status_string(da_status s);
-/* Text of the last DA_ERR_HIP on the calling thread: "<stage>: <hip error name> (<description>)";
- * empty if none occurred.  Points to thread-local storage owned by the library. */
+/* Text of the last DA_ERR_HIP on the calling thread: "<stage>: <hip error name> (<description>)" (also set by
+ * delta_attn_prefill_noalloc when the params need more scratch than it has); empty if none occurred.  Points to
+ * thread-local storage owned by the library. */
 const char *delta_attn_last_error(void);
 
 /*
@@ -130,6 +131,23 @@ da_status delta_attn_delta_scan(const da_prefill_params *p, const void *K, uint3
 da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const void *K, const void *V,
                              void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * delta_attn_prefill for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and bit-identical
+ * outputs as delta_attn_prefill without a cache; the scratch is a buffer of DA_NOALLOC_SCRATCH_BYTES built into the
+ * library's device image (one copy per GPU, held until the process ends), so the call itself allocates nothing.
+ *   - Returns DA_ERR_WORKSPACE, with the two sizes in delta_attn_last_error(), when
+ *     delta_attn_prefill_workspace_bytes(p) exceeds DA_NOALLOC_SCRATCH_BYTES (nothing has been enqueued then).
+ *   - Every call on a GPU uses that GPU's one buffer: two calls whose kernels overlap in time on the same GPU (two
+ *     streams, two threads) race.  Calls on one stream, or ordered by events, are safe; the buffer keeps the previous
+ *     call's contents and no call depends on them.
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress) and raises the kernels' LDS
+ *     limits; make that call outside graph capture.
+ */
+#define DA_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+da_status delta_attn_prefill_noalloc(const da_prefill_params *p, const void *Q, const void *K, const void *V,
+                                     void *O, uint32_t *mask_bits, uint64_t *nnz, void *hip_stream);
 
 /*
  * Chunked prefill (Sec. III-C: the cache built so far is carried on): the m = p->seq_len rows of Q, K, V

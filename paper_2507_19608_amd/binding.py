@@ -20,6 +20,7 @@ EXPORTS = [
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
     "delta_attn_stage_timing_enable", "delta_attn_stage_timing_read", "delta_attn_window_from_gamma",
     "delta_attn_prefill_workspace_bytes", "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan", "delta_attn_prefill",
+    "delta_attn_prefill_noalloc",
     "delta_attn_prefill_append_workspace_bytes", "delta_attn_prefill_append", "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset",
     "delta_attn_cache_set_launch_plan", "delta_attn_cache_length", "delta_attn_cache_nnz", "delta_attn_cache_mask", "delta_attn_decode",
     "delta_attn_sparsity",
@@ -36,7 +37,7 @@ class PrefillParams(ctypes.Structure):
 class DeltaAttnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        detail = lib().delta_attn_last_error().decode() if status == 5 else ""
+        detail = lib().delta_attn_last_error().decode() if status in (3, 5) else ""
         super().__init__(f"{where}: {status_string(status)} (da_status {status}) {detail}")
 
 
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.delta_attn_delta_scan.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.delta_attn_prefill.restype = ctypes.c_int
         L.delta_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.delta_attn_prefill_noalloc.restype = ctypes.c_int
+        L.delta_attn_prefill_noalloc.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
         L.delta_attn_prefill_append_workspace_bytes.restype = ctypes.c_size_t
         L.delta_attn_prefill_append_workspace_bytes.argtypes = [pp, vp]
         L.delta_attn_prefill_append.restype = ctypes.c_int
@@ -282,6 +285,26 @@ def delta_attn_prefill(Q, K, V, theta: float, window: int, scale: float = 0.0, s
                                   workspace.data_ptr(), workspace.numel(), _stream())
     _check(st, "delta_attn_prefill")
     return O, mask, nnz
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def delta_attn_prefill_noalloc(Q, K, V, theta: float, window: int, out, scale: float = 0.0,
+                               score_mode: int = DA_SCORE_GATHER, window_mode: int = DA_WINDOW_BLOCK):
+    """delta_attn_prefill on the library's built-in scratch: the call allocates nothing, so `out` = (O, mask_bits int32
+    [B, Hkv, n, d/32], nnz int64 [B, Hkv]) must be passed in.  Returns `out`."""
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V")) + tuple(zip(out, ("O", "mask_bits", "nnz"))):
+        _dev(t, name)
+    if K.shape != V.shape or Q.shape[0] != K.shape[0] or Q.shape[2:] != K.shape[2:] or Q.dtype != K.dtype \
+            or K.dtype != V.dtype:
+        raise ValueError("Q/K/V shapes or dtypes disagree")
+    p = make_params(Q, K, window, theta, scale, score_mode, window_mode)
+    O, mask, nnz = out
+    st = lib().delta_attn_prefill_noalloc(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                          mask.data_ptr(), nnz.data_ptr(), _stream())
+    _check(st, "delta_attn_prefill_noalloc")
+    return out
 
 
 def delta_attn_prefill_append(cache: Cache, Q, K, V, theta: float, window: int, scale: float = 0.0,

@@ -1,5 +1,6 @@
 // C ABI of the hybrid delta attention library: argument checks, workspace carving, launches.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -64,6 +65,35 @@ inline float score_scale(float scale, int d) { return resolved_scale(scale, d); 
 
 da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const void *Q, const void *K, const void *V,
                           void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace, hipStream_t s);
+
+// ---- built-in scratch of delta_attn_prefill_noalloc.  One copy per GPU, held from the time the library is loaded
+// on that GPU until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress, not a
+// device address: its address on a device is looked up once per device, with that device current, and only that
+// pointer is ever handed to kernels.
+constexpr size_t kScratchBytes = DA_NOALLOC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+void *scratch_of_current_device() {
+    static std::mutex mu;
+    static void *ptr_of[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        set_last_error("delta_attn_prefill_noalloc: no current device, or a device ordinal above 63");
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_last_error("delta_attn_prefill_noalloc: hipGetSymbolAddress: %s", hipGetErrorName(e));
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr_of[dev] = ptr;
+    }
+    return ptr_of[dev];
+}
 
 // the kernels read the workspace with 16-byte loads and 64-byte entry chunks; regions are carved at multiples of 256
 inline bool ws_aligned(const void *ws) { return ((uintptr_t)ws & (kAlign - 1)) == 0; }
@@ -144,10 +174,29 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
     return prefill_checked(p, w, Q, K, V, O, mask_bits, nnz, cache, workspace, (hipStream_t)hip_stream);
 }
 
+da_status delta_attn_prefill_noalloc(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
+                                     uint32_t *mask_bits, uint64_t *nnz, void *hip_stream) {
+    da_status st = check_params(p);
+    if (st != DA_OK) return st;
+    if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
+    const WsLayout w = layout(p);
+    if (w.total > kScratchBytes) {
+        set_last_error("delta_attn_prefill_noalloc: these params need %zu bytes of scratch, the built-in buffer holds %zu",
+                       w.total, kScratchBytes);
+        return DA_ERR_WORKSPACE;
+    }
+    void *ws = scratch_of_current_device();
+    if (!ws) return DA_ERR_HIP;
+    // Nothing in the buffer has to start at zero: every region is written by the scan, compaction and re-order
+    // kernels before the attention kernel reads it (the nnz counters, which do, are the caller's and are cleared by
+    // a fill kernel on the stream).
+    return prefill_checked(p, w, Q, K, V, O, mask_bits, nnz, nullptr, ws, (hipStream_t)hip_stream);
+}
+
 }  // extern "C"
 
 namespace {
-// the body of delta_attn_prefill; arguments, workspace and cache have been checked
+// the body shared by the two prefill entry points; arguments, workspace and cache have been checked
 da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const void *Q, const void *K, const void *V,
                           void *O, uint32_t *mask_bits, uint64_t *nnz, da_cache *cache, void *workspace,
                           hipStream_t s) {

@@ -19,11 +19,11 @@ def declared_symbols():
 
 # the boundary: the calls the method needs (prefill, decode, delta scan, sparsity, Eq. 5 window, cache life cycle,
 # workspace sizes, status / error text) plus the documented extensions (chunked prefill, launch plan, stage timing for
-# benchmarks)
+# benchmarks, the entry point that allocates nothing)
 BOUNDARY = sorted([
     "delta_attn_version", "delta_attn_status_string", "delta_attn_last_error",
     "delta_attn_window_from_gamma", "delta_attn_sparsity",
-    "delta_attn_prefill_workspace_bytes", "delta_attn_prefill",
+    "delta_attn_prefill_workspace_bytes", "delta_attn_prefill", "delta_attn_prefill_noalloc",
     "delta_attn_delta_scan_workspace_bytes", "delta_attn_delta_scan",
     "delta_attn_prefill_append_workspace_bytes", "delta_attn_prefill_append",
     "delta_attn_cache_create", "delta_attn_cache_destroy", "delta_attn_cache_reset", "delta_attn_cache_length",
@@ -87,6 +87,17 @@ def test_workspace_size_and_argument_checks():
     assert st == 3
     st = L.delta_attn_prefill(ctypes.byref(p), 1, 1, 1, 1, 1, 1, None, 256 + 64, need, None)   # not 256-byte aligned
     assert st == 3
+    # the entry point that allocates nothing: same argument checks; a prompt beyond its built-in scratch is refused
+    # with both sizes in the error text, before anything is enqueued
+    assert L.delta_attn_prefill_noalloc(ctypes.byref(_params(n_q_heads=3)), 1, 1, 1, 1, 1, 1, None) == 1
+    assert L.delta_attn_prefill_noalloc(ctypes.byref(p), None, 1, 1, 1, 1, 1, None) == 1
+    big = _params(batch=4, n_q_heads=20, n_kv_heads=5, head_dim=128, seq_len=8192, window=512)
+    assert binding.delta_attn_prefill_workspace_bytes(big) > binding.NOALLOC_SCRATCH_BYTES
+    assert L.delta_attn_prefill_noalloc(ctypes.byref(big), 1, 1, 1, 1, 1, 1, None) == 3
+    text = L.delta_attn_last_error().decode()
+    assert str(binding.delta_attn_prefill_workspace_bytes(big)) in text and str(binding.NOALLOC_SCRATCH_BYTES) in text
+    header = open(os.path.join(ROOT, "include", "delta_attn.h")).read()
+    assert "#define DA_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)" in header and binding.NOALLOC_SCRATCH_BYTES == 32 << 20
     assert L.delta_attn_decode(None, 1, 1, 1, 1, None, None) == 1
     assert L.delta_attn_cache_length(None) == -1
     h = ctypes.c_void_p()

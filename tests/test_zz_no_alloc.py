@@ -1,0 +1,56 @@
+"""delta_attn_prefill_noalloc (the entry point for callers that cannot allocate: its scratch is a buffer built into
+the library's device image) against delta_attn_prefill on the same inputs: same kernels, so masks, nnz and outputs
+must be bit-identical; one case is also held against the oracle.  Two calls in a row share the one buffer - the
+second, smaller prompt must not see anything of the first."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_19608_amd import binding as da
+from oracle import delta_oracle as orc
+from util import check_output, rand_walk, to_dev, unpack_mask
+
+pytestmark = pytest.mark.gpu
+
+
+def _outs(Q, K):
+    B, Hkv, n, d = K.shape
+    return (torch.empty_like(Q), torch.empty((B, Hkv, n, d // 32), dtype=torch.int32, device="cuda"),
+            torch.empty((B, Hkv), dtype=torch.int64, device="cuda"))
+
+
+@pytest.mark.parametrize("mode", [da.DA_SCORE_GATHER, da.DA_SCORE_REBASE])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 96)])
+def test_noalloc_equals_prefill_on_two_calls_in_a_row(mode, dtype, d):
+    theta = 0.15
+    shapes = [(2, 8, 2, 1500, 64), (1, 4, 1, 333, 16)]           # (B, Hq, Hkv, n, W): the second call is the smaller one
+    if dtype == "f32":
+        shapes = [(1, 4, 2, 400, 32), (1, 2, 1, 130, 8)]
+    for k, (B, Hq, Hkv, n, W) in enumerate(shapes):
+        Q, K, V = (rand_walk(200 + 10 * k + i, B, H, n, d, dtype, clip=c)
+                   for i, (H, c) in enumerate(((Hq, None), (Hkv, None), (Hkv, 3.5))))
+        Qd, Kd, Vd = (to_dev(x, dtype) for x in (Q, K, V))
+        want = da.delta_attn_prefill(Qd, Kd, Vd, theta, W, score_mode=mode)
+        out = _outs(Qd, Kd)
+        for t in out:
+            t.fill_(-1)
+        allocs = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
+        got = da.delta_attn_prefill_noalloc(Qd, Kd, Vd, theta, W, out, score_mode=mode)
+        # no allocation request reached torch's allocator during the call either (the binding marshals only)
+        assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == allocs
+        torch.cuda.synchronize()
+        for g, w_ in zip(got, want):
+            assert torch.equal(g, w_), (k, dtype, d)
+        if k == 1:                                               # and the shared result is the oracle's
+            ref = orc.prefill(Q, K, V, theta, W)
+            assert (unpack_mask(got[1], d) == ref["mask"]).all() and (got[2].cpu().numpy() == ref["nnz"]).all()
+            for h in range(Hq):
+                check_output(got[0][:, h], ref["O"][:, h], dtype)
+
+
+def test_noalloc_rejects_a_prompt_beyond_its_scratch():
+    Q = torch.zeros(4, 20, 8192, 128, dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros(4, 5, 8192, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(da.DeltaAttnError) as e:
+        da.delta_attn_prefill_noalloc(Q, K, K, 0.1, 512, _outs(Q, K))
+    assert e.value.status == 3 and str(da.NOALLOC_SCRATCH_BYTES) in str(e.value)
