@@ -19,7 +19,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, chunk_out, ents, counts, nch8, plan, vt, total;
+    size_t khat, chunk_out, ents, counts, nch8, plan, dense, vt, total;
 };
 
 da_status check_params(const da_prefill_params *p) {
@@ -55,6 +55,8 @@ WsLayout layout(const da_prefill_params *p) {
     off += align_up(units * (size_t)prefill_mfma_n_pad(p->seq_len));
     w.plan = off;
     off += align_up(units * (size_t)prefill_mfma_n_pad(p->seq_len) * 2);   // 8 waves x 8 bytes per block of 32 columns
+    w.dense = off;
+    off += align_up(units * (size_t)(prefill_mfma_n_pad(p->seq_len) / 32) * 4);
     w.vt = off;
     off += align_up(units * (size_t)p->head_dim * prefill_mfma_n_pad(p->seq_len) * 2);
     w.total = off;
@@ -215,8 +217,8 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
     if (p->score_mode == DA_SCORE_GATHER || cache) {
         stage_begin(kStageEmit, s);
-        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, ws + w.plan, units, p->seq_len,
-                            prefill_mfma_n_pad(p->seq_len), p->head_dim, s);
+        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, ws + w.plan, (uint32_t *)(ws + w.dense),
+                            units, p->seq_len, prefill_mfma_n_pad(p->seq_len), p->head_dim, s);
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
     }
@@ -243,6 +245,7 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     a.counts = counts;
     a.nch8 = nch8;
     a.plan = ws + w.plan;
+    a.dense = (const uint32_t *)(ws + w.dense);
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a))
@@ -263,7 +266,7 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
 
 // workspace of delta_attn_prefill_append: whole-sequence arrays of n_k = cached + new rows
 struct AppendLayout {
-    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, plan, vt, total;
+    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, plan, dense, vt, total;
 };
 
 AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
@@ -291,6 +294,8 @@ AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
     off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk));
     w.plan = off;
     off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk) * 2);
+    w.dense = off;
+    off += align_up(units * (size_t)(prefill_mfma_n_pad((int)nk) / 32) * 4);
     w.vt = off;
     off += align_up(units * d * (size_t)prefill_mfma_n_pad((int)nk) * 2);
     w.total = off;
@@ -365,8 +370,8 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     if (p->score_mode == DA_SCORE_GATHER) {
         stage_begin(kStageEmit, s);
         launch_emit_entries(p->dtype, ws + w.kfull, ws + w.hfull, (const uint32_t *)(ws + w.mfull), ws + w.ents,
-                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), ws + w.plan, units, nk,
-                            prefill_mfma_n_pad(nk), d, s);
+                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), ws + w.plan,
+                            (uint32_t *)(ws + w.dense), units, nk, prefill_mfma_n_pad(nk), d, s);
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
     }
@@ -393,6 +398,7 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.counts = (const uint32_t *)(ws + w.counts);
     a.nch8 = (const uint8_t *)(ws + w.nch8);
     a.plan = ws + w.plan;
+    a.dense = (const uint32_t *)(ws + w.dense);
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a))

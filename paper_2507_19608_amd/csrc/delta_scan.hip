@@ -281,18 +281,26 @@ __device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__
 // least one chunk.  The chunks of column j of a unit start at chunk (unit * n + j) * d / 8;
 // counts holds the unpadded length, nch8 (stride n_pad per unit) the number of chunks.
 // plan (may be NULL): which of the block's columns each of the 8 waves of the matrix-core prefill kernel takes in its
-// gather loop, and in which pairs.  The columns are ranked by chunk count (ties: lower index first), neighbours in
-// that order form the 16 pairs (so the two columns of a pair have nearly the same length), and wave w takes pairs w
-// and 15 - w (long with short).  A wave's 8 bytes: the four column indices (first pair, longer column first; second
-// pair), then their chunk counts; blocks that reach past row n get zero counts (that kernel only gathers in blocks
-// left of every row's window).  Which wave sums a column does not change the sum.
+// gather loop, and in which pairs.  Full columns - lists that fill all d / 8 chunks, i.e. more than d - 8 surviving
+// entries: the whole-vector jumps of the key stream, and the basis row - can be left out of the gather: the running
+// score of Eq. 4 is then re-based at such a column from the dense product q . k_hat(j), which the telescoped sum makes
+// exact, on the matrix cores.  That costs a block a fixed amount (one K_hat Q^T tile) and saves the gather of each
+// full column, so it is done in blocks with at least kRouteMin full columns (measured break-even: about three), and
+// only if every reference key of the block fits fp16, the tile's operand format.  Re-based columns get chunk count 0
+// in the plan and their bit set in the block's word of `dense` ([units][n_pad / 32]).  The other
+// columns are ranked by chunk count (ties: lower index first), neighbours in that order form the 16 pairs (so the two
+// columns of a pair have nearly the same length), and wave w takes pairs w and 15 - w (long with short).  A wave's 8
+// bytes: the four column indices (first pair, longer column first; second pair), then their chunk counts; blocks that
+// reach past row n get zero counts and no dense bits (that kernel only gathers in blocks left of every row's window).
+// Which wave sums a column does not change the sum.
 template <typename T>
 __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__ K, const T *__restrict__ Khat,
                                                            const uint32_t *__restrict__ mask_bits,
                                                            EntryChunk *__restrict__ ents, uint32_t *__restrict__ counts,
-                                                           uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan, int n,
-                                                           int n_pad, int d) {
+                                                           uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan,
+                                                           uint32_t *__restrict__ dense, int n, int n_pad, int d) {
     constexpr int kCols = 32, kPlanWaves = 8;                // columns per work group = the prefill kernel's key block
+    constexpr int kRouteMin = 4;
     __shared__ uint32_t blk_cnt[kCols];
     const int unit = blockIdx.y;
     const int lane = threadIdx.x & 63;
@@ -300,19 +308,31 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
                                                     blockIdx.x * kCols + 4 * k + (threadIdx.x >> 6), 4 * k + (threadIdx.x >> 6));
     if (!plan) return;
     __syncthreads();
-    if (threadIdx.x < kCols) {
-        const int c = threadIdx.x;
+    if (threadIdx.x < kWave) {                               // the first wave; its lanes 0 .. 31 own a column each
+        const int c = threadIdx.x & (kCols - 1);
         const bool whole = (blockIdx.x + 1) * kCols <= n;
-        const uint32_t mine = blk_cnt[c];
+        auto chunks_of = [&](int col) { return blk_cnt[col] & 0x7fffffffu; };
+        const uint64_t full_cols = __ballot(threadIdx.x < kCols && chunks_of(c) == (uint32_t)(d / kGroup));
+        const bool fits = whole && !__any((blk_cnt[c] >> 31) != 0u) && __popcll(full_cols) >= kRouteMin;
+        auto is_routed = [&](int col) { return fits && chunks_of(col) == (uint32_t)(d / kGroup); };
+        const bool routed = is_routed(c);
+        const uint64_t routed_cols = __ballot(routed && threadIdx.x < kCols);
+        const uint32_t mine = routed ? 0u : chunks_of(c);
         uint32_t rank = 0;
-        for (int o = 0; o < kCols; ++o) rank += (blk_cnt[o] > mine || (blk_cnt[o] == mine && o < c)) ? 1u : 0u;
+        for (int o = 0; o < kCols; ++o) {
+            const uint32_t other = is_routed(o) ? 0u : chunks_of(o);
+            rank += (other > mine || (other == mine && o < c)) ? 1u : 0u;
+        }
         if (!whole) rank = (uint32_t)c;
         const uint32_t pair = rank >> 1;
         const uint32_t wv = pair < (uint32_t)kPlanWaves ? pair : 15u - pair;
         const uint32_t slot = (pair < (uint32_t)kPlanWaves ? 0u : 2u) + (rank & 1u);
-        uint8_t *out = plan + (((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves + wv) * 8;
-        out[slot] = (uint8_t)c;
-        out[4 + slot] = whole ? (uint8_t)mine : (uint8_t)0;
+        if (threadIdx.x < kCols) {
+            uint8_t *out = plan + (((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves + wv) * 8;
+            out[slot] = (uint8_t)c;
+            out[4 + slot] = whole ? (uint8_t)mine : (uint8_t)0;
+        }
+        if (threadIdx.x == 0) dense[(size_t)unit * (n_pad / kCols) + blockIdx.x] = (uint32_t)routed_cols;
     }
 }
 
@@ -332,6 +352,7 @@ __device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__
     const uint32_t *Mp = mask_bits + row * wpr;
     EntryChunk *out = ents + row * (d / kGroup);
     uint32_t off = 0;
+    bool big = false;
     for (int c0 = 0; c0 < d; c0 += kWave) {
         const int c = c0 + lane;
         const bool act = c < d;
@@ -340,8 +361,12 @@ __device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__
         if (act) {
             bit = (Mp[c >> 5] >> (c & 31)) & 1u;
             const float k = load_f32(Kp, c);
-            delta = (j == 0) ? k : k - load_f32(Hprev, c);
+            const float held = (j == 0) ? 0.f : load_f32(Hprev, c);
+            delta = k - held;                                  // (row 0: the basis, delta = k)
+            const float now = (bit || j == 0) ? k : held;      // reference key after this row
+            big = big || !(fabsf(now) < 32768.f);
         }
+        big = __any(big);
         const uint64_t b = __ballot(bit);
         if (bit) {
             const uint32_t slot = off + lanes_below(b);
@@ -360,7 +385,9 @@ __device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__
     if (lane == 0) {
         counts[row] = off;
         nch8[(size_t)unit * n_pad + j] = (uint8_t)(padded / kGroup);
-        blk_cnt[slot_in_block] = padded / kGroup;
+        // bit 31: some reference key of this row is too large for (or not a number in) fp16, the format in which the
+        // matrix-core prefill kernel re-bases a column; such a column is gathered like any other
+        blk_cnt[slot_in_block] = (padded / kGroup) | (big ? 0x80000000u : 0u);
     }
 }
 
@@ -410,14 +437,16 @@ void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits
 }
 
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, uint8_t *nch8, void *plan, int units, int n, int n_pad, int d, hipStream_t s) {
+                         uint32_t *counts, uint8_t *nch8, void *plan, uint32_t *dense, int units, int n, int n_pad,
+                         int d, hipStream_t s) {
     dim3 grid(n_pad / 32, units), block(256);
     if (dtype == 0)
         hipLaunchKernelGGL(emit_entries_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)Khat,
-                           mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, n, n_pad, d);
+                           mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, dense, n, n_pad, d);
     else
         hipLaunchKernelGGL(emit_entries_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K,
-                           (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, n, n_pad, d);
+                           (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, dense, n,
+                           n_pad, d);
 }
 
 }  // namespace da

@@ -40,15 +40,18 @@ struct PrefillArgs {
     const uint32_t *counts;
     const uint8_t *nch8;  // chunks per column, stride prefill_mfma_n_pad(n) per unit
     const void *plan;     // gather mode: the column plan written by launch_emit_entries
+    const uint32_t *dense;   // gather mode: per unit and block of 32 columns, the columns re-based instead of gathered
 };
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 int delta_scan_num_chunks(int n);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr);
-// plan: NULL, or room for units * n_pad * 2 bytes: the gather loop's column plan (see emit_entries_kernel)
+// plan: NULL, or room for units * n_pad * 2 bytes: the gather loop's column plan; dense (used with plan): room for
+// units * n_pad / 32 words (see emit_entries_kernel)
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
-                         uint32_t *counts, uint8_t *nch8, void *plan, int units, int n, int n_pad, int d, hipStream_t s);
+                         uint32_t *counts, uint8_t *nch8, void *plan, uint32_t *dense, int units, int n, int n_pad,
+                         int d, hipStream_t s);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if
 // the head_dim has no instantiation.
 bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);

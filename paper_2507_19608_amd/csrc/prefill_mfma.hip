@@ -10,7 +10,9 @@
 //                surviving (channel, delta) entry of its column.  The entry lists arrive as two-address LDS reads
 //                from a per-wave ring; q comes from a transposed fp16 copy of the Q tile in LDS (one 16-byte read
 //                feeds 8 multiply-adds).  The per-column updates u are exchanged through LDS; the owner of a score
-//                row adds them up in column order (its running Eq. 4 score).
+//                row adds them up in column order (its running Eq. 4 score).  In blocks where the compaction kernel
+//                has marked full columns for re-basing, the score at such a column is taken from a K_hat Q^T tile
+//                on the matrix cores instead (Eq. 4 telescoped) and the running score continues from it.
 //   near blocks  (some row has the column inside its window): exact scores K Q^T on the matrix cores;
 //                where a tile straddles window squares, the not-yet-exact entries come from K_hat Q^T
 //                (Eq. 4 telescoped: sum of the deltas up to column j is the held key k_hat(j)).
@@ -48,6 +50,7 @@ struct MfmaArgs {
     bf16_t *__restrict__ O;
     const EntryChunk *__restrict__ ents;
     const uint8_t *__restrict__ plan;   // per unit and block of kTB columns: kWaves x 8 bytes (emit_entries_kernel)
+    const uint32_t *__restrict__ dense; // per unit and block: bit c set = column c is re-based, not gathered
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
@@ -109,6 +112,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const bf16_t *Vtp = a.Vt + (size_t)unit * D * a.n_pad;
     const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
     const uint8_t *Pp = a.plan + (size_t)unit * (a.n_pad / kTB) * (kWaves * 8);
+    const uint32_t *Dp = a.dense + (size_t)unit * (a.n_pad / kTB);
 
     // score row sr = hh * RT + r  ->  query row i0 + r of head head0 + hh
     auto q_row_ptr = [&](int sr) -> const bf16_t * {
@@ -264,12 +268,15 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 
         // this wave's columns of a block: .x = their indices inside the block, .y = their chunk counts, one byte each;
         // bytes 0, 1 are the first pair (longer column first), bytes 2, 3 the second
-        auto pack_of = [&](int blk) -> u32x2 {
-            if (blk >= far_blocks) return u32x2{0u, 0u};
+        // .z = the block's re-based columns (the same word for every wave)
+        typedef __attribute__((ext_vector_type(3))) uint32_t u32x3;
+        auto pack_of = [&](int blk) -> u32x3 {
+            if (blk >= far_blocks) return u32x3{0u, 0u, 0u};
             const const_u32_ptr pp = (const_u32_ptr)(uintptr_t)(Pp + ((size_t)blk * kWaves + wave) * 8);
-            return u32x2{pp[0], pp[1]};
+            const const_u32_ptr dp = (const_u32_ptr)(uintptr_t)(Dp + blk);
+            return u32x3{pp[0], pp[1], dp[0]};
         };
-        auto g_issue = [&](u32x4 (&st)[4], int blk, u32x2 pk) {
+        auto g_issue = [&](u32x4 (&st)[4], int blk, u32x3 pk) {
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
                 const uint32_t nch = (pk[1] >> (8 * cc)) & 0xffu, col = (pk[0] >> (8 * cc)) & 0xffu;
@@ -278,7 +285,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                     st[cc] = *(const u32x4 *)((const char *)(Ep + (size_t)(blk * kTB + col) * (D / kGroup)) + lane * 16);
             }
         };
-        auto w_store = [&](const u32x4 (&st)[4], u32x2 pk) {
+        auto w_store = [&](const u32x4 (&st)[4], u32x3 pk) {
             uint32_t base = 0;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
@@ -302,11 +309,11 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                                 (uint32_t)(lane & 31) * 16u;
         const uint32_t zero_addr = ring_lds + kZeroChunk * 64u;
 
-        u32x2 pk_cur = pack_of(0), pk_nxt = pack_of(1);
+        u32x3 pk_cur = pack_of(0), pk_nxt = pack_of(1);
         u32x4 st[4];
         g_issue(st, 0, pk_cur);
 
-        auto gather_block = [&](u32x2 pk) {
+        auto gather_block = [&](u32x3 pk) {
             uint32_t first = 0;                                  // first ring chunk of the pair's longer column
 #pragma unroll
             for (int pair = 0; pair < 2; ++pair) {
@@ -320,6 +327,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 float u[8];
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] = 0.f;
+                if (steps > 0) {                                 // (a pair of re-based columns has nothing to gather)
                 Set S0, S1;
                 u32x4 chn[2];                                    // channel indices of the chunk whose q reads come next
                 auto rd_ch = [&](uint32_t a) {
@@ -348,6 +356,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                     rd_d(y, a_next);
                     a_next = chunk_addr(t + 2);
                     rd_ch(a_next);
+                    // keep the reads above ahead of the multiply-adds below: left alone, the compiler at times sinks
+                    // each q read to just before its use (one register quad, a full LDS wait per entry)
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const float dl = x.d[i >> 2][i & 3];
@@ -361,6 +372,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                     step(S1, S0, t + 1);
                 }
                 if (t < steps) step(S0, S1, t);
+                }
                 // both columns of the pair are done: hand their update vectors to the score-row owners
                 float *dst = ubuf + my_col * kRows + (lane & 31) * 8;
                 *(f32x4 *)dst = f32x4{u[0], u[1], u[2], u[3]};
@@ -368,48 +380,168 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             }
         };
 
-        // per block: gather -> (all waves) -> owners read the updates -> (all waves) -> softmax and PV
+        // K_hat Q^T tile of a block with re-based columns, on the matrix cores in fp16.  The K_hat rows of block b + 1 are
+        // fetched once per work group (one 16-byte piece per thread, requested after the gather of block b), turned into
+        // fp16 - exact: a bf16 value has 8 significant bits, and the compaction kernel routes a block's columns only if
+        // its reference keys are below 2^15 - and parked in one of two LDS buffers in operand order at the end of
+        // iteration b; the barrier of iteration b + 1 publishes them.  The query operand is read from the fp16 Q tile
+        // the gather uses (8 two-byte reads per k-step: the tile is stored channel-major), so the product comes out in
+        // the units of the running score and no operand is held in registers across the gather loop.
+        constexpr int kHTileBytes = D * 64;                      // 32 keys x D channels, fp16
+        constexpr int kHPieces = kHTileBytes / 16;
+        char *hbuf = lds_raw + kQtBytes + (size_t)kTB * kRows * 4 + (size_t)kWaves * kRingBytes;
+        const bool h_has_piece = kHPieces == 512 || tid < kHPieces;
+        const int h_ptid = tid & (kHPieces - 1);
+        const int h_pr = h_ptid & 31, h_pseg = h_ptid >> 5;      // key row of the block, 8-channel segment
+        const int h_slot = ((h_pseg >> 1) * 64 + (h_pseg & 1) * 32 + h_pr) * 16;
+        u32x4 hpiece;
+        auto load_h_piece = [&](int blk) {
+            hpiece = *(const u32x4 *)(Hp + (size_t)(blk * kTB + h_pr) * D + h_pseg * 8);
+        };
+        auto park_h_piece = [&](int blk) {
+            u32x4 f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float lo = __uint_as_float(hpiece[k] << 16), hi = __uint_as_float(hpiece[k] & 0xffff0000u);
+                f[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+            }
+            if (h_has_piece) *(u32x4 *)(hbuf + (blk & 1) * kHTileBytes + h_slot) = f;
+        };
+        typedef __attribute__((ext_vector_type(8))) _Float16 half8v;
+        auto rebase_tile = [&](int blk) -> f32x16 {
+            f32x16 t0, t1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t0[r] = t1[r] = 0.f;
+            const char *ha = hbuf + (blk & 1) * kHTileBytes + lane * 16;
+            const _Float16 *qb = qt + (size_t)(half * 8) * kRows + my_sr;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const half8v xa = __builtin_bit_cast(half8v, *(const u32x4 *)(ha + ks * 1024));
+                half8v xq;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xq[e] = qb[(size_t)(ks * 16 + e) * kRows];
+                if (ks & 1)
+                    t1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, xq, t1, 0, 0, 0);
+                else
+                    t0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, xq, t0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t0[r] += t1[r];
+            return t0;
+        };
+        // Scores of one block from its column updates uu (this lane's 16 columns, read from the exchange buffer), then
+        // softmax and P V.  Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1 (the
+        // matrix-core D layout).  A lane sums inside its own groups and gets the other half's group totals from its
+        // partner lane, so the running Eq. 4 score advances in column order.
+        auto scores_softmax_pv = [&](int blk, const float (&uu)[16], uint32_t dm, const u32x4 (&vreg)[2 * MT]) {
+            float s[16];
+            if (dm == 0) {
+                float w[16], t_own[4], t_oth[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float run = 0.f;
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        run += uu[4 * q + bb];
+                        w[4 * q + bb] = run;
+                    }
+                    t_own[q] = run;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
+                const float r0 = (float)r_run;
+                float rel = 0.f;                                 // sum of this block's updates so far
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float mine = r0 + (half ? rel + t_oth[q] : rel);
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = mine + w[4 * q + bb];
+                    rel += t_own[q] + t_oth[q];
+                }
+                r_run += (double)rel;
+            } else {
+                // Some columns of the block are re-based: their score is the dense product q . k_hat(j) (Eq. 4
+                // telescoped), taken from the K_hat Q^T tile; the running score continues from it.
+                const f32x16 tile = rebase_tile(blk);
+                const uint32_t mybits = half ? (dm >> 4) : dm;   // bit 8q + bb: this lane's column 4q + bb is re-based
+                float w[16], t_own[4], t_oth[4];
+                bool ab[16];                                     // w holds an absolute score (a re-base came before)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float run = 0.f;
+                    bool absolute = false;
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const bool rb = (mybits >> (8 * q + bb)) & 1u;
+                        run = rb ? tile[4 * q + bb] : run + uu[4 * q + bb];
+                        absolute = absolute || rb;
+                        w[4 * q + bb] = run;
+                        ab[4 * q + bb] = absolute;
+                    }
+                    t_own[q] = run;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
+                float base = (float)r_run;                       // running score before the block's next group pair
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool f0 = (dm >> (8 * q)) & 0xfu, f1 = (dm >> (8 * q + 4)) & 0xfu;   // wave-uniform
+                    const float g0 = half ? t_oth[q] : t_own[q], g1 = half ? t_own[q] : t_oth[q];
+                    const float after0 = f0 ? g0 : base + g0;    // ... after lane half 0's group of four columns
+                    const float after1 = f1 ? g1 : after0 + g1;  // ... after lane half 1's
+                    const float mine = half ? after0 : base;
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = ab[4 * q + bb] ? w[4 * q + bb] : mine + w[4 * q + bb];
+                    base = after1;
+                }
+                r_run = (double)base;
+            }
+            softmax_pv(s, far_scale, vreg);
+        };
+
+        // Per block b: every wave gathers its four columns (G), the updates cross the work group through the exchange
+        // buffer (two barriers), and every wave turns the updates of its 32 score rows into scores, softmax and P V (S).
+        // S of block b is run during iteration b + 1, by the first wave of each SIMD before its gather and by the
+        // second one after it, so that on every SIMD the matrix-core / exponential phase of one wave meets the LDS-bound
+        // gather of the other instead of both waves idling through the same phases together.
+        const bool late_s = wave >= kWaves / 2;                  // (waves w and w + 4 share a SIMD)
+        float uu[16];
+        uint32_t dm_prev = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) uu[r] = 0.f;
         for (int blk = 0; blk < far_blocks; ++blk) {
+            if (blk > 0 && !late_s) {
+                u32x4 vreg[2 * MT];
+                load_v(vreg, (blk - 1) * kTB);
+                scores_softmax_pv(blk - 1, uu, dm_prev, vreg);
+            }
             w_store(st, pk_cur);                                 // this block's chunks into the ring
-            const u32x2 pk = pk_cur;
+            const u32x3 pk = pk_cur;
             pk_cur = pk_nxt;
             g_issue(st, blk + 1, pk_cur);                        // next block's chunks into registers
             pk_nxt = pack_of(blk + 2);
+            const uint32_t dm = pk[2];                           // re-based columns of this block (wave-uniform)
+            if (dm) load_h_piece(blk);
             gather_block(pk);
-            u32x4 vreg[2 * MT];
-            load_v(vreg, blk * kTB);
+            if (blk > 0 && late_s) {
+                u32x4 vreg[2 * MT];
+                load_v(vreg, (blk - 1) * kTB);
+                scores_softmax_pv(blk - 1, uu, dm_prev, vreg);
+            }
+            if (dm) park_h_piece(blk);                           // (its buffer was last read by S of block b - 2)
             lds_barrier();                                       // u of this block complete
-            // Keys of the block in groups of 4: group 2q belongs to lane half 0, group 2q+1 to half 1
-            // (the matrix-core D layout).  A lane sums inside its own groups and gets the other
-            // half's group totals from its partner lane, so the running Eq. 4 score advances in
-            // column order.
             const float *up = ubuf + (4 * half) * kRows + my_sr;
-            float w[16], t_own[4], t_oth[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float run = 0.f;
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int bb = 0; bb < 4; ++bb) {
-                    run += up[(8 * q + bb) * kRows];
-                    w[4 * q + bb] = run;
-                }
-                t_own[q] = run;
-            }
+                for (int bb = 0; bb < 4; ++bb) uu[4 * q + bb] = up[(8 * q + bb) * kRows];
+            dm_prev = dm;
             lds_barrier();                                       // u buffer free for the next block
-#pragma unroll
-            for (int q = 0; q < 4; ++q) t_oth[q] = __shfl_xor(t_own[q], 32);
-            float s[16];
-            const float r0 = (float)r_run;
-            float rel = 0.f;                                     // sum of this block's updates so far
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float mine = r0 + (half ? rel + t_oth[q] : rel);
-#pragma unroll
-                for (int bb = 0; bb < 4; ++bb) s[4 * q + bb] = mine + w[4 * q + bb];
-                rel += t_own[q] + t_oth[q];
-            }
-            r_run += (double)rel;
-            softmax_pv(s, far_scale, vreg);
+        }
+        {
+            u32x4 vreg[2 * MT];
+            load_v(vreg, (far_blocks - 1) * kTB);
+            scores_softmax_pv(far_blocks - 1, uu, dm_prev, vreg);
         }
     }
 
@@ -602,6 +734,7 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.O = (bf16_t *)p.O;
     a.ents = (const EntryChunk *)p.ents;
     a.plan = (const uint8_t *)p.plan;
+    a.dense = p.dense;
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.n = p.n;
@@ -617,7 +750,8 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.tiles = (p.nq + a.RT - 1) / a.RT;
     a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
-    const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64);
+    const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64) +
+                           (size_t)2 * D * 64;                  // u exchange, entry rings, two fp16 K_hat tiles
     const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
     static std::atomic<uint64_t> lds_set[4];                     // per instantiation of launch_d, one bit per device

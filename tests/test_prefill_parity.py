@@ -631,3 +631,31 @@ def test_tiny_sequences(mode, n, d, W, dtype):
     Q, K, V = rand_walk(91, 1, 2, n, d, dtype), rand_walk(92, 1, 1, n, d, dtype), rand_walk(93, 1, 1, n, d, dtype, clip=3.5)
     run_case(Q, K, V, 0.2, W, dtype, mode)
     run_case(Q, K, V, 0.2, W, dtype, mode, window_mode=da.DA_WINDOW_SLIDING)
+
+
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+@pytest.mark.parametrize("d,Hq,Hkv,n,W,p_jump,theta", [(128, 4, 1, 900, 64, 0.3, 0.12), (64, 8, 2, 700, 32, 0.5, 0.2),
+                                                       (128, 2, 2, 600, 96, 0.15, 0.0), (64, 2, 1, 500, 32, 1.0, 0.3)])
+def test_rebased_full_columns(window_mode, d, Hq, Hkv, n, W, p_jump, theta):
+    """Key streams with many whole-vector jumps (and theta = 0, where every column is full): in blocks with several
+    full columns the gather kernel does not gather those columns but re-bases the running Eq. 4 score there from
+    q . k_hat(j) on the matrix cores - exact by the telescoped sum - so masks, nnz and outputs must still match the
+    oracle, which adds up Eq. 4 column by column."""
+    rng = np.random.default_rng(int(1000 * p_jump) + d)
+    Q, V = rand_walk(111, 2, Hq, n, d), rand_walk(113, 2, Hkv, n, d, clip=3.5)
+    K = rand_walk(112, 2, Hkv, n, d, step=0.05)
+    jump = rng.random((2, Hkv, n, 1)) < p_jump
+    K = wl.round_to_dtype(np.where(jump, rng.standard_normal((2, Hkv, n, d)), K), "bf16")
+    run_case(Q, K, V, theta, W, "bf16", da.DA_SCORE_GATHER, window_mode=window_mode)
+
+
+def test_rebase_is_skipped_for_keys_beyond_fp16():
+    """The re-base tile is taken in fp16; a block whose reference keys do not fit (|k| >= 2^15) keeps gathering its
+    full columns in binary32.  Keys of 5e4 in part of the prompt, every column full (theta = 0): results still match."""
+    n, d = 400, 64
+    Q, V = wl.round_to_dtype(rand_walk(121, 1, 2, n, d) * 2.0 ** -14, "bf16"), rand_walk(123, 1, 1, n, d, clip=3.5)
+    K = rand_walk(122, 1, 1, n, d)
+    K[:, :, 100:230] *= 5e4 / np.abs(K[:, :, 100:230]).max()
+    K = wl.round_to_dtype(K, "bf16")
+    assert np.abs(K).max() >= 2.0 ** 15
+    run_case(Q, K, V, 0.0, 32, "bf16", da.DA_SCORE_GATHER)
