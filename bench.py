@@ -287,7 +287,9 @@ def eq5_sweep(args, da, wl, torch, np):
         r2, _ = prefill_bench(args, da, wl, torch, np, "rebase", data=(x, dev), workload=w)
         rows.append({"n": n, "window": W, "s_m": r["config"]["s_m"], "s_c": r["config"]["s_c"],
                      "gather_ms_per_step": r["ms_per_step"], "gather_tokens_per_s": r["value"],
-                     "rebase_ms_per_step": r2["ms_per_step"], "rebase_tokens_per_s": r2["value"]})
+                     "gather_stage_ms": r["stage_ms"],
+                     "rebase_ms_per_step": r2["ms_per_step"], "rebase_tokens_per_s": r2["value"],
+                     "rebase_stage_ms": r2["stage_ms"]})
         sys.stderr.write(json.dumps(rows[-1]) + "\n")
         sys.stderr.flush()
         del x, dev

@@ -210,20 +210,35 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     const int units = p->batch * p->n_kv_heads;
 
     (void)hipGetLastError();   // do not inherit an earlier, unrelated error
-    stage_begin(kStageScan, s);
-    launch_delta_scan(p->dtype, K, khat, mask_bits, ws + w.chunk_out, nnz, units, p->seq_len, p->head_dim,
-                      p->theta, s);
-    stage_end(kStageScan, s);
-    if (!launch_ok("delta_scan")) return DA_ERR_HIP;
-    if (p->score_mode == DA_SCORE_GATHER || cache) {
-        stage_begin(kStageEmit, s);
-        launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, ws + w.plan, (uint32_t *)(ws + w.dense),
-                            units, p->seq_len, prefill_mfma_n_pad(p->seq_len), p->head_dim, s);
-        stage_end(kStageEmit, s);
-        if (!launch_ok("emit_entries")) return DA_ERR_HIP;
-    }
-
     PrefillArgs a;
+    a.dtype = p->dtype;
+    a.d = p->head_dim;
+    a.B = p->batch;
+    a.Hkv = p->n_kv_heads;
+    a.Hq = p->n_q_heads;
+    a.n = p->seq_len;
+    // Short prompts on the matrix-core kernel: one launch does everything (the scan, the compaction and the V
+    // re-order run inside the attention launch, once per work group); longer ones take a launch per stage.
+    const bool fused = prefill_mfma_supported(a) && (int64_t)p->seq_len * p->head_dim <= kFusedMaxElems;
+    if (!fused) {
+        stage_begin(kStageScan, s);
+        launch_delta_scan(p->dtype, K, khat, mask_bits, ws + w.chunk_out, nnz, units, p->seq_len, p->head_dim,
+                          p->theta, s);
+        stage_end(kStageScan, s);
+        if (!launch_ok("delta_scan")) return DA_ERR_HIP;
+        if (p->score_mode == DA_SCORE_GATHER || cache) {
+            stage_begin(kStageEmit, s);
+            launch_emit_entries(p->dtype, K, khat, mask_bits, ents, counts, nch8, ws + w.plan,
+                                (uint32_t *)(ws + w.dense), units, p->seq_len, prefill_mfma_n_pad(p->seq_len),
+                                p->head_dim, s);
+            stage_end(kStageEmit, s);
+            if (!launch_ok("emit_entries")) return DA_ERR_HIP;
+        }
+    }
+    a.fused = fused ? 1 : 0;
+    a.mask_bits = mask_bits;
+    a.nnz = nnz;
+    a.theta = p->theta;
     a.dtype = p->dtype;
     a.B = p->batch;
     a.Hq = p->n_q_heads;
@@ -399,6 +414,10 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.nch8 = (const uint8_t *)(ws + w.nch8);
     a.plan = ws + w.plan;
     a.dense = (const uint32_t *)(ws + w.dense);
+    a.fused = 0;
+    a.mask_bits = nullptr;
+    a.nnz = nullptr;
+    a.theta = p->theta;
     stage_begin(kStageAttn, s);
     bool launched = true;
     if (prefill_mfma_supported(a))

@@ -28,6 +28,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
     return (bf16_t)(u >> 16);
 }
 
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
 __device__ __forceinline__ float load_f32(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void store_from_f32(float *p, size_t i, float v) { p[i] = v; }

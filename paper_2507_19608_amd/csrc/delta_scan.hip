@@ -2,6 +2,7 @@
 // compaction of the surviving entries per key column.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "scan_device.hpp"
 
 #include <stdarg.h>
 #include <stdio.h>
@@ -130,78 +131,17 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
     const int lane = threadIdx.x;
     const int c = blockIdx.x * kWave + lane;
     const bool active = c < d;
-    const int wpr = d >> 5;
     const T *Kp = K + (size_t)unit * n * d;
     T *Hp = Khat + (size_t)unit * n * d;
-    uint32_t *Mp = mask_bits + (size_t)unit * n * wpr;
-    const bool writer = active && ((lane & 31) == 0);
-    const int word = c >> 5;
+    uint32_t *Mp = mask_bits + (size_t)unit * n * (d >> 5);
     const int t0 = chunk * L, t1 = min(n, t0 + L);
-
-    float held = 0.f;
+    float start = 0.f;
+    if (chunk > 0 && active)
+        start = kFinal ? load_f32(guess_out, ((size_t)unit * nchunks + chunk - 1) * d + c)
+                       : load_f32(Kp, (size_t)(t0 - 1) * d + c);
     unsigned long long cnt = 0;
-    int t = t0;
-    if (chunk == 0 && init) {   // the rows continue a sequence: its reference key is the incoming state
-        if (active) held = load_f32(init, (size_t)unit * d + c);
-    } else if (chunk == 0) {   // row 0 is the basis: kept whole
-        if (active) held = load_f32(Kp, c);
-        if (kFinal) {
-            if (active) Hp[c] = Kp[c];
-            if (writer) Mp[word] = 0xffffffffu;
-            cnt = __popcll(__ballot(active));
-        }
-        t = 1;
-    } else if (active) {
-        held = kFinal ? load_f32(guess_out, ((size_t)unit * nchunks + chunk - 1) * d + c)
-                      : load_f32(Kp, (size_t)(t0 - 1) * d + c);
-    }
-    // Rows in batches of U; two register sets alternate, the next batch is requested before the current one is
-    // worked on (loads past the chunk's end are clamped to its last row and never used), so that a batch's memory
-    // latency is hidden behind the previous batch's arithmetic instead of being paid once per batch.
-    constexpr int U = 16;
-    const int cs = active ? c : 0;
-    auto load_batch = [&](float (&k)[U], int tb) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) k[u] = load_f32(Kp, (size_t)min(tb + u, t1 - 1) * d + cs);
-    };
-    auto work_batch = [&](const float (&k)[U], int tb) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float diff = k[u] - held;                  // Eq. 2 condition in binary32
-            const bool fire = active && (fabsf(diff) > theta);
-            held = fire ? k[u] : held;                        // Eq. 3
-            if (kFinal) {
-                const uint64_t b = __ballot(fire);
-                if (writer) Mp[(size_t)(tb + u) * wpr + word] = (uint32_t)(b >> (lane & 32));
-                if (active) store_from_f32(Hp, (size_t)(tb + u) * d + c, held);
-                cnt += __popcll(b);
-            }
-        }
-    };
-    if (t + U <= t1) {
-        float ka[U], kb[U];
-        load_batch(ka, t);
-        while (t + U <= t1) {
-            load_batch(kb, t + U);
-            work_batch(ka, t);
-            t += U;
-            if (t + U > t1) break;
-            load_batch(ka, t + U);
-            work_batch(kb, t);
-            t += U;
-        }
-    }
-    for (; t < t1; ++t) {
-        const float k = active ? load_f32(Kp, (size_t)t * d + c) : 0.f;
-        const bool fire = active && (fabsf(k - held) > theta);
-        held = fire ? k : held;
-        if (kFinal) {
-            const uint64_t b = __ballot(fire);
-            if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(b >> (lane & 32));
-            if (active) store_from_f32(Hp, (size_t)t * d + c, held);
-            cnt += __popcll(b);
-        }
-    }
+    const float held = scan_rows<T, kFinal>(Kp, Hp, Mp, d, c, lane, t0, t1, chunk == 0,
+                                            init ? init + (size_t)unit * d : nullptr, start, theta, &cnt);
     if (active) store_from_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + c, held);
     if (kFinal && lane == 0) atomicAdd(nnz + unit, cnt);
 }
@@ -270,12 +210,6 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
     if (lane == 0 && adjust != 0) atomicAdd(nnz + unit, (unsigned long long)adjust);
 }
 
-template <typename T>
-__device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__restrict__ Khat,
-                                            const uint32_t *__restrict__ mask_bits, EntryChunk *__restrict__ ents,
-                                            uint32_t *__restrict__ counts, uint8_t *__restrict__ nch8, uint32_t *blk_cnt,
-                                            int n, int n_pad, int d, int unit, int lane, int j, int slot_in_block);
-
 // One work group per block of 32 key columns, a wave per column at a time: ballot + prefix count turn the mask row into
 // a dense list of (channel, delta) pairs in EntryChunk form, padded with (0, 0.0f) to whole chunks and to at
 // least one chunk.  The chunks of column j of a unit start at chunk (unit * n + j) * d / 8;
@@ -299,96 +233,20 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
                                                            EntryChunk *__restrict__ ents, uint32_t *__restrict__ counts,
                                                            uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan,
                                                            uint32_t *__restrict__ dense, int n, int n_pad, int d) {
-    constexpr int kCols = 32, kPlanWaves = 8;                // columns per work group = the prefill kernel's key block
-    constexpr int kRouteMin = 4;
+    constexpr int kCols = kPlanCols, kPlanWaves = kPlanWaveCount;
     __shared__ uint32_t blk_cnt[kCols];
     const int unit = blockIdx.y;
     const int lane = threadIdx.x & 63;
-    for (int k = 0; k < kCols / 4; ++k) emit_column(K, Khat, mask_bits, ents, counts, nch8, blk_cnt, n, n_pad, d, unit, lane,
-                                                    blockIdx.x * kCols + 4 * k + (threadIdx.x >> 6), 4 * k + (threadIdx.x >> 6));
+    const size_t row0 = (size_t)unit * n;
+    for (int k = 0; k < kCols / 4; ++k)
+        emit_column(K + row0 * d, Khat + row0 * d, mask_bits + row0 * (d >> 5), ents + row0 * (d / kGroup), counts + row0,
+                    nch8 + (size_t)unit * n_pad, blk_cnt, n, d, lane, blockIdx.x * kCols + 4 * k + (threadIdx.x >> 6),
+                    4 * k + (threadIdx.x >> 6));
     if (!plan) return;
     __syncthreads();
-    if (threadIdx.x < kWave) {                               // the first wave; its lanes 0 .. 31 own a column each
-        const int c = threadIdx.x & (kCols - 1);
-        const bool whole = (blockIdx.x + 1) * kCols <= n;
-        auto chunks_of = [&](int col) { return blk_cnt[col] & 0x7fffffffu; };
-        const uint64_t full_cols = __ballot(threadIdx.x < kCols && chunks_of(c) == (uint32_t)(d / kGroup));
-        const bool fits = whole && !__any((blk_cnt[c] >> 31) != 0u) && __popcll(full_cols) >= kRouteMin;
-        auto is_routed = [&](int col) { return fits && chunks_of(col) == (uint32_t)(d / kGroup); };
-        const bool routed = is_routed(c);
-        const uint64_t routed_cols = __ballot(routed && threadIdx.x < kCols);
-        const uint32_t mine = routed ? 0u : chunks_of(c);
-        uint32_t rank = 0;
-        for (int o = 0; o < kCols; ++o) {
-            const uint32_t other = is_routed(o) ? 0u : chunks_of(o);
-            rank += (other > mine || (other == mine && o < c)) ? 1u : 0u;
-        }
-        if (!whole) rank = (uint32_t)c;
-        const uint32_t pair = rank >> 1;
-        const uint32_t wv = pair < (uint32_t)kPlanWaves ? pair : 15u - pair;
-        const uint32_t slot = (pair < (uint32_t)kPlanWaves ? 0u : 2u) + (rank & 1u);
-        if (threadIdx.x < kCols) {
-            uint8_t *out = plan + (((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves + wv) * 8;
-            out[slot] = (uint8_t)c;
-            out[4 + slot] = whole ? (uint8_t)mine : (uint8_t)0;
-        }
-        if (threadIdx.x == 0) dense[(size_t)unit * (n_pad / kCols) + blockIdx.x] = (uint32_t)routed_cols;
-    }
-}
-
-template <typename T>
-__device__ __forceinline__ void emit_column(const T *__restrict__ K, const T *__restrict__ Khat,
-                                            const uint32_t *__restrict__ mask_bits, EntryChunk *__restrict__ ents,
-                                            uint32_t *__restrict__ counts, uint8_t *__restrict__ nch8, uint32_t *blk_cnt,
-                                            int n, int n_pad, int d, int unit, int lane, int j, int slot_in_block) {
-    if (j >= n) {
-        if (lane == 0) blk_cnt[slot_in_block] = 0u;
-        return;
-    }
-    const int wpr = d >> 5;
-    const size_t row = (size_t)unit * n + j;
-    const T *Kp = K + row * d;
-    const T *Hprev = Khat + (row - (j > 0 ? 1 : 0)) * d;
-    const uint32_t *Mp = mask_bits + row * wpr;
-    EntryChunk *out = ents + row * (d / kGroup);
-    uint32_t off = 0;
-    bool big = false;
-    for (int c0 = 0; c0 < d; c0 += kWave) {
-        const int c = c0 + lane;
-        const bool act = c < d;
-        bool bit = false;
-        float delta = 0.f;
-        if (act) {
-            bit = (Mp[c >> 5] >> (c & 31)) & 1u;
-            const float k = load_f32(Kp, c);
-            const float held = (j == 0) ? 0.f : load_f32(Hprev, c);
-            delta = k - held;                                  // (row 0: the basis, delta = k)
-            const float now = (bit || j == 0) ? k : held;      // reference key after this row
-            big = big || !(fabsf(now) < 32768.f);
-        }
-        big = __any(big);
-        const uint64_t b = __ballot(bit);
-        if (bit) {
-            const uint32_t slot = off + lanes_below(b);
-            out[slot / kGroup].chan[slot % kGroup] = (uint32_t)c;
-            out[slot / kGroup].delta[slot % kGroup] = delta;
-        }
-        off += __popcll(b);
-    }
-    uint32_t padded = (off + kGroup - 1) & ~(uint32_t)(kGroup - 1);
-    if (padded == 0) padded = kGroup;
-    if (off + lane < padded) {
-        const uint32_t slot = off + lane;
-        out[slot / kGroup].chan[slot % kGroup] = 0u;
-        out[slot / kGroup].delta[slot % kGroup] = 0.f;
-    }
-    if (lane == 0) {
-        counts[row] = off;
-        nch8[(size_t)unit * n_pad + j] = (uint8_t)(padded / kGroup);
-        // bit 31: some reference key of this row is too large for (or not a number in) fp16, the format in which the
-        // matrix-core prefill kernel re-bases a column; such a column is gathered like any other
-        blk_cnt[slot_in_block] = (padded / kGroup) | (big ? 0x80000000u : 0u);
-    }
+    if (threadIdx.x < kWave)                                  // the first wave; its lanes 0 .. 31 own a column each
+        plan_block(blk_cnt, plan + ((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves * 8,
+                   dense + (size_t)unit * (n_pad / kCols) + blockIdx.x, (blockIdx.x + 1) * kCols <= n, d, threadIdx.x);
 }
 
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n) {

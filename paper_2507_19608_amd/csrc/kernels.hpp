@@ -41,7 +41,17 @@ struct PrefillArgs {
     const uint8_t *nch8;  // chunks per column, stride prefill_mfma_n_pad(n) per unit
     const void *plan;     // gather mode: the column plan written by launch_emit_entries
     const uint32_t *dense;   // gather mode: per unit and block of 32 columns, the columns re-based instead of gathered
+    // fused short-prompt launch (matrix-core kernel only): the attention launch itself runs the delta scan, the
+    // compaction and the V re-order; then K_hat, ents, counts, nch8, plan, dense are scratch it fills first
+    int fused;
+    uint32_t *mask_bits;  // out (fused)
+    uint64_t *nnz;        // out (fused)
+    float theta;          // (fused)
 };
+
+// the fused launch is used for prompts of at most this many key elements per unit (seq_len * head_dim): their keys,
+// reference keys and mask words fit in LDS side by side
+constexpr int kFusedMaxElems = 32768;
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 int delta_scan_num_chunks(int n);

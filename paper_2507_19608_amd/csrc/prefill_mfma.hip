@@ -25,6 +25,7 @@
 // the matching key order.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "scan_device.hpp"
 
 namespace da {
 
@@ -56,6 +57,13 @@ struct MfmaArgs {
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     int xsplit;                         // > 0: XCD-aware order, every unit split this many ways (see the kernel)
     float scale_log2;
+    // fused short-prompt launch only: what the stand-alone scan, compaction and V re-order kernels take
+    const bf16_t *__restrict__ V;       // [unit][n][D] as the caller passed it
+    uint32_t *__restrict__ mask_bits;   // out
+    unsigned long long *__restrict__ nnz;   // out
+    uint32_t *__restrict__ counts;
+    uint8_t *__restrict__ nch8;
+    float theta;
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -66,11 +74,159 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 
+// V [unit][n][D] -> matrix-core operand order [unit][block of 32 keys][k-step ka][channel tile mt][lane][8]:
+// lane l of operand (ka, mt) holds channel 32 mt + l % 32 at keys 16 ka + 4 (l / 32) + {0..3} and
+// 16 ka + 8 + 4 (l / 32) + {0..3} of the block (the key order of the score tile's D registers).
+// Keys beyond n are zero.  One block of 32 keys by `nt` threads (this one is number `lt`) that share `tile`
+// ([kTB][D + 2] bf16); `sync` orders the tile's writes before its reads among those threads.
+template <int D, int NT, typename Sync>
+__device__ __forceinline__ void transpose_v_block(const bf16_t *__restrict__ Vp, u32x4 *__restrict__ Op, int t0, int n,
+                                                  bf16_t (*tile)[D + 2], int lt, Sync sync) {
+    constexpr int MT = D / 32;
+    constexpr int kIn = kTB * (D / 8) / NT;                      // 16-byte loads per thread, 8 channels of one row each
+    static_assert(kTB * (D / 8) % NT == 0 && (2 * MT * 64) % NT == 0, "thread count must divide the tile");
+    u32x4 v[kIn];
+#pragma unroll
+    for (int i = 0; i < kIn; ++i) {                              // every load issued before the first is used
+        const int idx = lt + i * NT, r = idx / (D / 8), c = (idx % (D / 8)) * 8;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (t0 + r < n) v[i] = *(const u32x4 *)(Vp + (size_t)(t0 + r) * D + c);
+    }
+#pragma unroll
+    for (int i = 0; i < kIn; ++i) {
+        const int idx = lt + i * NT, r = idx / (D / 8), c = (idx % (D / 8)) * 8;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tile[r][c + 2 * k] = (bf16_t)(v[i][k] & 0xffffu);
+            tile[r][c + 2 * k + 1] = (bf16_t)(v[i][k] >> 16);
+        }
+    }
+    sync();
+#pragma unroll
+    for (int i = 0; i < 2 * MT * 64 / NT; ++i) {
+        const int idx = lt + i * NT;
+        const int l = idx % 64, k = idx / 64, ka = k / MT, mt = k % MT;
+        const int ch = mt * 32 + (l & 31), hf = l >> 5;
+        u32x4 w;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const int e = 2 * e2;
+            const int key0 = 16 * ka + (e < 4 ? 4 * hf + e : 8 + 4 * hf + (e - 4));
+            w[e2] = (uint32_t)tile[key0][ch] | ((uint32_t)tile[key0 + 1][ch] << 16);
+        }
+        Op[idx] = w;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
+                                                          int n, int n_pad) {
+    __shared__ bf16_t tile[kTB][D + 2];
+    constexpr int MT = D / 32;
+    const int unit = blockIdx.y, blk = blockIdx.x;
+    transpose_v_block<D, 256>(V + (size_t)unit * n * D,
+                              (u32x4 *)(Vt + (size_t)unit * D * n_pad) + (size_t)blk * (2 * MT * 64), blk * kTB, n, tile,
+                              (int)threadIdx.x, [] { __syncthreads(); });
+}
+
+// What the stand-alone scan, compaction and V re-order launches do for a unit, done by one work group of the fused
+// short-prompt kernel for the key rows 0 .. need - 1 that its own query rows see (512 threads; `lds` is scratch of
+// fused_lds_bytes(D, need) bytes that nothing else uses yet).  The key rows are copied into LDS once; Eq. 2-3 run
+// there row by row (wave ballot = mask word), leaving the reference keys and mask words beside them in LDS; the
+// compaction (ballot + prefix count per column) reads all three from LDS and writes the entry lists and gather plans
+// to the workspace, from where the gather loop streams them into its rings as in the multi-launch path.
+// Every work group of a unit does this on its own and writes the same workspace arrays with the same values (only
+// final values are ever stored, and only for rows and blocks all of whose inputs the work group holds): a work group
+// reads only what it has itself written, whatever the others are doing.
+// `writer` (one work group per unit, one that needs every row) also stores the unit's nnz.
+__host__ __device__ constexpr size_t fused_lds_bytes(int d, int need) {
+    return 64 + (size_t)2 * need * d * 2 + (size_t)need * (d / 32) * 4 + (size_t)need * 4;
+}
+
+template <int D>
+__device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int need, int gather_blocks, bool writer,
+                                              char *lds) {
+    constexpr int CW = D / kWave;                               // waves that scan (64 channels each)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = a.n;
+    const bf16_t *Kp = a.K + (size_t)unit * n * D;
+    bf16_t *Hp = const_cast<bf16_t *>(a.Khat) + (size_t)unit * n * D;
+    uint32_t *Mp = a.mask_bits + (size_t)unit * n * (D / 32);
+    unsigned long long *cnt = (unsigned long long *)lds;        // [CW] surviving entries per scanning wave
+    bf16_t *Kl = (bf16_t *)(lds + 64);                          // [need][D] keys
+    bf16_t *Hl = Kl + (size_t)need * D;                         // [need][D] reference keys
+    uint32_t *Ml = (uint32_t *)(Hl + (size_t)need * D);         // [need][D / 32] mask words
+    // 1. the key rows into LDS
+    {
+        constexpr int kPer = kFusedMaxElems / 8 / 512;           // 16-byte pieces per thread at the largest prompt
+        u32x4 piece[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {                         // every load issued before the first is parked
+            const int idx = tid + i * 512;
+            piece[i] = ((const u32x4 *)Kp)[min(idx, need * (D / 8) - 1)];
+        }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int idx = tid + i * 512;
+            if (idx < need * (D / 8)) ((u32x4 *)Kl)[idx] = piece[i];
+        }
+    }
+    __syncthreads();
+    // 2. Eq. 2-3 over the rows, in order, by CW waves (64 channels each)
+    if (wave < CW) {
+        unsigned long long c = 0;
+        scan_rows<bf16_t, true>(Kl, Hl, Ml, D, wave * kWave + lane, lane, 0, need, true, (const bf16_t *)nullptr, 0.f,
+                                a.theta, &c);
+        if (lane == 0) cnt[wave] = c;
+    }
+    __syncthreads();
+    // 3. reference keys and mask words out to the workspace / the caller's mask array; nnz
+    for (int idx = tid; idx < need * (D / 8); idx += 512) ((u32x4 *)Hp)[idx] = ((const u32x4 *)Hl)[idx];
+    for (int idx = tid; idx < need * (D / 32); idx += 512) Mp[idx] = Ml[idx];
+    if (writer && tid == 0) {
+        unsigned long long t = 0;
+        for (int w = 0; w < CW; ++w) t += cnt[w];
+        a.nnz[unit] = t;
+    }
+    // 4. compaction of the key columns of the blocks this work group will gather (whole blocks left of every one of
+    //    its rows' windows, so all their rows are here), a column per wave at a time, then their gather plans
+    uint32_t *blk_cnt = (uint32_t *)(Ml + (size_t)need * (D / 32));   // [gather_blocks][32] chunk counts
+    EntryChunk *ents0 = const_cast<EntryChunk *>(a.ents) + (size_t)unit * n * (D / kGroup);
+    uint32_t *counts0 = a.counts + (size_t)unit * n;
+    uint8_t *nch0 = a.nch8 + (size_t)unit * a.n_pad;
+    uint8_t *plan = const_cast<uint8_t *>(a.plan) + (size_t)unit * (a.n_pad / kTB) * kWaves * 8;
+    uint32_t *dense = const_cast<uint32_t *>(a.dense) + (size_t)unit * (a.n_pad / kTB);
+    for (int j = wave; j < gather_blocks * kTB; j += kWaves)
+        emit_column((const bf16_t *)Kl, (const bf16_t *)Hl, (const uint32_t *)Ml, ents0, counts0, nch0, blk_cnt, need, D,
+                    lane, j, j);
+    lds_barrier();                                               // (the chunk counts; the lists go to global memory)
+    for (int blk = wave; blk < gather_blocks; blk += kWaves)
+        plan_block(blk_cnt + blk * kTB, plan + (size_t)blk * kWaves * 8, dense + blk, (blk + 1) * kTB <= n, D, lane);
+    __syncthreads();
+    // 5. V into matrix-core operand order, a block of 32 keys per wave at a time (the LDS copies above are done with)
+    {
+        typedef bf16_t (*tile_t)[D + 2];
+        tile_t tile = (tile_t)(lds + 64 + (size_t)wave * kTB * (D + 2) * sizeof(bf16_t));
+        const bf16_t *Vp = a.V + (size_t)unit * n * D;
+        u32x4 *Op = (u32x4 *)(const_cast<bf16_t *>(a.Vt) + (size_t)unit * D * a.n_pad);
+        for (int blk = wave; blk * kTB < need; blk += kWaves)
+            transpose_v_block<D, kWave>(Vp, Op + (size_t)blk * (2 * (D / 32) * 64), blk * kTB, n, tile, lane, [] {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            });
+    }
+    __threadfence();
+    __syncthreads();
+}
+
 // kGather: Eq. 4 as written for the far blocks (DA_SCORE_GATHER); otherwise every block goes through the matrix
 // cores (DA_SCORE_REBASE) and neither the fp16 Q tile nor the gather loop exists in the instantiation.
 // kAligned: the launcher has checked that every tile's rows share one window whose start is a multiple of the block
 // size; the K_hat tile of the near blocks, its loads and its branches then do not exist in the instantiation.
-template <int D, bool kGather, bool kAligned>
+// kFused: the work group first runs the delta scan, the compaction and the V re-order for its unit itself (short
+// prompts: one launch instead of seven; see fused_prepare), and reads its gather plans with vector loads.
+template <int D, bool kGather, bool kAligned, bool kFused = false>
 __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     extern __shared__ char lds_raw[];
     constexpr size_t kQtBytes = kGather ? (size_t)D * kRows * 2 : 0;
@@ -120,6 +276,12 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         const int i = min(i0 + r, n - 1);
         return a.Q + (((size_t)b * a.Hq + head0 + hh) * a.nq + (i - a.q_off)) * D;
     };
+
+    if constexpr (kFused) {
+        const int first_win = a.sliding ? max(i0 - W + 1, 0) : (i0 / W) * W;   // window start of the tile's first row
+        fused_prepare<D>(a, unit, min(n, i_last + 1), kGather ? first_win / kTB : 0, tile == a.tiles - 1 && hchunk == 0,
+                         lds_raw);
+    }
 
     float qmul = 1.f;
     if constexpr (kGather) {
@@ -272,9 +434,19 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         typedef __attribute__((ext_vector_type(3))) uint32_t u32x3;
         auto pack_of = [&](int blk) -> u32x3 {
             if (blk >= far_blocks) return u32x3{0u, 0u, 0u};
-            const const_u32_ptr pp = (const_u32_ptr)(uintptr_t)(Pp + ((size_t)blk * kWaves + wave) * 8);
-            const const_u32_ptr dp = (const_u32_ptr)(uintptr_t)(Dp + blk);
-            return u32x3{pp[0], pp[1], dp[0]};
+            if constexpr (kFused) {
+                // written earlier by this very work group with vector stores: read back through the same (vector)
+                // cache, which sees them; the scalar cache need not
+                const uint32_t *pp = (const uint32_t *)(Pp + ((size_t)blk * kWaves + wave) * 8);
+                const uint32_t x = __builtin_nontemporal_load(pp), y = __builtin_nontemporal_load(pp + 1);
+                const uint32_t z = __builtin_nontemporal_load(Dp + blk);
+                return u32x3{(uint32_t)__builtin_amdgcn_readfirstlane((int)x), (uint32_t)__builtin_amdgcn_readfirstlane((int)y),
+                             (uint32_t)__builtin_amdgcn_readfirstlane((int)z)};
+            } else {
+                const const_u32_ptr pp = (const_u32_ptr)(uintptr_t)(Pp + ((size_t)blk * kWaves + wave) * 8);
+                const const_u32_ptr dp = (const_u32_ptr)(uintptr_t)(Dp + blk);
+                return u32x3{pp[0], pp[1], dp[0]};
+            }
         };
         auto g_issue = [&](u32x4 (&st)[4], int blk, u32x3 pk) {
 #pragma unroll
@@ -684,49 +856,19 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     }
 }
 
-// V [unit][n][D] -> matrix-core operand order [unit][block of 32 keys][k-step ka][channel tile mt][lane][8]:
-// lane l of operand (ka, mt) holds channel 32 mt + l % 32 at keys 16 ka + 4 (l / 32) + {0..3} and
-// 16 ka + 8 + 4 (l / 32) + {0..3} of the block (the key order of the score tile's D registers).
-// Keys beyond n are zero.
-template <int D>
-__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
-                                                          int n, int n_pad) {
-    __shared__ bf16_t tile[kTB][D + 2];
-    constexpr int MT = D / 32;
-    const int unit = blockIdx.y, blk = blockIdx.x, t0 = blk * kTB, tid = threadIdx.x;
-    const bf16_t *Vp = V + (size_t)unit * n * D;
-    for (int idx = tid; idx < kTB * (D / 8); idx += 256) {       // 16-byte loads, 8 channels of one row each
-        const int r = idx / (D / 8), c = (idx % (D / 8)) * 8;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (t0 + r < n) v = *(const u32x4 *)(Vp + (size_t)(t0 + r) * D + c);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            tile[r][c + 2 * k] = (bf16_t)(v[k] & 0xffffu);
-            tile[r][c + 2 * k + 1] = (bf16_t)(v[k] >> 16);
-        }
-    }
-    __syncthreads();
-    u32x4 *Op = (u32x4 *)(Vt + (size_t)unit * D * n_pad) + (size_t)blk * (2 * MT * 64);
-    for (int idx = tid; idx < 2 * MT * 64; idx += 256) {
-        const int l = idx % 64, k = idx / 64, ka = k / MT, mt = k % MT;
-        const int ch = mt * 32 + (l & 31), hf = l >> 5;
-        u32x4 w;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const int e = 2 * e2;
-            const int key0 = 16 * ka + (e < 4 ? 4 * hf + e : 8 + 4 * hf + (e - 4));
-            w[e2] = (uint32_t)tile[key0][ch] | ((uint32_t)tile[key0 + 1][ch] << 16);
-        }
-        Op[idx] = w;
-    }
-}
-
 template <int D>
 static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const int units = p.B * p.Hkv;
-    hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(n_pad / kTB, units), dim3(256), 0, s,
-                       (const bf16_t *)p.V, (bf16_t *)vt, p.n, n_pad);
+    if (!p.fused)
+        hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(n_pad / kTB, units), dim3(256), 0, s,
+                           (const bf16_t *)p.V, (bf16_t *)vt, p.n, n_pad);
     MfmaArgs a;
+    a.V = (const bf16_t *)p.V;
+    a.mask_bits = p.mask_bits;
+    a.nnz = (unsigned long long *)p.nnz;
+    a.counts = const_cast<uint32_t *>(p.counts);
+    a.nch8 = const_cast<uint8_t *>(p.nch8);
+    a.theta = p.theta;
     a.Q = (const bf16_t *)p.Q;
     a.K = (const bf16_t *)p.K;
     a.Khat = (const bf16_t *)p.Khat;
@@ -754,7 +896,14 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
                            (size_t)2 * D * 64;                  // u exchange, entry rings, two fp16 K_hat tiles
     const size_t lds_near = (size_t)9 * D * 64;
     const size_t lds_gather = (size_t)D * kRows * 2 + (lds_far > lds_near ? lds_far : lds_near);
-    static std::atomic<uint64_t> lds_set[4];                     // per instantiation of launch_d, one bit per device
+    // fused_prepare's scratch: LDS copies of up to kFusedMaxElems key elements, or the per-wave V tiles
+    const size_t lds_prep = fused_lds_bytes(D, kFusedMaxElems / D) > (size_t)64 + kWaves * kTB * (D + 2) * 2
+                                ? fused_lds_bytes(D, kFusedMaxElems / D) : (size_t)64 + kWaves * kTB * (D + 2) * 2;
+    const size_t lds_fused_gather = lds_gather > lds_prep ? lds_gather : lds_prep;
+    const size_t lds_fused_rebase = lds_near > lds_prep ? lds_near : lds_prep;
+    static std::atomic<uint64_t> lds_set[6];                     // per instantiation of launch_d, one bit per device
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, false, true>, (int)lds_fused_gather, lds_set[4]);
+    ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, false, true>, (int)lds_fused_rebase, lds_set[5]);
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, false>, (int)lds_gather, lds_set[0]);
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, true>, (int)lds_gather, lds_set[1]);
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, false>, (int)lds_near, lds_set[2]);
@@ -771,7 +920,11 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     // of the block size
     const bool all_aligned = !p.sliding && p.W % kTB == 0 && p.W % a.RT == 0 && p.q_off % a.RT == 0;
     const dim3 grid((unsigned)blocks), block(512);
-    if (p.rebase && all_aligned)
+    if (p.fused && p.rebase)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, false, false, true>), grid, block, lds_fused_rebase, s, a);
+    else if (p.fused)
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, true, false, true>), grid, block, lds_fused_gather, s, a);
+    else if (p.rebase && all_aligned)
         hipLaunchKernelGGL((prefill_mfma_kernel<D, false, true>), grid, block, lds_near, s, a);
     else if (p.rebase)
         hipLaunchKernelGGL((prefill_mfma_kernel<D, false, false>), grid, block, lds_near, s, a);

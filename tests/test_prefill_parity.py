@@ -659,3 +659,17 @@ def test_rebase_is_skipped_for_keys_beyond_fp16():
     K = wl.round_to_dtype(K, "bf16")
     assert np.abs(K).max() >= 2.0 ** 15
     run_case(Q, K, V, 0.0, 32, "bf16", da.DA_SCORE_GATHER)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+@pytest.mark.parametrize("n,d", [(64, 128), (128, 128), (256, 128), (512, 128), (100, 64), (512, 64), (257, 128)])
+def test_short_prompts_with_the_window_of_eq5(mode, window_mode, n, d):
+    """The paper's own regime: prompts of tens to hundreds of tokens with the window of Eq. 5 (gamma = 0.05: W = 3 .. 25).
+    Prompts whose keys fit in LDS (n * head_dim <= 32768) take the fused launch - scan, compaction, V re-order and
+    attention in one kernel, every work group preparing its unit itself - the others a launch per stage; both must
+    match the oracle in masks, nnz, sparsity and every output element."""
+    W = da.delta_attn_window_from_gamma(n, 0.05, 512)
+    assert W == orc.window_from_gamma(n, 0.05, 512) and 3 <= W <= 25
+    Q, K, V = rand_walk(131, 2, 8, n, d), rand_walk(132, 2, 2, n, d), rand_walk(133, 2, 2, n, d, clip=3.5)
+    run_case(Q, K, V, 0.12, W, "bf16", mode, window_mode=window_mode)
