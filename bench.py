@@ -21,19 +21,40 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
-PEAK_VALU_F32_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
-# rate measured on this chip for the multiply-add of the prefill kernel's gather loop (fp16 x fp32 + fp32 in one
-# instruction, no packed-fp32 forms) at that kernel's occupancy of 2 waves per SIMD (delta_attn_rate_probe, kind 3)
-MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD = 71.3
+PEAK_VALU_F32_TFLOPS = 157.3    # published: 256 CU x 4 SIMD x 32 fp32 multiply-adds per cycle x 2 flop x 2.4 GHz
+# The prefill kernel's gather loop multiplies with v_fma_mix_f32 (fp16 x fp32 + fp32), which issues once per 4 cycles per
+# SIMD: 256 CU x 4 SIMD x 64 lanes / 4 cycles x 2 flop x 2.4 GHz (a register-only loop of that instruction measured
+# 63 - 71 TFLOP/s at the kernel's 2 waves per SIMD).  The published 157.3 counts two fp32 multiply-adds per lane and
+# 2 cycles (packed or dual-rate fp32), the plain single-rate figure is half of it.
+FMA_MIX_ISSUE_TFLOPS = 78.6
 
-# HBM-side bytes per launch of the dominant kernel (fetch + write), measured once with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE on this command and scaled by a 1 GiB copy (profiles/prefill_C5_and_decode_C4_hbm_traffic.md).
-# Counters cannot be read from inside this process, so other workloads report null.
-MEASURED_TRAFFIC_BYTES = {
-    ("C5/p05/s60", "gather"): (761.5 + 160.0) * 2 ** 20,
-    ("C5/p05/s60", "rebase"): (451.2 + 160.0) * 2 ** 20,
-    ("C4/p05/s57", "decode"): (111.16 + 0.71) * 2 ** 20,
-}
+PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "prefill_C5_and_decode_C4_hbm_traffic.md")
+
+
+def measured_traffic(path=PROFILE_TRAFFIC):
+    """HBM-side bytes per launch of the dominant kernels (fetch + write), as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE and written down in the profile summary (its table, MiB per launch, already scaled by the copy
+    calibration), and the commit the counters were taken at.  Counters cannot be read from inside this process, so
+    the bench line quotes the summary; workloads it does not cover report null."""
+    rows, commit = {}, None
+    labels = {"prefill attention, gather mode": ("C5/p05/s60", "gather"),
+              "prefill attention, telescoped mode": ("C5/p05/s60", "rebase"),
+              "decode step kernel": ("C4/p05/s57", "decode")}
+    try:
+        text = open(path).read()
+    except OSError:
+        return rows, commit
+    for line in text.splitlines():
+        if line.startswith("Counters taken at commit"):
+            commit = line.split("`")[1]
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        for label, key in labels.items():
+            if len(cells) >= 4 and cells[0].startswith(label):
+                rows[key] = (float(cells[2]) + float(cells[3])) * 2 ** 20
+    return rows, commit
+
+
+MEASURED_TRAFFIC_BYTES, TRAFFIC_FROM_COMMIT = measured_traffic()
 
 
 def outside_rows(n, W, sliding=False):
@@ -117,6 +138,14 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     nnz_col = np.bitwise_count(mask).sum(axis=-1).astype(np.int64)   # [B, Hkv, n]
     rows_out = outside_rows(n, w.window, args.window_mode == "sliding")
     sparse_macs = float((nnz_col * rows_out[None, None, :]).sum()) * g
+    # of which in columns the gather kernel re-bases on the matrix cores instead of gathering: full columns (more than
+    # d - 8 surviving entries) of whole 32-column blocks that have at least four of them
+    nb = n // 32
+    full = (nnz_col[..., :nb * 32] > d - 8).reshape(B, Hkv, nb, 32)
+    routed = full & (full.sum(axis=-1, keepdims=True) >= 4)
+    rebased_macs = float((nnz_col[..., :nb * 32] * routed.reshape(B, Hkv, nb * 32) * rows_out[None, None, :nb * 32]).sum()) * g
+    if mode != da.DA_SCORE_GATHER or w.dtype != "bf16" or d not in (64, 128):
+        rebased_macs = 0.0
     outside_pairs = float(rows_out.sum()) * B * Hq
     causal_pairs = n * (n + 1) / 2.0 * B * Hq
     window_pairs = causal_pairs - outside_pairs
@@ -128,8 +157,10 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
         roof = {"bound": "alu", "achieved": alu_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_VALU_F32_TFLOPS,
                 "unit": "TFLOP/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
-        roof["measured_fma_rate_at_kernel_occupancy"] = MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD
-        roof["frac_of_measured_rate"] = roof["achieved"] / MEASURED_FMA_TFLOPS_AT_2_WAVES_PER_SIMD
+        roof["sparse_gmac_rebased_on_matrix_cores"] = rebased_macs / 1e9
+        roof["achieved_on_vector_alu"] = 2.0 * (sparse_macs - rebased_macs) / (attn_ms * 1e-3) / 1e12
+        roof["single_rate_issue_peak"] = FMA_MIX_ISSUE_TFLOPS
+        roof["frac_of_single_rate_issue_peak"] = roof["achieved"] / FMA_MIX_ISSUE_TFLOPS
     else:
         alu_flops = 0.0
         mfma_flops = 2.0 * (2.0 * causal_pairs) * d
@@ -141,6 +172,7 @@ def prefill_bench(args, da, wl, torch, np, mode_name, data=None, workload=None):
     roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "gather" if mode == da.DA_SCORE_GATHER else "rebase"))
                  if args.window_mode == "block" and pieces == 1 else None,
                  "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                 "traffic_from": f"profiles/{os.path.basename(PROFILE_TRAFFIC)} at commit {TRAFFIC_FROM_COMMIT}",
                  "kernel": "prefill attention", "kernel_ms": attn_ms,
                  "algorithmic_sparse_gmac": sparse_macs / 1e9, "row_weighted_density": sparse_macs / max(outside_pairs * d, 1),
                  "mfma_tflops": mfma_flops / (attn_ms * 1e-3) / 1e12,
@@ -248,6 +280,7 @@ def decode_bench(args, da, wl, torch, np):
                          "frac": bytes_step / (chunk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                          "traffic": MEASURED_TRAFFIC_BYTES.get((w.key(), "decode")),
                          "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                         "traffic_from": f"profiles/{os.path.basename(PROFILE_TRAFFIC)} at commit {TRAFFIC_FROM_COMMIT}",
                          "algorithmic_mb_per_step": bytes_step / 1e6}}
 
 
@@ -264,6 +297,7 @@ def c5_sweep(args, da, wl, torch, np):
                          "sparse_gmac": r["roofline"]["algorithmic_sparse_gmac"],
                          "gather_attn_ms": r["roofline"]["kernel_ms"], "gather_tokens_per_s": r["value"],
                          "gather_alu_tflops": r["roofline"]["achieved"],
+                         "gather_gmac_rebased_on_matrix_cores": r["roofline"]["sparse_gmac_rebased_on_matrix_cores"],
                          "rebase_attn_ms": r2["roofline"]["kernel_ms"], "rebase_tokens_per_s": r2["value"],
                          "rebase_mfma_frac": r2["roofline"]["frac"]})
             sys.stderr.write(json.dumps(rows[-1]) + "\n")
