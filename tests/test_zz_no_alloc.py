@@ -54,3 +54,29 @@ def test_noalloc_rejects_a_prompt_beyond_its_scratch():
     with pytest.raises(da.DeltaAttnError) as e:
         da.delta_attn_prefill_noalloc(Q, K, K, 0.1, 512, _outs(Q, K))
     assert e.value.status == 3 and str(da.NOALLOC_SCRATCH_BYTES) in str(e.value)
+
+
+@pytest.mark.parametrize("n,d", [(200, 64), (1500, 128)])
+def test_noalloc_replays_from_a_captured_graph(n, d):
+    """The callers it is for: captured into a HIP graph (after one eager call that did the one-time set-up), replayed
+    with eager work and synchronisations in between; every replay must reproduce delta_attn_prefill bit for bit.
+    200 tokens take the fused single launch, 1500 the launch-per-stage path (whose counters are cleared by a fill
+    kernel, not by a memset node)."""
+    B, Hq, Hkv, W, theta = 2, 4, 2, 32, 0.15
+    Qd, Kd, Vd = (to_dev(rand_walk(300 + i, B, H, n, d, clip=c), "bf16")
+                  for i, (H, c) in enumerate(((Hq, None), (Hkv, None), (Hkv, 3.5))))
+    want = da.delta_attn_prefill(Qd, Kd, Vd, theta, W)
+    out = _outs(Qd, Kd)
+    da.delta_attn_prefill_noalloc(Qd, Kd, Vd, theta, W, out)     # eager first call: symbol look-up, LDS limits
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        da.delta_attn_prefill_noalloc(Qd, Kd, Vd, theta, W, out)
+    for rep in range(3):
+        for t in out:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, w_ in zip(out, want):
+            assert torch.equal(g, w_), rep
