@@ -161,8 +161,16 @@ da_status delta_attn_prefill_noalloc(const da_prefill_params *p, const void *Q, 
  *             is empty: the exact scores against cached keys are taken from the cache's ring of raw keys;
  *             a decode_window above max_seq counts as max_seq),
  *             at most 32 query heads per KV head; otherwise DA_ERR_UNSUPPORTED
- *   workspace device scratch of at least delta_attn_prefill_append_workspace_bytes(p, cache), which
- *             depends on the cache length at the time of the call (0 if the arguments are invalid)
+ *   workspace device scratch of at least delta_attn_prefill_append_workspace_bytes(p, cache) (0 if the arguments
+ *             are invalid), 256-byte aligned; it grows with p->seq_len only
+ * The cache keeps the sequence so far as the plain arrays the prefill kernels read (keys, reference keys, values in
+ * two orders, mask rows, and in DA_SCORE_GATHER mode the entry lists and gather plans of all key columns), with
+ * max_seq rows of room: about 8 * head_dim + 4 * head_dim / 32 bytes per (KV head, row), 16 * head_dim + 8 in
+ * gather mode.  The first call on a cache allocates them (hipMalloc + hipMemset, released by
+ * delta_attn_cache_destroy; DA_ERR_HIP if that fails; make that call outside graph capture); a call that follows
+ * another such call, or delta_attn_cache_reset, then only adds its own rows.  After decode steps or a one-shot
+ * delta_attn_prefill into the cache the arrays are rebuilt from the cache by the next call, at a cost proportional to
+ * the cache length.
  */
 size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache);
 da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, const void *K, const void *V,

@@ -279,42 +279,57 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     return DA_OK;
 }
 
-// workspace of delta_attn_prefill_append: whole-sequence arrays of n_k = cached + new rows
+// workspace of delta_attn_prefill_append: what the scan of the new rows needs (the whole-sequence arrays live in the
+// cache, see da_prefix)
 struct AppendLayout {
-    size_t kfull, hfull, vfull, mfull, hnew, chunk_out, ents, counts, nch8, plan, dense, vt, total;
+    size_t hnew, chunk_out, total;
 };
 
-AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
+AppendLayout append_layout(const da_prefill_params *p) {
     const size_t units = (size_t)p->batch * p->n_kv_heads, d = p->head_dim, es = elt_size(p->dtype);
-    const size_t m = p->seq_len, nk = (size_t)cached + m;
+    const size_t m = p->seq_len;
     AppendLayout w;
     size_t off = 0;
-    w.kfull = off;
-    off += align_up(units * nk * d * es);
-    w.hfull = off;
-    off += align_up(units * nk * d * es);
-    w.vfull = off;
-    off += align_up(units * nk * d * es);
-    w.mfull = off;
-    off += align_up(units * nk * (d / 32) * 4);
     w.hnew = off;
     off += align_up(units * m * d * es);
     w.chunk_out = off;
     off += align_up(2 * units * (size_t)delta_scan_num_chunks((int)m) * d * es);
-    w.ents = off;
-    off += align_up(units * nk * d * 8);
-    w.counts = off;
-    off += align_up(units * nk * sizeof(uint32_t));
-    w.nch8 = off;
-    off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk));
-    w.plan = off;
-    off += align_up(units * (size_t)prefill_mfma_n_pad((int)nk) * 2);
-    w.dense = off;
-    off += align_up(units * (size_t)(prefill_mfma_n_pad((int)nk) / 32) * 4);
-    w.vt = off;
-    off += align_up(units * d * (size_t)prefill_mfma_n_pad((int)nk) * 2);
     w.total = off;
     return w;
+}
+
+// The cache's whole-sequence arrays (da_prefix), allocated on first use and zero-filled (rows nothing has written yet
+// must hold finite numbers: the kernels load whole tiles and discard what lies past the sequence).
+da_status ensure_prefix(da_cache *c, bool gather) {
+    if (!c->pf) {
+        c->pf = new (std::nothrow) da_prefix();
+        if (!c->pf) return DA_ERR_HIP;
+        memset(c->pf, 0, sizeof(*c->pf));
+    }
+    da_prefix *f = c->pf;
+    const size_t units = (size_t)c->B * c->Hkv, d = c->d, ld = c->max_seq, ld_pad = prefill_mfma_n_pad(c->max_seq);
+    bool ok = true;
+    auto room = [&](void **ptr, size_t bytes) {
+        if (!ok || *ptr) return;
+        ok = hipMalloc(ptr, bytes) == hipSuccess && hipMemset(*ptr, 0, bytes) == hipSuccess;
+    };
+    room(&f->k, units * ld * d * 2);
+    room(&f->h, units * ld * d * 2);
+    room(&f->v, units * ld * d * 2);
+    room((void **)&f->m, units * ld * (d / 32) * 4);
+    room(&f->vt, units * d * ld_pad * 2);
+    if (gather) {
+        room(&f->ents, units * ld * d * 8);
+        room((void **)&f->counts, units * ld * 4);
+        room((void **)&f->nch8, units * ld_pad);
+        room(&f->plan, units * ld_pad * 2);
+        room((void **)&f->dense, units * (ld_pad / 32) * 4);
+    }
+    if (!ok) {
+        (void)launch_ok("prefill_append: room for the cached sequence as plain arrays");   // records the error text
+        return DA_ERR_HIP;
+    }
+    return DA_OK;
 }
 
 da_status check_append(const da_prefill_params *p, const da_cache *c) {
@@ -339,7 +354,7 @@ extern "C" {
 
 size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache) {
     if (check_append(p, cache) != DA_OK) return 0;
-    return append_layout(p, cache->len).total;
+    return append_layout(p).total;
 }
 
 da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
@@ -349,19 +364,31 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     if (st != DA_OK) return st;
     if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     const int t0 = (int)cache->len, m = p->seq_len, nk = t0 + m, d = p->head_dim;
-    const AppendLayout w = append_layout(p, t0);
+    const AppendLayout w = append_layout(p);
     if (!workspace || workspace_bytes < w.total || !ws_aligned(workspace)) return DA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     const int units = p->batch * p->n_kv_heads;
     const size_t row = (size_t)d * 2, mrow = (size_t)(d / 32) * 4;
+    const bool gather = p->score_mode == DA_SCORE_GATHER;
     (void)hipGetLastError();
+    st = ensure_prefix(cache, gather);
+    if (st != DA_OK) return st;
+    da_prefix *f = cache->pf;
+    const int ld = cache->max_seq;
+    const int n_pad = prefill_mfma_n_pad(nk);
 
-    // 1. the cached rows as plain arrays; the new rows behind them
-    expand_cache_runs(cache, t0, nk, ws + w.kfull, ws + w.hfull, ws + w.vfull, (uint32_t *)(ws + w.mfull), s);
-    if (hipMemcpy2DAsync(ws + w.kfull + (size_t)t0 * row, (size_t)nk * row, K, (size_t)m * row, (size_t)m * row, units,
+    // 1. the cached rows as plain arrays: kept from the previous piece, or (after decode steps or a one-shot prefill
+    //    into this cache) unpacked from the cache; the new rows behind them
+    const bool kept = f->rows == t0;
+    f->rows = -1;                                   // in flux until this call has gone through
+    if (!kept) {
+        expand_cache_runs(cache, t0, ld, f->k, f->h, f->v, f->m, s);
+        f->ent_rows = 0;
+    }
+    if (hipMemcpy2DAsync((char *)f->k + (size_t)t0 * row, (size_t)ld * row, K, (size_t)m * row, (size_t)m * row, units,
                          hipMemcpyDeviceToDevice, s) != hipSuccess ||
-        hipMemcpy2DAsync(ws + w.vfull + (size_t)t0 * row, (size_t)nk * row, V, (size_t)m * row, (size_t)m * row, units,
+        hipMemcpy2DAsync((char *)f->v + (size_t)t0 * row, (size_t)ld * row, V, (size_t)m * row, (size_t)m * row, units,
                          hipMemcpyDeviceToDevice, s) != hipSuccess)
     {
         (void)launch_ok("prefill_append copy");   // records the error text
@@ -372,21 +399,22 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     launch_delta_scan(p->dtype, K, ws + w.hnew, mask_bits, ws + w.chunk_out, nnz, units, m, d, p->theta, s,
                       t0 > 0 ? cache->khat : nullptr);
     stage_end(kStageScan, s);
-    if (hipMemcpy2DAsync(ws + w.hfull + (size_t)t0 * row, (size_t)nk * row, ws + w.hnew, (size_t)m * row,
+    if (hipMemcpy2DAsync((char *)f->h + (size_t)t0 * row, (size_t)ld * row, ws + w.hnew, (size_t)m * row,
                          (size_t)m * row, units, hipMemcpyDeviceToDevice, s) != hipSuccess ||
-        hipMemcpy2DAsync(ws + w.mfull + (size_t)t0 * mrow, (size_t)nk * mrow, mask_bits, (size_t)m * mrow,
+        hipMemcpy2DAsync((char *)f->m + (size_t)t0 * mrow, (size_t)ld * mrow, mask_bits, (size_t)m * mrow,
                          (size_t)m * mrow, units, hipMemcpyDeviceToDevice, s) != hipSuccess)
     {
         (void)launch_ok("prefill_append copy");   // records the error text
         return DA_ERR_HIP;
     }
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
-    // 3. entry lists of every key column (cached ones from reference keys: where a bit is set they equal the key)
-    if (p->score_mode == DA_SCORE_GATHER) {
+    // 3. entry lists and plans of the key columns that do not have them yet, from the first block of 32 columns that
+    //    is new or was incomplete (cached columns from reference keys: where a bit is set they equal the key)
+    if (gather) {
+        const int64_t have = f->ent_rows < t0 ? f->ent_rows : t0;
         stage_begin(kStageEmit, s);
-        launch_emit_entries(p->dtype, ws + w.kfull, ws + w.hfull, (const uint32_t *)(ws + w.mfull), ws + w.ents,
-                            (uint32_t *)(ws + w.counts), (uint8_t *)(ws + w.nch8), ws + w.plan,
-                            (uint32_t *)(ws + w.dense), units, nk, prefill_mfma_n_pad(nk), d, s);
+        launch_emit_entries(p->dtype, f->k, f->h, f->m, f->ents, f->counts, f->nch8, f->plan, f->dense, units, nk, n_pad,
+                            d, s, ld, (int)(have / 32));
         stage_end(kStageEmit, s);
         if (!launch_ok("emit_entries")) return DA_ERR_HIP;
     }
@@ -400,39 +428,39 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.n = nk;
     a.q_off = t0;
     a.nq = m;
+    a.ld = ld;
+    a.vt_from = kept ? t0 / 32 : 0;
     a.W = p->window;
     a.scale_log2 = score_scale(p->scale, d) * 1.4426950408889634f;
     a.rebase = p->score_mode == DA_SCORE_REBASE;
     a.sliding = p->window_mode == DA_WINDOW_SLIDING;
     a.Q = Q;
-    a.K = ws + w.kfull;
-    a.V = ws + w.vfull;
-    a.Khat = ws + w.hfull;
+    a.K = f->k;
+    a.V = f->v;
+    a.Khat = f->h;
     a.O = O;
-    a.ents = ws + w.ents;
-    a.counts = (const uint32_t *)(ws + w.counts);
-    a.nch8 = (const uint8_t *)(ws + w.nch8);
-    a.plan = ws + w.plan;
-    a.dense = (const uint32_t *)(ws + w.dense);
+    a.ents = f->ents;
+    a.counts = f->counts;
+    a.nch8 = f->nch8;
+    a.plan = f->plan;
+    a.dense = f->dense;
     a.fused = 0;
     a.mask_bits = nullptr;
     a.nnz = nullptr;
     a.theta = p->theta;
+    if (!prefill_mfma_supported(a)) return DA_ERR_UNSUPPORTED;
     stage_begin(kStageAttn, s);
-    bool launched = true;
-    if (prefill_mfma_supported(a))
-        launch_prefill_mfma(a, ws + w.vt, s);
-    else
-        launched = launch_prefill_generic(a, s);
+    launch_prefill_mfma(a, f->vt, s);
     stage_end(kStageAttn, s);
-    if (!launched) return DA_ERR_UNSUPPORTED;
     if (!launch_ok("prefill_append attention")) return DA_ERR_HIP;
     // 5. the new rows join the cache
     stage_begin(kStageCacheFill, s);
-    cache_fill_runs(cache, t0, nk, ws + w.kfull, V, ws + w.hfull, (const uint32_t *)(ws + w.mfull), nnz, s);
+    cache_fill_runs(cache, t0, nk, ld, f->k, V, f->h, f->m, nnz, s);
     stage_end(kStageCacheFill, s);
     if (!launch_ok("cache_fill")) return DA_ERR_HIP;
     cache->len = nk;
+    f->rows = nk;
+    if (gather) f->ent_rows = nk;
     return DA_OK;
 }
 

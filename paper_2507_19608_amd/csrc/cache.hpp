@@ -8,6 +8,26 @@
 
 constexpr int kChunk = 64;   // rows per decode chunk; one reference-key checkpoint per chunk
 
+// What delta_attn_prefill_append keeps between its calls on one cache (Sec. III-C, a prompt processed in pieces):
+// the sequence so far as the plain arrays the prefill kernels read, so that a piece only adds its own rows instead
+// of unpacking and compacting the whole prefix again.  Device memory with max_seq rows of room per unit (row stride
+// max_seq, padded strides from prefill_mfma_n_pad(max_seq)), allocated by the first such call (the entry-list
+// arrays by the first one in gather mode), freed with the cache.  Host-side bookkeeping: kernels never see it.
+struct da_prefix {
+    void *k, *h, *v;      // [units][max_seq][d]     keys (raw where a window may need them, see expand_cache_kernel),
+                          //                         reference keys, values
+    uint32_t *m;          // [units][max_seq][d/32]  mask rows
+    void *vt;             // V in matrix-core operand order (transpose_v_kernel)
+    void *ents;           // entry lists, counts, chunk counts, gather plan, re-based columns (emit_entries_kernel)
+    uint32_t *counts;
+    uint8_t *nch8;
+    void *plan;
+    uint32_t *dense;
+    int64_t rows;         // k, h, v, m, vt describe rows 0 .. rows - 1 of the cached sequence; only trusted while
+                          // rows == the cache's length (decode steps and one-shot prefills do not maintain them)
+    int64_t ent_rows;     // key columns 0 .. ent_rows - 1 have their entry lists and plans
+};
+
 struct da_cache {
     int B, Hq, Hkv, d, max_seq, Wd, dtype;
     float theta, scale;
@@ -43,6 +63,7 @@ struct da_cache {
                           //            accumulator order (slot 8 k + i holds row 8 (i / 4) + 4 k + i % 4)
     uint64_t *nnz;        // [units]
     float *part;          // [B*Hq][max_chunks][d + 4] partial (o[d], m, l, 2 unused) rows of one decode step
+    da_prefix *pf;        // host pointer, NULL until delta_attn_prefill_append has run on this cache
 };
 
 // elements of room per chunk for the surviving values: one per key element, one carried-in value per channel, and
@@ -63,11 +84,12 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
                              const void *Khat, const uint32_t *mask_bits, const uint32_t *counts,
                              const uint64_t *nnz, hipStream_t s);
 // column-run layout (fast == 1)
-// appends rows t0 .. n_k - 1 (t0 = rows already held) from whole-sequence arrays [units][n_k][...]
-void cache_fill_runs(da_cache *c, int t0, int n_k, const void *Kfull, const void *Vnew, const void *Hfull,
+// appends rows t0 .. n_k - 1 (t0 = rows already held) from whole-sequence arrays [units][ld][...] (ld >= n_k rows of
+// room per unit)
+void cache_fill_runs(da_cache *c, int t0, int n_k, int ld, const void *Kfull, const void *Vnew, const void *Hfull,
                      const uint32_t *Mfull, const uint64_t *nnz_new, hipStream_t s);
-// writes the cached rows 0 .. t0 - 1 out as whole-sequence arrays with n_k rows of room per unit
-void expand_cache_runs(da_cache *c, int t0, int n_k, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
+// writes the cached rows 0 .. t0 - 1 out as whole-sequence arrays with ld >= t0 rows of room per unit
+void expand_cache_runs(da_cache *c, int t0, int ld, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
                        hipStream_t s);
 // returns the number of partial rows written per head, 0 if the launch wrote the output itself
 int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,

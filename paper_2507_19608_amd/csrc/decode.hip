@@ -646,6 +646,12 @@ void free_all(da_cache *c) {
     void *ptrs[] = {c->mask, c->surv, c->ccnt, c->ck, c->khat, c->ring, c->V, c->nnz, c->part};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (da_prefix *f = c->pf) {
+        void *more[] = {f->k, f->h, f->v, f->m, f->vt, f->ents, f->counts, f->nch8, f->plan, f->dense};
+        for (void *p : more)
+            if (p) (void)hipFree(p);
+        delete f;
+    }
 }
 
 }  // namespace
@@ -667,7 +673,7 @@ void cache_fill_from_prefill(da_cache *c, const da_prefill_params *p, const void
     (void)counts;
     const int units = c->B * c->Hkv, n = p->seq_len;
     if (c->fast) {
-        da::cache_fill_runs(c, 0, n, K, V, Khat, mask_bits, nnz, s);
+        da::cache_fill_runs(c, 0, n, n, K, V, Khat, mask_bits, nnz, s);
         c->len = n;
         return;
     }
@@ -757,6 +763,7 @@ da_status delta_attn_cache_reset(da_cache *c, void *hip_stream) {
     if (!c) return DA_ERR_INVALID_ARG;
     launch_fill_u64(c->nnz, 0, c->B * c->Hkv, (hipStream_t)hip_stream);
     c->len = 0;
+    if (c->pf) c->pf->rows = c->pf->ent_rows = 0;   // an empty sequence, which the (empty) prefix arrays describe
     return launch_ok("cache_reset") ? DA_OK : DA_ERR_HIP;
 }
 

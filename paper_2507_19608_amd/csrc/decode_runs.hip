@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64) void seal_from_ring_kernel(da_cache c, int chun
 
 // Hand-off of prefilled rows to the cache (Sec. III-C): rows t0 .. n_k - 1 (t0 = rows the cache already
 // holds) are appended; one wave per (chunk that contains such a row, unit).  Kfull, Hfull, Mfull describe the
-// whole sequence [units][n_k][...]: keys (for rows the decode window no longer holds raw, the reference key
+// whole sequence [units][ld][...] (ld >= n_k rows of room per unit): keys (for rows the decode window no longer holds raw, the reference key
 // stands in - the two agree wherever a mask bit is set, which is all that is read), reference keys, mask
 // rows; Vnew [units][n_k - t0][d] the new value rows.  With t0 = 0 these are the prefill's own arrays.
 __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__restrict__ Kfull,
@@ -101,17 +101,17 @@ __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__res
                                                              const bf16_t *__restrict__ Hfull,
                                                              const uint32_t *__restrict__ Mfull,
                                                              const uint64_t *__restrict__ nnz_new, da_cache c, int t0,
-                                                             int n_k) {
+                                                             int n_k, int ld) {
     const int chunk = blockIdx.x + t0 / kChunk, unit = blockIdx.y, lane = threadIdx.x;
     const int d = c.d, wpr = d >> 5, m = n_k - t0;
     const int r0 = chunk * kChunk;
     const int ra = max(r0, t0), rb = min(r0 + kChunk, n_k);          // new rows of this chunk
-    const uint32_t *Mp = Mfull + ((size_t)unit * n_k + r0) * wpr;    // the chunk's mask rows, old ones included
+    const uint32_t *Mp = Mfull + ((size_t)unit * ld + r0) * wpr;     // the chunk's mask rows, old ones included
     uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
     for (int i = (ra - r0) * wpr + lane; i < (rb - r0) * wpr; i += kWave) Mc[i] = Mp[i];
     if (lane == 0 && blockIdx.x == 0) c.nnz[unit] = (t0 == 0 ? 0ull : c.nnz[unit]) + nnz_new[unit];
-    const bf16_t *Kp = Kfull + ((size_t)unit * n_k + r0) * d;
-    const bf16_t *Hp = Hfull + ((size_t)unit * n_k + r0) * d;
+    const bf16_t *Kp = Kfull + ((size_t)unit * ld + r0) * d;
+    const bf16_t *Hp = Hfull + ((size_t)unit * ld + r0) * d;
     const bf16_t *Vp = Vnew + (size_t)unit * m * d;
     for (int ch = lane; ch < d; ch += kWave) {
         for (int rq = ra; rq < rb; rq += 16) {               // 16 rows at a time: loads first (clamped), then stores
@@ -158,10 +158,10 @@ __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__res
 }
 
 // The inverse of the hand-off, for a prefill that continues a cached sequence: rows 0 .. t0 - 1 of the cache
-// are written out as plain arrays [units][n_k][...] (n_k >= t0 rows of room per unit): reference keys (from
+// are written out as plain arrays [units][ld][...] (ld >= t0 rows of room per unit): reference keys (from
 // the sealed runs, or for the unsealed last chunk from the ring), keys (raw for the rows the ring still
 // holds, the reference key otherwise), values, mask rows.  One wave per (chunk, unit), lane = channel.
-__global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, int n_k, bf16_t *__restrict__ Kfull,
+__global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, int ld, bf16_t *__restrict__ Kfull,
                                                           bf16_t *__restrict__ Hfull, bf16_t *__restrict__ Vfull,
                                                           uint32_t *__restrict__ Mfull) {
     const int chunk = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, in
     const int r0 = chunk * kChunk, rows = min(kChunk, t0 - r0);
     const bool sealed = rows == kChunk;
     const uint32_t *Mp = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
-    for (int i = lane; i < rows * wpr; i += kWave) Mfull[((size_t)unit * n_k + r0) * wpr + i] = Mp[i];
+    for (int i = lane; i < rows * wpr; i += kWave) Mfull[((size_t)unit * ld + r0) * wpr + i] = Mp[i];
     const bf16_t *room = run_room(c, unit, chunk);
     const bf16_t *ring = (const bf16_t *)c.ring + (size_t)unit * c.Wd * d;
     uint32_t base = 0;
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(64) void expand_cache_kernel(da_cache c, int t0, in
                 if ((bits >> u) & 1u) held = sealed ? sv[u] : kraw[u];
                 const int slot = 8 * ((u >> 2) & 1) + 4 * (u >> 3) + (u & 3);
                 const uint32_t vw = slot < 8 ? v0[slot >> 1] : v1[(slot - 8) >> 1];
-                const size_t o = ((size_t)unit * n_k + row) * d + ch;
+                const size_t o = ((size_t)unit * ld + row) * d + ch;
                 if (r < rows) {
                     Hfull[o] = held;
                     Kfull[o] = raw_here ? kraw[u] : held;
@@ -614,19 +614,19 @@ __global__ __launch_bounds__(64 * NW * (D / 64), 2) void decode_step_runs_kernel
 
 namespace da {
 
-void cache_fill_runs(da_cache *c, int t0, int n_k, const void *Kfull, const void *Vnew, const void *Hfull,
+void cache_fill_runs(da_cache *c, int t0, int n_k, int ld, const void *Kfull, const void *Vnew, const void *Hfull,
                      const uint32_t *Mfull, const uint64_t *nnz_new, hipStream_t s) {
     const int units = c->B * c->Hkv;
     const int chunks = (n_k + kChunk - 1) / kChunk - t0 / kChunk;
     hipLaunchKernelGGL(cache_fill_runs_kernel, dim3(chunks, units), dim3(64), 0, s, (const bf16_t *)Kfull,
-                       (const bf16_t *)Vnew, (const bf16_t *)Hfull, Mfull, nnz_new, *c, t0, n_k);
+                       (const bf16_t *)Vnew, (const bf16_t *)Hfull, Mfull, nnz_new, *c, t0, n_k, ld);
 }
 
-void expand_cache_runs(da_cache *c, int t0, int n_k, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
+void expand_cache_runs(da_cache *c, int t0, int ld, void *Kfull, void *Hfull, void *Vfull, uint32_t *Mfull,
                        hipStream_t s) {
     if (t0 <= 0) return;
     hipLaunchKernelGGL(expand_cache_kernel, dim3((t0 + kChunk - 1) / kChunk, c->B * c->Hkv), dim3(64), 0, s, *c, t0,
-                       n_k, (bf16_t *)Kfull, (bf16_t *)Hfull, (bf16_t *)Vfull, Mfull);
+                       ld, (bf16_t *)Kfull, (bf16_t *)Hfull, (bf16_t *)Vfull, Mfull);
 }
 
 int decode_step_runs(da_cache *c, const void *q, const void *k, const void *v, void *o, uint32_t *mask_row, int t,

@@ -232,21 +232,22 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
                                                            const uint32_t *__restrict__ mask_bits,
                                                            EntryChunk *__restrict__ ents, uint32_t *__restrict__ counts,
                                                            uint8_t *__restrict__ nch8, uint8_t *__restrict__ plan,
-                                                           uint32_t *__restrict__ dense, int n, int n_pad, int d) {
+                                                           uint32_t *__restrict__ dense, int n, int ld, int ld_pad,
+                                                           int blk0, int d) {
     constexpr int kCols = kPlanCols, kPlanWaves = kPlanWaveCount;
     __shared__ uint32_t blk_cnt[kCols];
-    const int unit = blockIdx.y;
+    const int unit = blockIdx.y, blk = blk0 + blockIdx.x;
     const int lane = threadIdx.x & 63;
-    const size_t row0 = (size_t)unit * n;
+    const size_t row0 = (size_t)unit * ld;
     for (int k = 0; k < kCols / 4; ++k)
         emit_column(K + row0 * d, Khat + row0 * d, mask_bits + row0 * (d >> 5), ents + row0 * (d / kGroup), counts + row0,
-                    nch8 + (size_t)unit * n_pad, blk_cnt, n, d, lane, blockIdx.x * kCols + 4 * k + (threadIdx.x >> 6),
+                    nch8 + (size_t)unit * ld_pad, blk_cnt, n, d, lane, blk * kCols + 4 * k + (threadIdx.x >> 6),
                     4 * k + (threadIdx.x >> 6));
     if (!plan) return;
     __syncthreads();
     if (threadIdx.x < kWave)                                  // the first wave; its lanes 0 .. 31 own a column each
-        plan_block(blk_cnt, plan + ((size_t)unit * (n_pad / kCols) + blockIdx.x) * kPlanWaves * 8,
-                   dense + (size_t)unit * (n_pad / kCols) + blockIdx.x, (blockIdx.x + 1) * kCols <= n, d, threadIdx.x);
+        plan_block(blk_cnt, plan + ((size_t)unit * (ld_pad / kCols) + blk) * kPlanWaves * 8,
+                   dense + (size_t)unit * (ld_pad / kCols) + blk, (blk + 1) * kCols <= n, d, threadIdx.x);
 }
 
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n) {
@@ -294,17 +295,22 @@ void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits
         scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
 }
 
+// ld > 0: the arrays have ld rows of room per unit (padded strides from prefill_mfma_n_pad(ld)) of which n are valid,
+// and only the blocks of 32 columns from blk0 on are (re)written; ld == 0: the arrays are exactly n rows per unit.
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
                          uint32_t *counts, uint8_t *nch8, void *plan, uint32_t *dense, int units, int n, int n_pad,
-                         int d, hipStream_t s) {
-    dim3 grid(n_pad / 32, units), block(256);
+                         int d, hipStream_t s, int ld, int blk0) {
+    const int ld_pad = ld > 0 ? prefill_mfma_n_pad(ld) : n_pad;
+    if (ld <= 0) ld = n;
+    if (blk0 >= n_pad / 32) return;
+    dim3 grid(n_pad / 32 - blk0, units), block(256);
     if (dtype == 0)
         hipLaunchKernelGGL(emit_entries_kernel<float>, grid, block, 0, s, (const float *)K, (const float *)Khat,
-                           mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, dense, n, n_pad, d);
+                           mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, dense, n, ld, ld_pad, blk0, d);
     else
         hipLaunchKernelGGL(emit_entries_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)K,
                            (const bf16_t *)Khat, mask_bits, (EntryChunk *)ents, counts, nch8, (uint8_t *)plan, dense, n,
-                           n_pad, d);
+                           ld, ld_pad, blk0, d);
 }
 
 }  // namespace da

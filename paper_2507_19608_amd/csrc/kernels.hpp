@@ -31,6 +31,9 @@ struct PrefillArgs {
     int dtype;            // 0 f32, 1 bf16
     int B, Hq, Hkv, d, n, W;   // n = number of key rows
     int q_off, nq;             // the query rows are positions q_off .. q_off + nq - 1 (q_off + nq == n)
+    int ld = 0;                // > 0 (matrix-core path only): K, V, Khat, ents, counts have ld >= n rows of room per
+                               // unit and nch8, plan, dense, vt the strides of prefill_mfma_n_pad(ld); 0: exactly n
+    int vt_from = 0;           // blocks of 32 rows below this one are already in vt (V re-order of earlier rows kept)
     float scale_log2;     // score scale * log2(e)
     int rebase;           // 1: outside scores from q . k_hat instead of the entry lists
     int sliding;          // 1: exact region is the band i - j < W instead of squares of side W
@@ -61,7 +64,7 @@ void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits
 // units * n_pad / 32 words (see emit_entries_kernel)
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
                          uint32_t *counts, uint8_t *nch8, void *plan, uint32_t *dense, int units, int n, int n_pad,
-                         int d, hipStream_t s);
+                         int d, hipStream_t s, int ld = 0, int blk0 = 0);
 // Generic path: any head_dim in {32, 64, ..., 256}, both dtypes, VALU only.  Returns false if
 // the head_dim has no instantiation.
 bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);

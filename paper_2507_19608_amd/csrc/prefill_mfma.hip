@@ -53,6 +53,8 @@ struct MfmaArgs {
     const uint8_t *__restrict__ plan;   // per unit and block of kTB columns: kWaves x 8 bytes (emit_entries_kernel)
     const uint32_t *__restrict__ dense; // per unit and block: bit c set = column c is re-based, not gathered
     int Hq, Hkv, n, n_pad, W, rebase, sliding;
+    int ld, ld_pad;                     // rows of room per unit in K, Khat, V, ents, counts (>= n), and the padded
+                                        // stride of Vt, nch8, plan, dense that goes with it (>= n_pad)
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     int xsplit;                         // > 0: XCD-aware order, every unit split this many ways (see the kernel)
@@ -120,12 +122,12 @@ __device__ __forceinline__ void transpose_v_block(const bf16_t *__restrict__ Vp,
 
 template <int D>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
-                                                          int n, int n_pad) {
+                                                          int n, int ld, int ld_pad, int blk0) {
     __shared__ bf16_t tile[kTB][D + 2];
     constexpr int MT = D / 32;
-    const int unit = blockIdx.y, blk = blockIdx.x;
-    transpose_v_block<D, 256>(V + (size_t)unit * n * D,
-                              (u32x4 *)(Vt + (size_t)unit * D * n_pad) + (size_t)blk * (2 * MT * 64), blk * kTB, n, tile,
+    const int unit = blockIdx.y, blk = blk0 + blockIdx.x;
+    transpose_v_block<D, 256>(V + (size_t)unit * ld * D,
+                              (u32x4 *)(Vt + (size_t)unit * D * ld_pad) + (size_t)blk * (2 * MT * 64), blk * kTB, n, tile,
                               (int)threadIdx.x, [] { __syncthreads(); });
 }
 
@@ -149,8 +151,8 @@ __device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int n
     constexpr int CW = D / kWave;                               // waves that scan (64 channels each)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = a.n;
-    const bf16_t *Kp = a.K + (size_t)unit * n * D;
-    bf16_t *Hp = const_cast<bf16_t *>(a.Khat) + (size_t)unit * n * D;
+    const bf16_t *Kp = a.K + (size_t)unit * a.ld * D;
+    bf16_t *Hp = const_cast<bf16_t *>(a.Khat) + (size_t)unit * a.ld * D;
     uint32_t *Mp = a.mask_bits + (size_t)unit * n * (D / 32);
     unsigned long long *cnt = (unsigned long long *)lds;        // [CW] surviving entries per scanning wave
     bf16_t *Kl = (bf16_t *)(lds + 64);                          // [need][D] keys
@@ -191,11 +193,11 @@ __device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int n
     // 4. compaction of the key columns of the blocks this work group will gather (whole blocks left of every one of
     //    its rows' windows, so all their rows are here), a column per wave at a time, then their gather plans
     uint32_t *blk_cnt = (uint32_t *)(Ml + (size_t)need * (D / 32));   // [gather_blocks][32] chunk counts
-    EntryChunk *ents0 = const_cast<EntryChunk *>(a.ents) + (size_t)unit * n * (D / kGroup);
-    uint32_t *counts0 = a.counts + (size_t)unit * n;
-    uint8_t *nch0 = a.nch8 + (size_t)unit * a.n_pad;
-    uint8_t *plan = const_cast<uint8_t *>(a.plan) + (size_t)unit * (a.n_pad / kTB) * kWaves * 8;
-    uint32_t *dense = const_cast<uint32_t *>(a.dense) + (size_t)unit * (a.n_pad / kTB);
+    EntryChunk *ents0 = const_cast<EntryChunk *>(a.ents) + (size_t)unit * a.ld * (D / kGroup);
+    uint32_t *counts0 = a.counts + (size_t)unit * a.ld;
+    uint8_t *nch0 = a.nch8 + (size_t)unit * a.ld_pad;
+    uint8_t *plan = const_cast<uint8_t *>(a.plan) + (size_t)unit * (a.ld_pad / kTB) * kWaves * 8;
+    uint32_t *dense = const_cast<uint32_t *>(a.dense) + (size_t)unit * (a.ld_pad / kTB);
     for (int j = wave; j < gather_blocks * kTB; j += kWaves)
         emit_column((const bf16_t *)Kl, (const bf16_t *)Hl, (const uint32_t *)Ml, ents0, counts0, nch0, blk_cnt, need, D,
                     lane, j, j);
@@ -207,8 +209,8 @@ __device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int n
     {
         typedef bf16_t (*tile_t)[D + 2];
         tile_t tile = (tile_t)(lds + 64 + (size_t)wave * kTB * (D + 2) * sizeof(bf16_t));
-        const bf16_t *Vp = a.V + (size_t)unit * n * D;
-        u32x4 *Op = (u32x4 *)(const_cast<bf16_t *>(a.Vt) + (size_t)unit * D * a.n_pad);
+        const bf16_t *Vp = a.V + (size_t)unit * a.ld * D;
+        u32x4 *Op = (u32x4 *)(const_cast<bf16_t *>(a.Vt) + (size_t)unit * D * a.ld_pad);
         for (int blk = wave; blk * kTB < need; blk += kWaves)
             transpose_v_block<D, kWave>(Vp, Op + (size_t)blk * (2 * (D / 32) * 64), blk * kTB, n, tile, lane, [] {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -263,12 +265,12 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int i0 = a.q_off + tile * RT;
     const int i_last = min(n - 1, i0 + RT - 1);
 
-    const bf16_t *Kp = a.K + (size_t)unit * n * D;
-    const bf16_t *Hp = a.Khat + (size_t)unit * n * D;
-    const bf16_t *Vtp = a.Vt + (size_t)unit * D * a.n_pad;
-    const EntryChunk *Ep = a.ents + (size_t)unit * n * (D / kGroup);
-    const uint8_t *Pp = a.plan + (size_t)unit * (a.n_pad / kTB) * (kWaves * 8);
-    const uint32_t *Dp = a.dense + (size_t)unit * (a.n_pad / kTB);
+    const bf16_t *Kp = a.K + (size_t)unit * a.ld * D;
+    const bf16_t *Hp = a.Khat + (size_t)unit * a.ld * D;
+    const bf16_t *Vtp = a.Vt + (size_t)unit * D * a.ld_pad;
+    const EntryChunk *Ep = a.ents + (size_t)unit * a.ld * (D / kGroup);
+    const uint8_t *Pp = a.plan + (size_t)unit * (a.ld_pad / kTB) * (kWaves * 8);
+    const uint32_t *Dp = a.dense + (size_t)unit * (a.ld_pad / kTB);
 
     // score row sr = hh * RT + r  ->  query row i0 + r of head head0 + hh
     auto q_row_ptr = [&](int sr) -> const bf16_t * {
@@ -859,10 +861,13 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
 template <int D>
 static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     const int units = p.B * p.Hkv;
-    if (!p.fused)
-        hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(n_pad / kTB, units), dim3(256), 0, s,
-                           (const bf16_t *)p.V, (bf16_t *)vt, p.n, n_pad);
+    const int ld = p.ld > 0 ? p.ld : p.n, ld_pad = p.ld > 0 ? prefill_mfma_n_pad(p.ld) : n_pad;
+    if (!p.fused && p.vt_from < n_pad / kTB)
+        hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(n_pad / kTB - p.vt_from, units), dim3(256), 0, s,
+                           (const bf16_t *)p.V, (bf16_t *)vt, p.n, ld, ld_pad, p.vt_from);
     MfmaArgs a;
+    a.ld = ld;
+    a.ld_pad = ld_pad;
     a.V = (const bf16_t *)p.V;
     a.mask_bits = p.mask_bits;
     a.nnz = (unsigned long long *)p.nnz;

@@ -360,6 +360,61 @@ def test_chunked_prefill_then_decode(score_mode, window_mode, d, Hq, Hkv, W, Wd,
     cache.close()
 
 
+@pytest.mark.parametrize("d,Hq,Hkv", [(64, 4, 2), (128, 4, 1)])
+def test_chunked_prefill_between_decode_steps_resets_and_score_modes(d, Hq, Hkv):
+    """The cache keeps the sequence as plain arrays between pieces and only adds a piece's rows; whatever else moves
+    the cache on (decode steps, a reset, a one-shot prefill into it) must make the next piece rebuild them, and a
+    piece in gather mode must find the entry lists of columns that earlier telescoped pieces did not write.  Every
+    piece against the same rows of the oracle's prefill over the whole prefix, the final cache through decode."""
+    B, W, Wd, theta = 2, 40, 96, 0.2
+    G, R = da.DA_SCORE_GATHER, da.DA_SCORE_REBASE
+    # (kind, rows, score mode): pieces that start inside a block of 32 columns and inside a chunk of 64 rows
+    plan = [("piece", 75, G), ("piece", 50, R), ("piece", 45, G), ("decode", 7, None), ("piece", 90, R),
+            ("piece", 33, G), ("decode", 1, None), ("piece", 64, G)]
+    L = sum(r for _, r, _ in plan) + 6
+    Q, K, V = rand_walk(81, B, Hq, L, d), rand_walk(82, B, Hkv, L, d), rand_walk(83, B, Hkv, L, d, clip=3.5)
+    Qd, Kd, Vd = (to_dev(x, "bf16") for x in (Q, K, V))
+    cache = da.Cache(B, Hq, Hkv, d, L, Wd, theta, torch.bfloat16)
+
+    def run(plan, t0):
+        for kind, rows, mode in plan:
+            if kind == "decode":
+                for t in range(t0, t0 + rows):
+                    da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+                t0 += rows
+                continue
+            sl = slice(t0, t0 + rows)
+            O, maskg, nnzg = da.delta_attn_prefill_append(cache, Qd[:, :, sl].contiguous(), Kd[:, :, sl].contiguous(),
+                                                          Vd[:, :, sl].contiguous(), theta, W, score_mode=mode)
+            ref = orc.prefill(Q[:, :, :t0 + rows], K[:, :, :t0 + rows], V[:, :, :t0 + rows], theta, W, rows=(t0, t0 + rows))
+            assert ref["knife"] == 0
+            assert (unpack_mask(maskg, d) == ref["mask"][:, :, t0:]).all(), (t0, rows)
+            for h in range(Hq):
+                check_output(O[:, h], ref["O"][:, h], "bf16")
+            t0 += rows
+            assert len(cache) == t0
+            assert (cache.nnz().cpu().numpy() == ref["nnz"]).all()
+        return t0
+
+    t0 = run(plan, 0)
+    # the same cache again from empty: pieces straight after a reset, then after a one-shot prefill into the cache
+    cache.reset()
+    t0 = run([("piece", 40, G), ("piece", 30, G)], 0)
+    cache.reset()
+    da.delta_attn_prefill(Qd[:, :, :100].contiguous(), Kd[:, :, :100].contiguous(), Vd[:, :, :100].contiguous(), theta, W,
+                          cache=cache)
+    t0 = run([("piece", 70, G), ("piece", 70, R), ("piece", 31, G)], 100)
+    st = orc.DecodeState(theta, Wd)
+    st.append(K[:, :, :t0], V[:, :, :t0])
+    assert (unpack_mask(cache.mask_rows(), d) == st.mask).all()
+    for t in range(t0, t0 + 6):
+        o, mrow = da.delta_attn_decode(cache, Qd[:, :, t].contiguous(), Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        o_ref, m_ref = st.step(Q[:, :, t], K[:, :, t], V[:, :, t])
+        assert (unpack_mask(mrow, d) == m_ref).all()
+        check_output(o, o_ref, "bf16")
+    cache.close()
+
+
 def test_chunked_prefill_argument_checks():
     z = lambda h, m, d=64: torch.zeros(1, h, m, d, dtype=torch.bfloat16, device="cuda")
     small = da.Cache(1, 2, 1, 64, 300, 8, 0.1, torch.bfloat16)          # decode window below one chunk: row layout
