@@ -239,10 +239,10 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
     const int unit = blockIdx.y, blk = blk0 + blockIdx.x;
     const int lane = threadIdx.x & 63;
     const size_t row0 = (size_t)unit * ld;
-    for (int k = 0; k < kCols / 4; ++k)
-        emit_column(K + row0 * d, Khat + row0 * d, mask_bits + row0 * (d >> 5), ents + row0 * (d / kGroup), counts + row0,
-                    nch8 + (size_t)unit * ld_pad, blk_cnt, n, d, lane, blk * kCols + 4 * k + (threadIdx.x >> 6),
-                    4 * k + (threadIdx.x >> 6));
+    // the 4 waves take every 4th column of the block
+    emit_columns(K + row0 * d, Khat + row0 * d, mask_bits + row0 * (d >> 5), ents + row0 * (d / kGroup), counts + row0,
+                 nch8 + (size_t)unit * ld_pad, blk_cnt, n, d, lane, blk * kCols + (int)(threadIdx.x >> 6), 4,
+                 (blk + 1) * kCols, blk * kCols);
     if (!plan) return;
     __syncthreads();
     if (threadIdx.x < kWave)                                  // the first wave; its lanes 0 .. 31 own a column each

@@ -198,9 +198,8 @@ __device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int n
     uint8_t *nch0 = a.nch8 + (size_t)unit * a.ld_pad;
     uint8_t *plan = const_cast<uint8_t *>(a.plan) + (size_t)unit * (a.ld_pad / kTB) * kWaves * 8;
     uint32_t *dense = const_cast<uint32_t *>(a.dense) + (size_t)unit * (a.ld_pad / kTB);
-    for (int j = wave; j < gather_blocks * kTB; j += kWaves)
-        emit_column((const bf16_t *)Kl, (const bf16_t *)Hl, (const uint32_t *)Ml, ents0, counts0, nch0, blk_cnt, need, D,
-                    lane, j, j);
+    emit_columns((const bf16_t *)Kl, (const bf16_t *)Hl, (const uint32_t *)Ml, ents0, counts0, nch0, blk_cnt, need, D,
+                 lane, wave, kWaves, gather_blocks * kTB, 0);
     lds_barrier();                                               // (the chunk counts; the lists go to global memory)
     for (int blk = wave; blk < gather_blocks; blk += kWaves)
         plan_block(blk_cnt + blk * kTB, plan + (size_t)blk * kWaves * 8, dense + blk, (blk + 1) * kTB <= n, D, lane);

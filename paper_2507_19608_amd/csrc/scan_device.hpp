@@ -98,33 +98,58 @@ __device__ __forceinline__ float scan_rows(const T *__restrict__ Kp, T *__restri
 
 // Compaction of one key column j of a unit by one wave: ballot + prefix count turn the mask row into a dense list of
 // (channel, delta) pairs in EntryChunk form (see emit_entries_kernel); blk_cnt[slot_in_block] receives the chunk count.
+// In two steps, so that a wave can have the next column's inputs in flight while it works on this one (a column is
+// a short chain of dependent memory round trips; one column at a time is latency bound):
+//   load_column    every input of the column: the lane's mask word, key and previous reference key of each 64-channel
+//                  pass (all loads unconditional, indices clamped into the arrays)
+//   finish_column  the compaction proper
 // K0, H0, M0: row 0 of the unit's keys, reference keys and mask words (global memory or an LDS copy);
 // ents0, counts0, nch0: the unit's first entry chunk, count and chunk-count slot (global).
+constexpr int kMaxPass = 4;                                   // 64-channel passes of a column: head_dim <= 256
+struct ColumnIn {
+    float k[kMaxPass], held[kMaxPass];
+    uint32_t word[kMaxPass];
+};
+
 template <typename T>
-__device__ __forceinline__ void emit_column(const T *K0, const T *H0, const uint32_t *M0, EntryChunk *__restrict__ ents0,
-                                            uint32_t *__restrict__ counts0, uint8_t *__restrict__ nch0,
-                                            uint32_t *blk_cnt, int n, int d, int lane, int j, int slot_in_block) {
+__device__ __forceinline__ void load_column(ColumnIn &in, const T *K0, const T *H0, const uint32_t *M0, int n, int d,
+                                            int lane, int j) {
+    const size_t row = (size_t)min(j, n - 1);                 // columns past the end are never finished
+    const T *Kp = K0 + row * d;
+    const T *Hprev = H0 + (row - (row > 0 ? 1 : 0)) * d;
+    const uint32_t *Mp = M0 + row * (d >> 5);
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        const int c = min(p * kWave + lane, d - 1);
+        in.word[p] = Mp[c >> 5];
+        in.k[p] = load_f32(Kp, c);
+        in.held[p] = load_f32(Hprev, c);
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void finish_column(const ColumnIn &in, EntryChunk *__restrict__ ents0,
+                                              uint32_t *__restrict__ counts0, uint8_t *__restrict__ nch0,
+                                              uint32_t *blk_cnt, int n, int d, int lane, int j, int slot_in_block) {
     if (j >= n) {
         if (lane == 0) blk_cnt[slot_in_block] = 0u;
         return;
     }
-    const int wpr = d >> 5;
     const size_t row = (size_t)j;
-    const T *Kp = K0 + row * d;
-    const T *Hprev = H0 + (row - (j > 0 ? 1 : 0)) * d;
-    const uint32_t *Mp = M0 + row * wpr;
     EntryChunk *out = ents0 + row * (d / kGroup);
     uint32_t off = 0;
     bool big = false;
-    for (int c0 = 0; c0 < d; c0 += kWave) {
-        const int c = c0 + lane;
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        if (p * kWave >= d) break;
+        const int c = p * kWave + lane;
         const bool act = c < d;
         bool bit = false;
         float delta = 0.f;
         if (act) {
-            bit = (Mp[c >> 5] >> (c & 31)) & 1u;
-            const float k = load_f32(Kp, c);
-            const float held = (j == 0) ? 0.f : load_f32(Hprev, c);
+            bit = (in.word[p] >> (c & 31)) & 1u;
+            const float k = in.k[p];
+            const float held = (j == 0) ? 0.f : in.held[p];
             delta = k - held;                                  // (row 0: the basis, delta = k)
             const float now = (bit || j == 0) ? k : held;      // reference key after this row
             big = big || !(fabsf(now) < 32768.f);
@@ -151,6 +176,24 @@ __device__ __forceinline__ void emit_column(const T *K0, const T *H0, const uint
         // bit 31: some reference key of this row is too large for (or not a number in) fp16, the format in which the
         // matrix-core prefill kernel re-bases a column; such a column is gathered like any other
         blk_cnt[slot_in_block] = (padded / kGroup) | (big ? 0x80000000u : 0u);
+    }
+}
+
+// Columns first, first + step, ... below end (end - first a multiple of step is not required) by one wave, the
+// inputs of column i + 1 requested before column i is compacted; the chunk count of column j goes to
+// blk_cnt[j - cnt_base].
+template <typename T>
+__device__ __forceinline__ void emit_columns(const T *K0, const T *H0, const uint32_t *M0, EntryChunk *__restrict__ ents0,
+                                             uint32_t *__restrict__ counts0, uint8_t *__restrict__ nch0,
+                                             uint32_t *blk_cnt, int n, int d, int lane, int first, int step, int end,
+                                             int cnt_base) {
+    if (first >= end) return;
+    ColumnIn cur, nxt;
+    load_column(cur, K0, H0, M0, n, d, lane, first);
+    for (int j = first; j < end; j += step) {
+        load_column(nxt, K0, H0, M0, n, d, lane, j + step);   // clamped to the last row; unused after the last column
+        finish_column<T>(cur, ents0, counts0, nch0, blk_cnt, n, d, lane, j, j - cnt_base);
+        cur = nxt;
     }
 }
 
