@@ -134,9 +134,12 @@ da_status delta_attn_prefill(const da_prefill_params *p, const void *Q, const vo
 
 /*
  * delta_attn_prefill for callers that cannot allocate device memory or bring a workspace: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and bit-identical
- * outputs as delta_attn_prefill without a cache; the scratch is a buffer of DA_NOALLOC_SCRATCH_BYTES built into the
- * library's device image (one copy per GPU, held until the process ends), so the call itself allocates nothing.
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation and same kernels as
+ * delta_attn_prefill without a cache, masks and nnz bit-identical; outputs bit-identical too unless delta_attn_prefill
+ * cuts a small launch along the keys (several work groups per row tile, merged afterwards) and the built-in buffer has
+ * no room for the parts: this call then runs uncut and the outputs differ in rounding order only.  The scratch is a
+ * buffer of DA_NOALLOC_SCRATCH_BYTES built into the library's device image (one copy per GPU, held until the process
+ * ends), so the call itself allocates nothing.
  *   - Returns DA_ERR_WORKSPACE, with the two sizes in delta_attn_last_error(), when
  *     delta_attn_prefill_workspace_bytes(p) exceeds DA_NOALLOC_SCRATCH_BYTES (nothing has been enqueued then).
  *   - Every call on a GPU uses that GPU's one buffer: two calls whose kernels overlap in time on the same GPU (two
@@ -162,7 +165,8 @@ da_status delta_attn_prefill_noalloc(const da_prefill_params *p, const void *Q, 
  *             a decode_window above max_seq counts as max_seq),
  *             at most 32 query heads per KV head; otherwise DA_ERR_UNSUPPORTED
  *   workspace device scratch of at least delta_attn_prefill_append_workspace_bytes(p, cache) (0 if the arguments
- *             are invalid), 256-byte aligned; it grows with p->seq_len only
+ *             are invalid), 256-byte aligned; it depends on p->seq_len and (through the key split
+ *             of launches that do not fill the chip) on the cache length at the time of the call
  * The cache keeps the sequence so far as the plain arrays the prefill kernels read (keys, reference keys, values in
  * two orders, mask rows, and in DA_SCORE_GATHER mode the entry lists and gather plans of all key columns), with
  * max_seq rows of room: about 8 * head_dim + 4 * head_dim / 32 bytes per (KV head, row), 16 * head_dim + 8 in

@@ -19,8 +19,26 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline size_t elt_size(int dtype) { return dtype == DA_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t khat, chunk_out, ents, counts, nch8, plan, dense, vt, total;
+    size_t khat, chunk_out, ents, counts, nch8, plan, dense, vt, part, total;
+    int ksplit;   // work groups per tile of the attention launch (prefill_mfma_ksplit); `part` holds their results
 };
+
+// what prefill_mfma_ksplit reads, for a prefill of p's rows behind `cached` rows
+PrefillArgs split_args(const da_prefill_params *p, int64_t cached) {
+    PrefillArgs a = {};
+    a.dtype = p->dtype;
+    a.B = p->batch;
+    a.Hq = p->n_q_heads;
+    a.Hkv = p->n_kv_heads;
+    a.d = p->head_dim;
+    a.n = (int)cached + p->seq_len;
+    a.q_off = (int)cached;
+    a.nq = p->seq_len;
+    a.ksplit = 1;
+    a.rebase = p->score_mode == DA_SCORE_REBASE;
+    a.fused = cached == 0 && prefill_mfma_supported(a) && (int64_t)p->seq_len * p->head_dim <= kFusedMaxElems;
+    return a;
+}
 
 da_status check_params(const da_prefill_params *p) {
     if (!p) return DA_ERR_INVALID_ARG;
@@ -38,7 +56,8 @@ da_status check_params(const da_prefill_params *p) {
     return DA_OK;
 }
 
-WsLayout layout(const da_prefill_params *p) {
+// split: cut the attention launch along the keys where that pays (more scratch); false: never
+WsLayout layout(const da_prefill_params *p, bool split = true) {
     const size_t units = (size_t)p->batch * p->n_kv_heads;
     const size_t rows = units * (size_t)p->seq_len;
     WsLayout w;
@@ -59,6 +78,10 @@ WsLayout layout(const da_prefill_params *p) {
     off += align_up(units * (size_t)(prefill_mfma_n_pad(p->seq_len) / 32) * 4);
     w.vt = off;
     off += align_up(units * (size_t)p->head_dim * prefill_mfma_n_pad(p->seq_len) * 2);
+    const PrefillArgs a = split_args(p, 0);
+    w.ksplit = split ? prefill_mfma_ksplit(a) : 1;
+    w.part = off;
+    off += align_up(prefill_mfma_part_bytes(a, w.ksplit));
     w.total = off;
     return w;
 }
@@ -181,7 +204,8 @@ da_status delta_attn_prefill_noalloc(const da_prefill_params *p, const void *Q, 
     da_status st = check_params(p);
     if (st != DA_OK) return st;
     if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
-    const WsLayout w = layout(p);
+    WsLayout w = layout(p);
+    if (w.total > kScratchBytes) w = layout(p, false);   // without the key split of small launches: less scratch
     if (w.total > kScratchBytes) {
         set_last_error("delta_attn_prefill_noalloc: these params need %zu bytes of scratch, the built-in buffer holds %zu",
                        w.total, kScratchBytes);
@@ -259,6 +283,8 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     a.ents = ents;
     a.counts = counts;
     a.nch8 = nch8;
+    a.ksplit = w.ksplit;
+    a.part = ws + w.part;
     a.plan = ws + w.plan;
     a.dense = (const uint32_t *)(ws + w.dense);
     stage_begin(kStageAttn, s);
@@ -282,10 +308,11 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
 // workspace of delta_attn_prefill_append: what the scan of the new rows needs (the whole-sequence arrays live in the
 // cache, see da_prefix)
 struct AppendLayout {
-    size_t hnew, chunk_out, total;
+    size_t hnew, chunk_out, part, total;
+    int ksplit;
 };
 
-AppendLayout append_layout(const da_prefill_params *p) {
+AppendLayout append_layout(const da_prefill_params *p, int64_t cached) {
     const size_t units = (size_t)p->batch * p->n_kv_heads, d = p->head_dim, es = elt_size(p->dtype);
     const size_t m = p->seq_len;
     AppendLayout w;
@@ -294,6 +321,10 @@ AppendLayout append_layout(const da_prefill_params *p) {
     off += align_up(units * m * d * es);
     w.chunk_out = off;
     off += align_up(2 * units * (size_t)delta_scan_num_chunks((int)m) * d * es);
+    const PrefillArgs a = split_args(p, cached);
+    w.ksplit = prefill_mfma_ksplit(a);
+    w.part = off;
+    off += align_up(prefill_mfma_part_bytes(a, w.ksplit));
     w.total = off;
     return w;
 }
@@ -354,7 +385,7 @@ extern "C" {
 
 size_t delta_attn_prefill_append_workspace_bytes(const da_prefill_params *p, const da_cache *cache) {
     if (check_append(p, cache) != DA_OK) return 0;
-    return append_layout(p).total;
+    return append_layout(p, cache->len).total;
 }
 
 da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, const void *K, const void *V, void *O,
@@ -364,7 +395,7 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     if (st != DA_OK) return st;
     if (!Q || !K || !V || !O || !mask_bits || !nnz) return DA_ERR_INVALID_ARG;
     const int t0 = (int)cache->len, m = p->seq_len, nk = t0 + m, d = p->head_dim;
-    const AppendLayout w = append_layout(p);
+    const AppendLayout w = append_layout(p, t0);
     if (!workspace || workspace_bytes < w.total || !ws_aligned(workspace)) return DA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
@@ -430,6 +461,8 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.nq = m;
     a.ld = ld;
     a.vt_from = kept ? t0 / 32 : 0;
+    a.ksplit = w.ksplit;
+    a.part = ws + w.part;
     a.W = p->window;
     a.scale_log2 = score_scale(p->scale, d) * 1.4426950408889634f;
     a.rebase = p->score_mode == DA_SCORE_REBASE;

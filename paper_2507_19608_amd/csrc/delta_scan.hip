@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
 
     float held = load_f32(o2, 0);   // chunk 0 is exact
     long long adjust = 0;
-    constexpr int G = 16;           // chunks whose boundary values are fetched together
+    constexpr int G = 4;            // chunks whose boundary values are fetched together
     for (int cb = 1; cb < nchunks; cb += G) {
         float g1[G], g2[G];
 #pragma unroll
@@ -185,21 +185,43 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
                 float spec = g1[u];
                 bool synced = !active || (__float_as_uint(held) == __float_as_uint(spec));
                 if (__any(!synced)) {
+                    // Re-run the chunk's rows until every channel has met pass 2's chain.  The rows are fetched 16 at
+                    // a time, the next batch requested before this one is worked on (indices clamped to the chunk):
+                    // one row at a time the loop paid a full memory round trip per row.
                     const int t1 = min(n, chunk * L + L);
-                    for (int t = chunk * L; t < t1 && __any(!synced); ++t) {
-                        const float k = load_f32(Kp, (size_t)t * d + cs);
-                        const bool fs = fabsf(k - spec) > theta;
-                        const bool ft = fabsf(k - held) > theta;
-                        spec = fs ? k : spec;
-                        if (!synced) {
-                            held = ft ? k : held;
-                            store_from_f32(Hp, (size_t)t * d + c, held);
+                    constexpr int U = 16;
+                    auto load_batch = [&](float (&k)[U], int tb) {
+#pragma unroll
+                        for (int r = 0; r < U; ++r) k[r] = load_f32(Kp, (size_t)min(tb + r, t1 - 1) * d + cs);
+                    };
+                    auto work_batch = [&](const float (&kk)[U], int tb) -> bool {   // true: nothing left to do
+#pragma unroll
+                        for (int r = 0; r < U; ++r) {
+                            const int t = tb + r;
+                            if (t >= t1 || !__any(!synced)) return true;
+                            const float k = kk[r];
+                            const bool fs = fabsf(k - spec) > theta;
+                            const bool ft = fabsf(k - held) > theta;
+                            spec = fs ? k : spec;
+                            if (!synced) {
+                                held = ft ? k : held;
+                                store_from_f32(Hp, (size_t)t * d + c, held);
+                            }
+                            const uint64_t bt = __ballot(synced ? fs : ft);
+                            const uint64_t bs = __ballot(fs);
+                            if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
+                            adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
+                            synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
                         }
-                        const uint64_t bt = __ballot(synced ? fs : ft);
-                        const uint64_t bs = __ballot(fs);
-                        if (writer) Mp[(size_t)t * wpr + word] = (uint32_t)(bt >> (lane & 32));
-                        adjust += (long long)__popcll(bt) - (long long)__popcll(bs);
-                        synced = synced || (__float_as_uint(held) == __float_as_uint(spec));
+                        return false;
+                    };
+                    float ka[U], kb[U];
+                    load_batch(ka, chunk * L);
+                    for (int tb = chunk * L; tb < t1; tb += 2 * U) {
+                        load_batch(kb, tb + U);
+                        if (work_batch(ka, tb)) break;
+                        load_batch(ka, tb + 2 * U);
+                        if (work_batch(kb, tb + U)) break;
                     }
                 }
                 // a synced channel ends the chunk where pass 2's chain ended; an unsynced one walked all of it
@@ -253,6 +275,23 @@ __global__ __launch_bounds__(256) void emit_entries_kernel(const T *__restrict__
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+int device_cu_count() {
+    static std::atomic<int> cached[64];                          // per device ordinal; 0 = not asked yet
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus > 0) return cus;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
 }
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s) {

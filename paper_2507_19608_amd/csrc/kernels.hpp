@@ -34,6 +34,8 @@ struct PrefillArgs {
     int ld = 0;                // > 0 (matrix-core path only): K, V, Khat, ents, counts have ld >= n rows of room per
                                // unit and nch8, plan, dense, vt the strides of prefill_mfma_n_pad(ld); 0: exactly n
     int vt_from = 0;           // blocks of 32 rows below this one are already in vt (V re-order of earlier rows kept)
+    int ksplit = 1;            // matrix-core path: work groups per tile (prefill_mfma_ksplit), each on a part of the keys
+    void *part = nullptr;      // ksplit > 1: prefill_mfma_part_bytes of scratch for the parts' results
     float scale_log2;     // score scale * log2(e)
     int rebase;           // 1: outside scores from q . k_hat instead of the entry lists
     int sliding;          // 1: exact region is the band i - j < W instead of squares of side W
@@ -72,5 +74,12 @@ bool launch_prefill_generic(const PrefillArgs &a, hipStream_t s);
 bool prefill_mfma_supported(const PrefillArgs &a);
 int prefill_mfma_n_pad(int n);
 void launch_prefill_mfma(const PrefillArgs &a, void *vt, hipStream_t s);
+// Key-range split of the matrix-core launch (flash-decoding style, for launches that do not fill the chip): the
+// number of work groups per tile that pays for these arguments on the current device (1: none; reads B, Hq, Hkv, d,
+// nq, q_off, fused, dtype) and the scratch that many need.
+int prefill_mfma_ksplit(const PrefillArgs &a);
+size_t prefill_mfma_part_bytes(const PrefillArgs &a, int ksplit);
+// compute units of the current device (256 if it cannot be asked)
+int device_cu_count();
 
 }  // namespace da

@@ -58,6 +58,10 @@ struct MfmaArgs {
     int q_off, nq;                      // query rows are positions q_off .. q_off + nq - 1 of the n keys
     int GH, RT, tiles, hgroups;         // heads per group chunk, rows per tile, row tiles, head chunks per unit
     int xsplit;                         // > 0: XCD-aware order, every unit split this many ways (see the kernel)
+    int ksplit;                         // >= 1: most work groups a tile gets, each on a part of the tile's key blocks
+    int parts_total;                    // sum over a unit's row tiles of TileGeometry::parts (= tiles when ksplit == 1)
+    float *__restrict__ part_o;         // ksplit > 1: [tile][ksplit][256][D] unnormalised outputs of the parts
+    float *__restrict__ part_ml;        //             [tile][ksplit][256][2] their running maximum and sum
     float scale_log2;
     // fused short-prompt launch only: what the stand-alone scan, compaction and V re-order kernels take
     const bf16_t *__restrict__ V;       // [unit][n][D] as the caller passed it
@@ -130,6 +134,40 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
                               (u32x4 *)(Vt + (size_t)unit * D * ld_pad) + (size_t)blk * (2 * MT * 64), blk * kTB, n, tile,
                               (int)threadIdx.x, [] { __syncthreads(); });
 }
+
+// A tile (kRows score rows: RT query rows from position i0 on, of GH heads) and how its key blocks are split.
+// Key blocks 0 .. far_blocks - 1 lie left of every row's window (gather mode only: they take the Eq. 4 gather), the
+// rest up to nblocks go through the matrix cores.  A launch may give every tile `ksplit` work groups ("parts"), each
+// on a contiguous range of the tile's blocks, whose unnormalised outputs a second launch merges (flash-decoding
+// style); that is done when a gather-mode launch has too few tiles to fill the chip.  A tile is cut into at most one
+// part per kSplitMinBlocks gather blocks, so short tiles are not cut at all and write their output themselves.  A gather part that does not start at block 0 starts its running
+// score from the dense product q . k_hat(j - 1) of the column before its first (Eq. 4 telescoped).
+constexpr int kSplitMinBlocks = 8;
+struct TileGeometry {
+    int i0, i_last;        // first and last query position
+    int win_first;         // smallest window start of the tile's rows
+    int far_blocks, nblocks;
+    int parts;             // work groups that share the tile (<= ksplit)
+};
+// (host and device: the launcher sizes the grid by the sum of `parts` over the tiles)
+__host__ __device__ inline TileGeometry tile_geometry_of(int q_off, int RT, int n, int W, int sliding, int ksplit,
+                                                         bool gather, int tile) {
+    TileGeometry g;
+    g.i0 = q_off + tile * RT;
+    g.i_last = g.i0 + RT - 1 < n - 1 ? g.i0 + RT - 1 : n - 1;
+    g.win_first = sliding ? (g.i0 - W + 1 > 0 ? g.i0 - W + 1 : 0) : (g.i0 / W) * W;
+    g.far_blocks = gather ? g.win_first / kTB : 0;
+    g.nblocks = g.i_last / kTB + 1;
+    const int cut = (gather ? g.far_blocks : g.nblocks) / kSplitMinBlocks;
+    g.parts = cut < 1 ? 1 : (cut < ksplit ? cut : ksplit);
+    return g;
+}
+template <bool kGather>
+__device__ __forceinline__ TileGeometry tile_geometry(const MfmaArgs &a, int tile) {
+    return tile_geometry_of(a.q_off, a.RT, a.n, a.W, a.sliding, a.ksplit, kGather, tile);
+}
+// blocks [lo, hi) of `count` blocks that part `seg` of `parts` takes
+__device__ __forceinline__ int part_begin(int count, int seg, int parts) { return (int)((long long)count * seg / parts); }
 
 // What the stand-alone scan, compaction and V re-order launches do for a unit, done by one work group of the fused
 // short-prompt kernel for the key rows 0 .. need - 1 that its own query rows see (512 threads; `lds` is scratch of
@@ -245,7 +283,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     //      divide by 8, units split `xsplit` ways by tile index modulo xsplit - one after the other: a unit's
     //      streams are then fetched into xsplit L2s instead of all 8.  Within a part, heavy (late) tiles first.
     int bid = blockIdx.x;
-    const int per_unit = a.tiles * a.hgroups;
+    const int per_unit = a.parts_total * a.hgroups;
     if (a.xsplit > 0) {
         const int xcd = bid & 7, slot = bid >> 3;
         const int per_part = per_unit / a.xsplit;            // work groups of one part
@@ -256,13 +294,26 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     const int unit = bid / per_unit;
     bid -= unit * per_unit;
     const int hchunk = bid % a.hgroups;
-    const int tile = a.tiles - 1 - bid / a.hgroups;
+    // The unit's parts are numbered tile by tile from the last (heaviest) tile down, a tile's parts in a row: every
+    // index of the grid is a part that exists (work groups that only find out that they have nothing to do still
+    // hold up the ones queued behind them when a launch has more of them than the chip has room for).
+    int tile = a.tiles - 1 - bid / a.hgroups, seg = 0;
+    if (a.ksplit > 1) {
+        int q = bid / a.hgroups;
+        for (tile = a.tiles - 1; tile > 0; --tile) {
+            const int p = tile_geometry<kGather>(a, tile).parts;
+            if (q < p) break;
+            q -= p;
+        }
+        seg = q;
+    }
     const int b = unit / a.Hkv, hk = unit % a.Hkv;
     const int g = a.Hq / a.Hkv;
     const int head0 = hk * g + hchunk * a.GH;
     const int n = a.n, W = a.W, RT = a.RT;
-    const int i0 = a.q_off + tile * RT;
-    const int i_last = min(n - 1, i0 + RT - 1);
+    const TileGeometry geo = tile_geometry<kGather>(a, tile);
+    const int i0 = geo.i0, i_last = geo.i_last;
+    if (seg >= geo.parts) return;                            // a short tile is not split as many ways as the launch allows
 
     const bf16_t *Kp = a.K + (size_t)unit * a.ld * D;
     const bf16_t *Hp = a.Khat + (size_t)unit * a.ld * D;
@@ -349,11 +400,32 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // of the one long sum does not grow with the prompt length (in binary32 it showed at ~130 000 columns).
     double r_run = 0.0;
 
-    const int win_first = win_start(i0);         // smallest window start of the tile's rows
+    const int win_first = geo.win_first;         // smallest window start of the tile's rows
     const int win_last = win_start(i_last);      // largest
     const bool aligned = kAligned || ((win_first % kTB == 0) && (win_first == win_last));
-    const int far_blocks = kGather ? win_first / kTB : 0;
-    const int nblocks = i_last / kTB + 1;
+    const int far_blocks = geo.far_blocks;
+    const int nblocks = geo.nblocks;
+    // this work group's part of the tile: gather blocks [f_lo, f_hi), matrix-core blocks [n_lo, n_hi)
+    const int f_lo = kGather ? part_begin(far_blocks, seg, geo.parts) : 0;
+    const int f_hi = kGather ? part_begin(far_blocks, seg + 1, geo.parts) : 0;
+    const int n_lo = kGather ? (seg == geo.parts - 1 ? far_blocks : nblocks) : part_begin(nblocks, seg, geo.parts);
+    const int n_hi = kGather ? nblocks : part_begin(nblocks, seg + 1, geo.parts);
+    if (kGather && f_lo > 0) {
+        // running score at the end of column 32 f_lo - 1, in the units of the gather (the Q tile's scale): bf16
+        // products are exact in binary32, the sum is taken in binary64
+        const bf16_t *hrow = Hp + (size_t)(f_lo * kTB - 1) * D;
+        double acc = 0.0;
+#pragma unroll 4
+        for (int c8 = 0; c8 < D / 8; ++c8) {
+            const u32x4 qv = *(const u32x4 *)(my_q + c8 * 8), hv = *(const u32x4 *)(hrow + c8 * 8);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc += (double)(__uint_as_float(qv[k] << 16) * __uint_as_float(hv[k] << 16));
+                acc += (double)(__uint_as_float(qv[k] & 0xffff0000u) * __uint_as_float(hv[k] & 0xffff0000u));
+            }
+        }
+        r_run = acc * (double)qmul;
+    }
 
     __syncthreads();   // Q tile staged
 
@@ -423,7 +495,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // a pair at the same time, a lane on 8 score rows: one two-address 16-byte LDS read fetches a piece of a chunk
     // of either column, one 16-byte q read per entry feeds 8 multiply-adds.  No scalar memory load sits in the
     // inner loop, so all its LDS traffic completes in order; the loop is software-pipelined two chunks deep.
-    if (kGather && far_blocks > 0) {
+    if (kGather && f_lo < f_hi) {
         const char *qtb = (const char *)qt;
         constexpr int kRingBytes = 4 * (D / kGroup) * 64 + 4 * 64;
         char *ring = lds_raw + kQtBytes + (size_t)kTB * kRows * 4 + (size_t)wave * kRingBytes;
@@ -434,7 +506,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         // .z = the block's re-based columns (the same word for every wave)
         typedef __attribute__((ext_vector_type(3))) uint32_t u32x3;
         auto pack_of = [&](int blk) -> u32x3 {
-            if (blk >= far_blocks) return u32x3{0u, 0u, 0u};
+            if (blk >= f_hi) return u32x3{0u, 0u, 0u};
             if constexpr (kFused) {
                 // written earlier by this very work group with vector stores: read back through the same (vector)
                 // cache, which sees them; the scalar cache need not
@@ -482,9 +554,9 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                                 (uint32_t)(lane & 31) * 16u;
         const uint32_t zero_addr = ring_lds + kZeroChunk * 64u;
 
-        u32x3 pk_cur = pack_of(0), pk_nxt = pack_of(1);
+        u32x3 pk_cur = pack_of(f_lo), pk_nxt = pack_of(f_lo + 1);
         u32x4 st[4];
-        g_issue(st, 0, pk_cur);
+        g_issue(st, f_lo, pk_cur);
 
         auto gather_block = [&](u32x3 pk) {
             uint32_t first = 0;                                  // first ring chunk of the pair's longer column
@@ -682,8 +754,8 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         uint32_t dm_prev = 0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) uu[r] = 0.f;
-        for (int blk = 0; blk < far_blocks; ++blk) {
-            if (blk > 0 && !late_s) {
+        for (int blk = f_lo; blk < f_hi; ++blk) {
+            if (blk > f_lo && !late_s) {
                 u32x4 vreg[2 * MT];
                 load_v(vreg, (blk - 1) * kTB);
                 scores_softmax_pv(blk - 1, uu, dm_prev, vreg);
@@ -696,7 +768,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             const uint32_t dm = pk[2];                           // re-based columns of this block (wave-uniform)
             if (dm) load_h_piece(blk);
             gather_block(pk);
-            if (blk > 0 && late_s) {
+            if (blk > f_lo && late_s) {
                 u32x4 vreg[2 * MT];
                 load_v(vreg, (blk - 1) * kTB);
                 scores_softmax_pv(blk - 1, uu, dm_prev, vreg);
@@ -713,8 +785,8 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         }
         {
             u32x4 vreg[2 * MT];
-            load_v(vreg, (far_blocks - 1) * kTB);
-            scores_softmax_pv(far_blocks - 1, uu, dm_prev, vreg);
+            load_v(vreg, (f_hi - 1) * kTB);
+            scores_softmax_pv(f_hi - 1, uu, dm_prev, vreg);
         }
     }
 
@@ -723,7 +795,7 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     // block are fetched once per work group, one 16-byte piece per thread, a block ahead into registers,
     // then parked in LDS in operand order (lane-contiguous 16-byte slots, conflict free) where all 8 waves
     // read them.  Three LDS buffers rotate (tiles are requested two blocks ahead); one barrier per block.
-    if (far_blocks < nblocks) {
+    if (n_lo < n_hi) {
         u32x4 qreg[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const u32x4 *)(my_q + ks * 16 + half * 8);
@@ -807,24 +879,24 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         // a copy nobody reads), so that the number of loads in flight is the same on every path and the wait
         // before a set is parked lets the younger set's loads stay in flight.
         Pieces pa, pb;
-        load_tiles(pa, far_blocks);
-        load_tiles(pb, min(far_blocks + 1, nblocks - 1));
+        load_tiles(pa, n_lo);
+        load_tiles(pb, min(n_lo + 1, n_hi - 1));
         lds_barrier();                                           // the far loop's LDS use is over
         store_tiles(pa, 0);
-        load_tiles(pa, min(far_blocks + 2, nblocks - 1));
+        load_tiles(pa, min(n_lo + 2, n_hi - 1));
         lds_barrier();
         float s_a[16], s_b[16];                                  // raw scores of the current / the next block, in turn
         const char *lane_tiles = tiles + lane * 16;              // per-lane view of the tile buffers
-        block_scores(s_a, lane_tiles, far_blocks * kTB);
+        block_scores(s_a, lane_tiles, n_lo * kTB);
         int buf = 0;
         // one block: `next` holds the pieces of block blk + 1, s_cur this block's scores, s_next receives the next one's
         auto do_block = [&](int blk, Pieces &next, float (&s_cur)[16], float (&s_next)[16]) {
             const char *base = lane_tiles + buf * (3 * kTileBytes);
             const int nbuf = buf == 2 ? 0 : buf + 1;
             store_tiles(next, nbuf);
-            load_tiles(next, min(blk + 3, nblocks - 1));         // in flight for two iterations
+            load_tiles(next, min(blk + 3, n_hi - 1));            // in flight for two iterations
             lds_barrier();                                       // LDS only: the tile loads stay in flight
-            if (blk + 1 < nblocks) block_scores(s_next, lane_tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
+            if (blk + 1 < n_hi) block_scores(s_next, lane_tiles + nbuf * (3 * kTileBytes), (blk + 1) * kTB);
             u32x4 vreg[2 * MT];
 #pragma unroll
             for (int k = 0; k < 2 * MT; ++k) vreg[k] = *(const u32x4 *)(base + 2 * kTileBytes + k * 1024);
@@ -834,14 +906,31 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         // everything requested so far has landed before the loop is entered: the wait at its head then only has to
         // cover what the previous trip left in flight (the compiler sizes it for the worse of both ways in)
         __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0)
-        for (int blk = far_blocks; blk < nblocks; blk += 2) {
+        for (int blk = n_lo; blk < n_hi; blk += 2) {
             do_block(blk, pb, s_a, s_b);
-            if (blk + 1 < nblocks) do_block(blk + 1, pa, s_b, s_a);
+            if (blk + 1 < n_hi) do_block(blk + 1, pa, s_b, s_a);
         }
     }
 
     // ---------------------------------------------------------------- epilogue
     const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (geo.parts > 1) {
+        // one part of a split tile: unnormalised output rows, running maximum and sum for prefill_merge_kernel
+        // (rows past the end of the sequence are written too, as they stand, and never read: the stores stay whole)
+        // Pieces of 4 channels in the order the accumulators hold them - piece (wave, mt, q4, lane) = score row
+        // 32 wave + lane % 32, channels 32 mt + 8 q4 + 4 (lane / 32) .. + 3 - so that every store instruction of a
+        // wave writes 1 KiB in one run.
+        const size_t slot = ((size_t)(unit * a.hgroups + hchunk) * a.tiles + tile) * a.ksplit + seg;
+        f32x4 *po = (f32x4 *)(a.part_o + slot * kRows * D) + (size_t)wave * (MT * 4 * 64) + lane;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                po[(mt * 4 + q4) * 64] = f32x4{oacc[mt][4 * q4 + 0], oacc[mt][4 * q4 + 1], oacc[mt][4 * q4 + 2],
+                                               oacc[mt][4 * q4 + 3]};
+        if (half == 0) *(f32x2 *)(a.part_ml + (slot * kRows + my_sr) * 2) = f32x2{m_run, l_tot};
+        return;
+    }
     if (my_valid) {
         const float inv = 1.f / l_tot;
         bf16_t *orow = a.O + (((size_t)b * a.Hq + head0 + my_hh) * a.nq + (my_i - a.q_off)) * D;
@@ -855,6 +944,67 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
                 *(u32x2 *)(orow + mt * 32 + 8 * q4 + 4 * half) = w;
             }
     }
+}
+
+// Second launch of a split attention launch: the parts of every tile that was cut (TileGeometry::parts > 1) are
+// merged flash-decoding style - with M the largest running maximum, O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s -
+// and the output rows written.  One work group per (tile, wave slab of 32 score rows); a thread on pieces of 4
+// channels, all parts of a piece loaded at once (indices clamped, the surplus weighted 0: no load sits under a
+// condition, so they are all in flight together).
+constexpr int kMaxSplit = 8;
+template <int D, bool kGather>
+__global__ __launch_bounds__(256) void prefill_merge_kernel(MfmaArgs a) {
+    constexpr int MT = D / 32, kSlab = MT * 4 * 64;          // pieces of one wave's 32 score rows
+    const int t = blockIdx.x / kWaves, wv = blockIdx.x % kWaves;   // t = (unit * hgroups + hchunk) * tiles + tile
+    const int tile = t % a.tiles, uh = t / a.tiles, hchunk = uh % a.hgroups, unit = uh / a.hgroups;
+    const TileGeometry geo = tile_geometry<kGather>(a, tile);
+    if (geo.parts <= 1) return;                              // that tile's one work group has written its rows itself
+    const int b = unit / a.Hkv, hk = unit % a.Hkv, g = a.Hq / a.Hkv, head0 = hk * g + hchunk * a.GH;
+    const float *po = a.part_o + (size_t)t * a.ksplit * kRows * D;
+    const float *pml = a.part_ml + (size_t)t * a.ksplit * kRows * 2;
+    for (int k = threadIdx.x; k < kSlab; k += 256) {
+        // piece of a part's output, in the order the attention kernel stored it (see its epilogue)
+        const int idx = wv * kSlab + k, ln = k & 63, slot = k >> 6;
+        const int sr = 32 * wv + (ln & 31), ch = 32 * (slot >> 2) + 8 * (slot & 3) + 4 * (ln >> 5);
+        const int hh = sr / a.RT, i = geo.i0 + sr - hh * a.RT;
+        f32x2 ml[kMaxSplit];
+        f32x4 o[kMaxSplit];
+#pragma unroll
+        for (int p = 0; p < kMaxSplit; ++p) {
+            const size_t pe = (size_t)min(p, geo.parts - 1);
+            ml[p] = *(const f32x2 *)(pml + (pe * kRows + sr) * 2);
+            o[p] = *(const f32x4 *)(po + pe * kRows * D + (size_t)idx * 4);
+        }
+        if (i >= a.n) continue;
+        float M = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < kMaxSplit; ++p)
+            if (p < geo.parts) M = fmaxf(M, ml[p][0]);
+        float L = 0.f;
+        f32x4 O = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int p = 0; p < kMaxSplit; ++p) {
+            // (part 0 holds key 0, which every row sees: M is finite; a part none of whose keys a row sees has m = -inf)
+            const float w = (p >= geo.parts || ml[p][0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[p][0] - M);
+            L = w == 0.f ? L : fmaf(w, ml[p][1], L);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) O[e] = w == 0.f ? O[e] : fmaf(w, o[p][e], O[e]);   // (unread rows may hold anything)
+        }
+        const float inv = 1.f / L;
+        u32x2 w2;
+        w2[0] = pack_bf16x2(O[0] * inv, O[1] * inv);
+        w2[1] = pack_bf16x2(O[2] * inv, O[3] * inv);
+        *(u32x2 *)(a.O + (((size_t)b * a.Hq + head0 + hh) * a.nq + (i - a.q_off)) * D + ch) = w2;
+    }
+}
+
+// tiles of a launch: row tiles x head chunks x units; GH heads of RT rows make a tile's kRows score rows
+static void tile_counts(const PrefillArgs &p, int &GH, int &RT, int &tiles, int &hgroups) {
+    const int g = p.Hq / p.Hkv;
+    GH = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
+    RT = kRows / GH;
+    tiles = (p.nq + RT - 1) / RT;
+    hgroups = g / GH;
 }
 
 template <int D>
@@ -888,14 +1038,17 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     a.W = p.W;
     a.rebase = p.rebase;
     a.sliding = p.sliding;
-    const int g = p.Hq / p.Hkv;
-    a.GH = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
-    a.RT = kRows / a.GH;
+    tile_counts(p, a.GH, a.RT, a.tiles, a.hgroups);
     a.q_off = p.q_off;
     a.nq = p.nq;
-    a.tiles = (p.nq + a.RT - 1) / a.RT;
-    a.hgroups = g / a.GH;
     a.scale_log2 = p.scale_log2;
+    a.ksplit = (!p.fused && !p.rebase && p.ksplit > 1 && p.part) ? p.ksplit : 1;
+    a.parts_total = 0;
+    for (int t = 0; t < a.tiles; ++t)
+        a.parts_total += tile_geometry_of(a.q_off, a.RT, a.n, a.W, a.sliding, a.ksplit, !p.rebase, t).parts;
+
+    a.part_o = (float *)p.part;
+    a.part_ml = a.part_o + (size_t)units * a.tiles * a.hgroups * a.ksplit * kRows * D;
     const size_t lds_far = (size_t)kTB * kRows * 4 + (size_t)kWaves * (4 * (D / kGroup) * 64 + 4 * 64) +
                            (size_t)2 * D * 64;                  // u exchange, entry rings, two fp16 K_hat tiles
     const size_t lds_near = (size_t)9 * D * 64;
@@ -912,12 +1065,12 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, true, true>, (int)lds_gather, lds_set[1]);
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, false>, (int)lds_near, lds_set[2]);
     ensure_dynamic_lds((const void *)prefill_mfma_kernel<D, false, true>, (int)lds_near, lds_set[3]);
-    const size_t blocks = (size_t)units * a.tiles * a.hgroups;
+    const size_t blocks = (size_t)units * a.parts_total * a.hgroups;
     // XCD-aware order needs units * xsplit parts to deal out evenly over 8 XCDs and a unit to split evenly
     a.xsplit = 0;
     for (int sp = 1; sp <= 8; sp *= 2)
         if ((units * sp) % 8 == 0) {
-            if ((a.tiles * a.hgroups) % sp == 0 && sp < 8) a.xsplit = sp;
+            if ((a.parts_total * a.hgroups) % sp == 0 && sp < 8) a.xsplit = sp;
             break;
         }
     // every tile's rows (RT consecutive positions from q_off on) lie in one window square whose start is a multiple
@@ -936,6 +1089,34 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
         hipLaunchKernelGGL((prefill_mfma_kernel<D, true, true>), grid, block, lds_gather, s, a);
     else
         hipLaunchKernelGGL((prefill_mfma_kernel<D, true, false>), grid, block, lds_gather, s, a);
+    if (a.ksplit > 1) {
+        const dim3 mgrid((unsigned)(units * a.tiles * a.hgroups * kWaves));
+        if (p.rebase)
+            hipLaunchKernelGGL((prefill_merge_kernel<D, false>), mgrid, dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((prefill_merge_kernel<D, true>), mgrid, dim3(256), 0, s, a);
+    }
+}
+
+// A launch with fewer than four tiles per compute unit is cut along the keys, as many ways (a power of two, at most
+// 8) as bring it there; never more parts than the longest tile has runs of kSplitMinBlocks key blocks.
+int prefill_mfma_ksplit(const PrefillArgs &p) {
+    if (p.fused || p.rebase || !prefill_mfma_supported(p)) return 1;   // (matrix-core blocks are too cheap to pay for it)
+    int GH, RT, tiles, hgroups;
+    tile_counts(p, GH, RT, tiles, hgroups);
+    const long long groups = (long long)p.B * p.Hkv * tiles * hgroups, want = 4LL * device_cu_count();
+    int ks = 1;
+    while (ks < kMaxSplit && groups * ks < want) ks *= 2;
+    const int longest = (p.q_off + p.nq - 1) / kTB + 1;      // key blocks of the last tile
+    while (ks > 1 && longest / kSplitMinBlocks < ks) ks /= 2;
+    return ks;
+}
+
+size_t prefill_mfma_part_bytes(const PrefillArgs &p, int ksplit) {
+    if (ksplit <= 1) return 0;
+    int GH, RT, tiles, hgroups;
+    tile_counts(p, GH, RT, tiles, hgroups);
+    return (size_t)p.B * p.Hkv * tiles * hgroups * ksplit * kRows * (p.d + 2) * sizeof(float);
 }
 
 int prefill_mfma_n_pad(int n) { return (n + 63) / 64 * 64; }

@@ -649,6 +649,22 @@ def test_rebased_full_columns(window_mode, d, Hq, Hkv, n, W, p_jump, theta):
     run_case(Q, K, V, theta, W, "bf16", da.DA_SCORE_GATHER, window_mode=window_mode)
 
 
+@pytest.mark.parametrize("window_mode", [da.DA_WINDOW_BLOCK, da.DA_WINDOW_SLIDING])
+@pytest.mark.parametrize("B,Hq,Hkv,n,d,W,theta", [
+    (1, 4, 2, 1777, 64, 100, 0.15),     # 28 tiles of 128 rows x 2 heads: cut up to 4 ways, ragged last tile and block
+    (1, 2, 1, 2500, 128, 32, 0.2),      # 10 tiles of 256 rows: up to 8 parts per tile, short first tiles uncut
+    (2, 8, 2, 1100, 128, 300, 0.1),     # windows wider than a part: late tiles have few gather blocks, early ones none
+    (1, 1, 1, 3000, 64, 64, 0.0),       # one head; every column full, so parts also re-base columns inside them
+])
+def test_small_launches_cut_along_the_keys(window_mode, B, Hq, Hkv, n, d, W, theta):
+    """A gather-mode launch with too few row tiles to fill the chip gives every long tile several work groups, each on
+    a range of its key blocks (a part that does not start at key 0 starts its running Eq. 4 score from q . k_hat of
+    the column before, exact by the telescoped sum), and a second launch merges their partial softmax results.  The
+    outputs are still those of the oracle's column-by-column recursion, for every row; masks and nnz bit-exact."""
+    Q, K, V = rand_walk(131, B, Hq, n, d), rand_walk(132, B, Hkv, n, d), rand_walk(133, B, Hkv, n, d, clip=3.5)
+    run_case(Q, K, V, theta, W, "bf16", da.DA_SCORE_GATHER, window_mode=window_mode)
+
+
 def test_rebase_is_skipped_for_keys_beyond_fp16():
     """The re-base tile is taken in fp16; a block whose reference keys do not fit (|k| >= 2^15) keeps gathering its
     full columns in binary32.  Keys of 5e4 in part of the prompt, every column full (theta = 0): results still match."""

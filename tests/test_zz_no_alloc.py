@@ -1,6 +1,8 @@
 """delta_attn_prefill_noalloc (the entry point for callers that cannot allocate: its scratch is a buffer built into
-the library's device image) against delta_attn_prefill on the same inputs: same kernels, so masks, nnz and outputs
-must be bit-identical; one case is also held against the oracle.  Two calls in a row share the one buffer - the
+the library's device image) against delta_attn_prefill on the same inputs: same kernels, so masks and nnz must be
+bit-identical and so must the outputs - except where delta_attn_prefill cuts a small launch along the keys and the
+built-in buffer has no room for the parts' results: the two then differ in rounding order, each inside the output
+tolerance of the oracle, against which both calls are held as well.  Two calls in a row share the one buffer - the
 second, smaller prompt must not see anything of the first."""
 import numpy as np
 import pytest
@@ -39,13 +41,14 @@ def test_noalloc_equals_prefill_on_two_calls_in_a_row(mode, dtype, d):
         # no allocation request reached torch's allocator during the call either (the binding marshals only)
         assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == allocs
         torch.cuda.synchronize()
-        for g, w_ in zip(got, want):
-            assert torch.equal(g, w_), (k, dtype, d)
-        if k == 1:                                               # and the shared result is the oracle's
-            ref = orc.prefill(Q, K, V, theta, W)
-            assert (unpack_mask(got[1], d) == ref["mask"]).all() and (got[2].cpu().numpy() == ref["nnz"]).all()
-            for h in range(Hq):
-                check_output(got[0][:, h], ref["O"][:, h], dtype)
+        assert torch.equal(got[1], want[1]) and torch.equal(got[2], want[2]), (k, dtype, d)
+        if k == 1 or dtype == "f32":                             # one work group per tile in both: the same arithmetic
+            assert torch.equal(got[0], want[0]), (k, dtype, d)
+        check_output(got[0], want[0].double().cpu().numpy(), dtype)
+        ref = orc.prefill(Q, K, V, theta, W)                     # and the results are the oracle's
+        assert (unpack_mask(got[1], d) == ref["mask"]).all() and (got[2].cpu().numpy() == ref["nnz"]).all()
+        for h in range(Hq):
+            check_output(got[0][:, h], ref["O"][:, h], dtype)
 
 
 def test_noalloc_rejects_a_prompt_beyond_its_scratch():
@@ -59,7 +62,8 @@ def test_noalloc_rejects_a_prompt_beyond_its_scratch():
 @pytest.mark.parametrize("n,d", [(200, 64), (1500, 128)])
 def test_noalloc_replays_from_a_captured_graph(n, d):
     """The callers it is for: captured into a HIP graph (after one eager call that did the one-time set-up), replayed
-    with eager work and synchronisations in between; every replay must reproduce delta_attn_prefill bit for bit.
+    with eager work and synchronisations in between; every replay must reproduce the eager call bit for bit (and
+    delta_attn_prefill's masks and nnz; its outputs to the tolerance, see above).
     200 tokens take the fused single launch, 1500 the launch-per-stage path (whose counters are cleared by a fill
     kernel, not by a memset node)."""
     B, Hq, Hkv, W, theta = 2, 4, 2, 32, 0.15
@@ -69,6 +73,9 @@ def test_noalloc_replays_from_a_captured_graph(n, d):
     out = _outs(Qd, Kd)
     da.delta_attn_prefill_noalloc(Qd, Kd, Vd, theta, W, out)     # eager first call: symbol look-up, LDS limits
     torch.cuda.synchronize()
+    eager = [t.clone() for t in out]
+    assert torch.equal(eager[1], want[1]) and torch.equal(eager[2], want[2])
+    check_output(eager[0], want[0].double().cpu().numpy(), "bf16")
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         da.delta_attn_prefill_noalloc(Qd, Kd, Vd, theta, W, out)
@@ -78,5 +85,5 @@ def test_noalloc_replays_from_a_captured_graph(n, d):
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for g, w_ in zip(out, want):
+        for g, w_ in zip(out, eager):
             assert torch.equal(g, w_), rep
