@@ -291,8 +291,13 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         const int within = slot % per_part;
         bid = (part / a.xsplit) * per_unit + within * a.xsplit + part % a.xsplit;
     }
-    const int unit = bid / per_unit;
-    bid -= unit * per_unit;
+    // Without the XCD-aware order, a launch that is cut along the keys (few, long tiles) deals its work groups out
+    // heaviest first across all units - unit after unit, the heavy tiles of the last unit would start last; an uncut
+    // launch goes unit after unit, so that all its work groups stream the same unit's tiles at a time.
+    const int units = gridDim.x / per_unit;
+    const bool across = a.xsplit == 0 && a.ksplit > 1;
+    const int unit = across ? bid % units : bid / per_unit;
+    bid = across ? bid / units : bid - unit * per_unit;
     const int hchunk = bid % a.hgroups;
     // The unit's parts are numbered tile by tile from the last (heaviest) tile down, a tile's parts in a row: every
     // index of the grid is a part that exists (work groups that only find out that they have nothing to do still
