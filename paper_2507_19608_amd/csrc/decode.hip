@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *
 template <typename T>
 __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *__restrict__ q_new, int t,
                                                           float scale_log2) {
-    extern __shared__ float lds_f[];
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];   // (16-byte accesses below, whatever static LDS precedes it)
     float *lds = lds_f;
     const int d = c.d, wpr = d >> 5;
     const int ldk = d + 1;
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
                                                               const bf16_t *__restrict__ v_new,
                                                               uint32_t *__restrict__ mask_row, int t,
                                                               float scale_log2) {
-    extern __shared__ float lds_f[];
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];   // (16-byte accesses below, whatever static LDS precedes it)
     char *lds = (char *)lds_f;
     const int d = DT ? DT : c.d, wpr = d >> 5;
     const int nw = (d + kWave - 1) / kWave;

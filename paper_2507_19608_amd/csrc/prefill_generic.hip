@@ -27,7 +27,7 @@ struct KArgs {
 
 template <typename T, int D>
 __global__ __launch_bounds__(64) void prefill_generic_kernel(KArgs<T> a) {
-    extern __shared__ float qt[];   // [D][64]: qt[c * 64 + lane] = q_row(lane)[c]
+    extern __shared__ __attribute__((aligned(16))) float qt[];   // [D][64]: qt[c * 64 + lane] = q_row(lane)[c]
     const int lane = threadIdx.x;
     const int tiles = (a.nq + 63) / 64;
     const int tile = tiles - 1 - (int)blockIdx.x;   // longest rows first

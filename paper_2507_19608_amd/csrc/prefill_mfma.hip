@@ -267,7 +267,10 @@ __device__ __forceinline__ void fused_prepare(const MfmaArgs &a, int unit, int n
 // prompts: one launch instead of seven; see fused_prepare), and reads its gather plans with vector loads.
 template <int D, bool kGather, bool kAligned, bool kFused = false>
 __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
-    extern __shared__ char lds_raw[];
+    // (aligned explicitly: the dynamic region starts where the static variables below end, and every tile and ring
+    // in it is accessed with 16-byte instructions - at an offset that was not a multiple of 16 the far loop ran seven
+    // times slower)
+    extern __shared__ __attribute__((aligned(256))) char lds_raw[];
     constexpr size_t kQtBytes = kGather ? (size_t)D * kRows * 2 : 0;
     _Float16 *qt = (_Float16 *)lds_raw;                                   // [D][256] fp16, scaled by 2^qexp
     float *ubuf = (float *)(lds_raw + kQtBytes);                          // [kTB][256]; then 8 entry rings
