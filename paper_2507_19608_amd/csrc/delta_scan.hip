@@ -245,7 +245,8 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
 // only if every reference key of the block fits fp16, the tile's operand format.  Re-based columns get chunk count 0
 // in the plan and their bit set in the block's word of `dense` ([units][n_pad / 32]).  The other
 // columns are ranked by chunk count (ties: lower index first), neighbours in that order form the 16 pairs (so the two
-// columns of a pair have nearly the same length), and wave w takes pairs w and 15 - w (long with short).  A wave's 8
+// columns of a pair have nearly the same length), and every wave is dealt two pairs so that the four SIMDs carry
+// nearly equal numbers of gather steps (plan_block).  A wave's 8
 // bytes: the four column indices (first pair, longer column first; second pair), then their chunk counts; blocks that
 // reach past row n get zero counts and no dense bits (that kernel only gathers in blocks left of every row's window).
 // Which wave sums a column does not change the sum.

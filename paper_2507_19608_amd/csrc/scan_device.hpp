@@ -220,8 +220,35 @@ __device__ __forceinline__ void plan_block(const uint32_t *blk_cnt, uint8_t *pla
     }
     if (!whole) rank = (uint32_t)c;
     const uint32_t pair = rank >> 1;
-    const uint32_t wv = pair < (uint32_t)kPlanWaves ? pair : 15u - pair;
-    const uint32_t slot = (pair < (uint32_t)kPlanWaves ? 0u : 2u) + (rank & 1u);
+    // The pairs go, longest first, to the wave whose SIMD has the fewest gather steps so far (waves w and w + 4 of the
+    // 8 share a SIMD and its vector ALU; ties: the wave with fewer steps, then the lower index), two pairs per wave.
+    // A whole-vector jump of the key stream - a column of d / 8 chunks among columns a third as long - then lands on a
+    // SIMD whose other pairs are short.  (Dealt by rank alone, pairs w and 15 - w to wave w: 8.25 instead of 8.09 ms on
+    // the 8K workload; treating waves w and w ^ 1 as SIMD partners instead: 8.38 ms.)
+    // (lane w < 8 keeps wave w's tally; the choice is a minimum over those 8 lanes)
+    uint32_t steps_mine = 0, pairs_mine = 0;                 // of wave `lane & 7`
+    uint32_t wv = 0, nth = 0;                                // this lane's column: its wave, first or second pair there
+    for (int r = 0; r < kCols / 2; ++r) {
+        // steps of pair r = chunk count of its longer column, the one of rank 2 r
+        const uint64_t holder = __ballot(lane < kCols && rank == (uint32_t)(2 * r));
+        const uint32_t a = (uint32_t)__shfl((int)mine, (int)__builtin_ctzll(holder | (1ull << 63)));
+        const uint32_t partner = (uint32_t)__shfl_xor((int)steps_mine, kPlanWaves / 2);
+        uint32_t key = pairs_mine < 2u ? ((steps_mine + partner) << 16) | (steps_mine << 4) | (uint32_t)(lane & (kPlanWaves - 1))
+                                       : 0xffffffffu;
+#pragma unroll
+        for (int sft = 1; sft < kPlanWaves; sft <<= 1) key = min(key, (uint32_t)__shfl_xor((int)key, sft));
+        const uint32_t best = key & (uint32_t)(kPlanWaves - 1);
+        const uint32_t had = (uint32_t)__shfl((int)pairs_mine, (int)best);
+        if (pair == (uint32_t)r) {
+            wv = best;
+            nth = had;
+        }
+        if ((uint32_t)(lane & (kPlanWaves - 1)) == best) {
+            steps_mine += a;
+            pairs_mine += 1u;
+        }
+    }
+    const uint32_t slot = 2u * nth + (rank & 1u);
     if (lane < kCols) {
         uint8_t *out = plan_out + wv * 8;
         out[slot] = (uint8_t)c;
