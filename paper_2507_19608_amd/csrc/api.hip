@@ -377,6 +377,7 @@ da_status check_append(const da_prefill_params *p, const da_cache *c) {
     // than the sequence is long
     const int64_t reach = p->window < c->len + p->seq_len ? p->window : c->len + p->seq_len;
     if (c->len > 0 && reach > c->Wd) return DA_ERR_UNSUPPORTED;
+    if (!prefill_mfma_supported(split_args(p, c->len))) return DA_ERR_UNSUPPORTED;   // (more tiles than a grid holds)
     return DA_OK;
 }
 }  // namespace
@@ -481,9 +482,8 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     a.mask_bits = nullptr;
     a.nnz = nullptr;
     a.theta = p->theta;
-    if (!prefill_mfma_supported(a)) return DA_ERR_UNSUPPORTED;
     stage_begin(kStageAttn, s);
-    launch_prefill_mfma(a, f->vt, s);
+    launch_prefill_mfma(a, f->vt, s);                  // (supported: check_append has asked)
     stage_end(kStageAttn, s);
     if (!launch_ok("prefill_append attention")) return DA_ERR_HIP;
     // 5. the new rows join the cache

@@ -166,7 +166,8 @@ __global__ __launch_bounds__(64) void decode_append_kernel(da_cache c, const T *
 template <typename T>
 __global__ __launch_bounds__(64) void decode_chunk_kernel(da_cache c, const T *__restrict__ q_new, int t,
                                                           float scale_log2) {
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];   // (16-byte accesses below, whatever static LDS precedes it)
+    // (16-byte accesses below, whatever static LDS precedes it)
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
     float *lds = lds_f;
     const int d = c.d, wpr = d >> 5;
     const int ldk = d + 1;
@@ -333,7 +334,8 @@ __global__ __launch_bounds__(64) void decode_step_bf16_kernel(da_cache c, const 
                                                               const bf16_t *__restrict__ v_new,
                                                               uint32_t *__restrict__ mask_row, int t,
                                                               float scale_log2) {
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];   // (16-byte accesses below, whatever static LDS precedes it)
+    // (16-byte accesses below, whatever static LDS precedes it)
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
     char *lds = (char *)lds_f;
     const int d = DT ? DT : c.d, wpr = d >> 5;
     const int nw = (d + kWave - 1) / kWave;

@@ -93,8 +93,9 @@ __global__ __launch_bounds__(64) void seal_from_ring_kernel(da_cache c, int chun
 
 // Hand-off of prefilled rows to the cache (Sec. III-C): rows t0 .. n_k - 1 (t0 = rows the cache already
 // holds) are appended; one wave per (chunk that contains such a row, unit).  Kfull, Hfull, Mfull describe the
-// whole sequence [units][ld][...] (ld >= n_k rows of room per unit): keys (for rows the decode window no longer holds raw, the reference key
-// stands in - the two agree wherever a mask bit is set, which is all that is read), reference keys, mask
+// whole sequence [units][ld][...] (ld >= n_k rows of room per unit): keys (for rows the decode window no longer
+// holds raw, the reference key stands in - the two agree wherever a mask bit is set, which is all that is read),
+// reference keys, mask
 // rows; Vnew [units][n_k - t0][d] the new value rows.  With t0 = 0 these are the prefill's own arrays.
 __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__restrict__ Kfull,
                                                              const bf16_t *__restrict__ Vnew,

@@ -107,8 +107,8 @@ int timing_collect(double *ms_per_stage, int *calls_per_stage) {
 // So time is cut into chunks that are scanned in parallel from a guessed incoming state:
 //
 //   pass 1  (one wave per (unit, 64 channels, time chunk)): chunk 0 starts from the basis row (or, when the
-//           rows continue a sequence, from the reference key `init` carried over from it) and is exact.  Chunk c > 0 starts from the guess "held = k(t0 - 1)" and records only its final
-//           held value.  That final value is already the true one for every channel that fired at
+//           rows continue a sequence, from the reference key `init` carried over from it) and is exact.
+//           Chunk c > 0 starts from the guess "held = k(t0 - 1)" and records only its final held value.  That final value is already the true one for every channel that fired at
 //           least once inside the chunk at a row where the true chain fired too - nearly all.
 //   pass 2  same scan, but chunk c starts from pass 1's final value of chunk c - 1, and writes mask
 //           words, held keys, nnz and its own final values.

@@ -140,8 +140,9 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
 // rest up to nblocks go through the matrix cores.  A launch may give every tile `ksplit` work groups ("parts"), each
 // on a contiguous range of the tile's blocks, whose unnormalised outputs a second launch merges (flash-decoding
 // style); that is done when a gather-mode launch has too few tiles to fill the chip.  A tile is cut into at most one
-// part per kSplitMinBlocks gather blocks, so short tiles are not cut at all and write their output themselves.  A gather part that does not start at block 0 starts its running
-// score from the dense product q . k_hat(j - 1) of the column before its first (Eq. 4 telescoped).
+// part per kSplitMinBlocks gather blocks, so short tiles are not cut at all and write their output themselves.  A
+// gather part that does not start at block 0 starts its running score from the dense product q . k_hat(j - 1) of the
+// column before its first (Eq. 4 telescoped).
 constexpr int kSplitMinBlocks = 8;
 struct TileGeometry {
     int i0, i_last;        // first and last query position
