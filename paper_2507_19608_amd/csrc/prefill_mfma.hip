@@ -348,16 +348,23 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
     if constexpr (kGather) {
         // ---- stage the Q tile: per-tile power-of-two scale so that the fp16 copy neither overflows nor
         //      loses bits that matter (|q| max lands in [2^14, 2^15)).
+        //      The tile is read once: a thread keeps its pieces (score row idx % 256, 8 channels) in registers from
+        //      the pass that finds the maximum to the pass that scales and stores them.
+        constexpr int kQPer = kRows * (D / 8) / 512;             // 16-byte pieces per thread
+        u32x4 raw[kQPer];
         float amax = 0.f;
-        for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
-            const int sr = idx / (D / 8), c8 = idx % (D / 8);
-            const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
-    #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] << 16)));
-                amax = fmaxf(amax, fabsf(__uint_as_float(raw[k] & 0xffff0000u)));
-            }
+#pragma unroll
+        for (int p = 0; p < kQPer; ++p) {
+            const int idx = tid + p * 512, sr = idx % kRows, c8 = idx / kRows;   // consecutive threads -> consecutive score rows
+            raw[p] = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
         }
+#pragma unroll
+        for (int p = 0; p < kQPer; ++p)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                amax = fmaxf(amax, fabsf(__uint_as_float(raw[p][k] << 16)));
+                amax = fmaxf(amax, fabsf(__uint_as_float(raw[p][k] & 0xffff0000u)));
+            }
     #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) amax = fmaxf(amax, __shfl_xor(amax, s));
         if (lane == 0) red[wave] = amax;
@@ -371,13 +378,13 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
             qexp = 14 - e;
         }
         qmul = __uint_as_float((uint32_t)(min(max(qexp, -126), 127) + 127) << 23);
-        for (int idx = tid; idx < kRows * (D / 8); idx += 512) {
-            const int sr = idx % kRows, c8 = idx / kRows;    // consecutive threads -> consecutive score rows
-            const u32x4 raw = *(const u32x4 *)(q_row_ptr(sr) + c8 * 8);
+#pragma unroll
+        for (int p = 0; p < kQPer; ++p) {
+            const int idx = tid + p * 512, sr = idx % kRows, c8 = idx / kRows;
     #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float lo = __uint_as_float(raw[k] << 16) * qmul;
-                const float hi = __uint_as_float(raw[k] & 0xffff0000u) * qmul;
+                const float lo = __uint_as_float(raw[p][k] << 16) * qmul;
+                const float hi = __uint_as_float(raw[p][k] & 0xffff0000u) * qmul;
                 qt[(c8 * 8 + 2 * k) * kRows + sr] = (_Float16)lo;
                 qt[(c8 * 8 + 2 * k + 1) * kRows + sr] = (_Float16)hi;
             }
