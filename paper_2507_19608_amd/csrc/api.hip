@@ -401,7 +401,6 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     const int units = p->batch * p->n_kv_heads;
-    const size_t row = (size_t)d * 2, mrow = (size_t)(d / 32) * 4;
     const bool gather = p->score_mode == DA_SCORE_GATHER;
     (void)hipGetLastError();
     st = ensure_prefix(cache, gather);
@@ -418,27 +417,13 @@ da_status delta_attn_prefill_append(const da_prefill_params *p, const void *Q, c
         expand_cache_runs(cache, t0, ld, f->k, f->h, f->v, f->m, s);
         f->ent_rows = 0;
     }
-    if (hipMemcpy2DAsync((char *)f->k + (size_t)t0 * row, (size_t)ld * row, K, (size_t)m * row, (size_t)m * row, units,
-                         hipMemcpyDeviceToDevice, s) != hipSuccess ||
-        hipMemcpy2DAsync((char *)f->v + (size_t)t0 * row, (size_t)ld * row, V, (size_t)m * row, (size_t)m * row, units,
-                         hipMemcpyDeviceToDevice, s) != hipSuccess)
-    {
-        (void)launch_ok("prefill_append copy");   // records the error text
-        return DA_ERR_HIP;
-    }
-    // 2. Eq. 2-3 over the new rows, continuing from the cache's reference key (row 0 of an empty cache is the basis)
+    // 2. Eq. 2-3 over the new rows, continuing from the cache's reference key (row 0 of an empty cache is the basis);
+    //    the new rows (keys, values, reference keys, mask rows) go behind the cached ones
     stage_begin(kStageScan, s);
     launch_delta_scan(p->dtype, K, ws + w.hnew, mask_bits, ws + w.chunk_out, nnz, units, m, d, p->theta, s,
                       t0 > 0 ? cache->khat : nullptr);
+    launch_append_rows(K, V, ws + w.hnew, mask_bits, f->k, f->v, f->h, f->m, units, t0, m, ld, d, s);
     stage_end(kStageScan, s);
-    if (hipMemcpy2DAsync((char *)f->h + (size_t)t0 * row, (size_t)ld * row, ws + w.hnew, (size_t)m * row,
-                         (size_t)m * row, units, hipMemcpyDeviceToDevice, s) != hipSuccess ||
-        hipMemcpy2DAsync((char *)f->m + (size_t)t0 * mrow, (size_t)ld * mrow, mask_bits, (size_t)m * mrow,
-                         (size_t)m * mrow, units, hipMemcpyDeviceToDevice, s) != hipSuccess)
-    {
-        (void)launch_ok("prefill_append copy");   // records the error text
-        return DA_ERR_HIP;
-    }
     if (!launch_ok("delta_scan")) return DA_ERR_HIP;
     // 3. entry lists and plans of the key columns that do not have them yet, from the first block of 32 columns that
     //    is new or was incomplete (cached columns from reference keys: where a bit is set they equal the key)

@@ -92,28 +92,58 @@ __global__ __launch_bounds__(64) void seal_from_ring_kernel(da_cache c, int chun
 }
 
 // Hand-off of prefilled rows to the cache (Sec. III-C): rows t0 .. n_k - 1 (t0 = rows the cache already
-// holds) are appended; one wave per (chunk that contains such a row, unit).  Kfull, Hfull, Mfull describe the
+// holds) are appended; two waves per (chunk that contains such a row, unit).  Kfull, Hfull, Mfull describe the
 // whole sequence [units][ld][...] (ld >= n_k rows of room per unit): keys (for rows the decode window no longer
 // holds raw, the reference key stands in - the two agree wherever a mask bit is set, which is all that is read),
 // reference keys, mask
 // rows; Vnew [units][n_k - t0][d] the new value rows.  With t0 = 0 these are the prefill's own arrays.
-__global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__restrict__ Kfull,
+__global__ __launch_bounds__(128) void cache_fill_runs_kernel(const bf16_t *__restrict__ Kfull,
                                                              const bf16_t *__restrict__ Vnew,
                                                              const bf16_t *__restrict__ Hfull,
                                                              const uint32_t *__restrict__ Mfull,
                                                              const uint64_t *__restrict__ nnz_new, da_cache c, int t0,
                                                              int n_k, int ld) {
-    const int chunk = blockIdx.x + t0 / kChunk, unit = blockIdx.y, lane = threadIdx.x;
+    // two waves: wave 0 takes mask rows, raw-key ring, checkpoint, newest reference key and the chunk's runs; wave 1
+    // the value rows (two chains of dependent memory round trips side by side instead of one after the other)
+    const int chunk = blockIdx.x + t0 / kChunk, unit = blockIdx.y, lane = threadIdx.x & (kWave - 1);
+    const bool values = threadIdx.x >= kWave;
     const int d = c.d, wpr = d >> 5, m = n_k - t0;
     const int r0 = chunk * kChunk;
     const int ra = max(r0, t0), rb = min(r0 + kChunk, n_k);          // new rows of this chunk
     const uint32_t *Mp = Mfull + ((size_t)unit * ld + r0) * wpr;     // the chunk's mask rows, old ones included
-    uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
-    for (int i = (ra - r0) * wpr + lane; i < (rb - r0) * wpr; i += kWave) Mc[i] = Mp[i];
-    if (lane == 0 && blockIdx.x == 0) c.nnz[unit] = (t0 == 0 ? 0ull : c.nnz[unit]) + nnz_new[unit];
     const bf16_t *Kp = Kfull + ((size_t)unit * ld + r0) * d;
     const bf16_t *Hp = Hfull + ((size_t)unit * ld + r0) * d;
     const bf16_t *Vp = Vnew + (size_t)unit * m * d;
+    if (values) {
+        // V: 16 rows of one channel are contiguous.  A group that starts with a new row is written whole (32
+        // bytes per lane, consecutive lanes adjacent; rows past the end as zeros), one that starts with old
+        // rows only gets its new slots
+        for (int ch = lane; ch < d; ch += kWave) {
+            for (int g0 = r0; g0 < rb; g0 += 16) {
+                if (g0 + 16 <= ra) continue;
+                bf16_t *dst = (bf16_t *)c.V + (((size_t)unit * (c.vrows >> 4) + (g0 >> 4)) * d + ch) * 16;
+                if (g0 >= ra) {
+                    bf16_t v16[16];
+#pragma unroll
+                    for (int slot = 0; slot < 16; ++slot) {
+                        const int k = slot >> 3, i = slot & 7;
+                        const int row = g0 + 8 * (i >> 2) + 4 * k + (i & 3);
+                        const bf16_t v = Vp[(size_t)(min(row, rb - 1) - t0) * d + ch];   // clamped: no conditional load
+                        v16[slot] = row < rb ? v : (bf16_t)0;
+                    }
+#pragma unroll
+                    for (int slot = 0; slot < 16; ++slot) dst[slot] = v16[slot];
+                } else {
+                    for (int row = ra; row < min(g0 + 16, rb); ++row)
+                        ((bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)] = Vp[(size_t)(row - t0) * d + ch];
+                }
+            }
+        }
+        return;
+    }
+    uint32_t *Mc = c.mask + ((size_t)unit * c.max_seq + r0) * wpr;
+    for (int i = (ra - r0) * wpr + lane; i < (rb - r0) * wpr; i += kWave) Mc[i] = Mp[i];
+    if (lane == 0 && blockIdx.x == 0) c.nnz[unit] = (t0 == 0 ? 0ull : c.nnz[unit]) + nnz_new[unit];
     for (int ch = lane; ch < d; ch += kWave) {
         for (int rq = ra; rq < rb; rq += 16) {               // 16 rows at a time: loads first (clamped), then stores
             bf16_t kk[16];
@@ -128,28 +158,6 @@ __global__ __launch_bounds__(64) void cache_fill_runs_kernel(const bf16_t *__res
         }
         if (chunk > 0 && r0 >= t0) ((bf16_t *)c.ck)[((size_t)unit * c.nck + chunk) * d + ch] = Hp[ch - d];
         if (rb == n_k) ((bf16_t *)c.khat)[(size_t)unit * d + ch] = Hp[(size_t)(rb - 1 - r0) * d + ch];
-        // V: 16 rows of one channel are contiguous.  A group that starts with a new row is written whole (32
-        // bytes per lane, consecutive lanes adjacent; rows past the end as zeros), one that starts with old
-        // rows only gets its new slots
-        for (int g0 = r0; g0 < rb; g0 += 16) {
-            if (g0 + 16 <= ra) continue;
-            bf16_t *dst = (bf16_t *)c.V + (((size_t)unit * (c.vrows >> 4) + (g0 >> 4)) * d + ch) * 16;
-            if (g0 >= ra) {
-                bf16_t v16[16];
-#pragma unroll
-                for (int slot = 0; slot < 16; ++slot) {
-                    const int k = slot >> 3, i = slot & 7;
-                    const int row = g0 + 8 * (i >> 2) + 4 * k + (i & 3);
-                    const bf16_t v = Vp[(size_t)(min(row, rb - 1) - t0) * d + ch];   // clamped: no conditional load
-                    v16[slot] = row < rb ? v : (bf16_t)0;
-                }
-#pragma unroll
-                for (int slot = 0; slot < 16; ++slot) dst[slot] = v16[slot];
-            } else {
-                for (int row = ra; row < min(g0 + 16, rb); ++row)
-                    ((bf16_t *)c.V)[v16_index(unit, c.vrows, d, row, ch)] = Vp[(size_t)(row - t0) * d + ch];
-            }
-        }
     }
     // chunks completed by these rows are sealed here (the run's first element comes from the reference keys)
     if (rb - r0 == kChunk)
@@ -619,7 +627,7 @@ void cache_fill_runs(da_cache *c, int t0, int n_k, int ld, const void *Kfull, co
                      const uint32_t *Mfull, const uint64_t *nnz_new, hipStream_t s) {
     const int units = c->B * c->Hkv;
     const int chunks = (n_k + kChunk - 1) / kChunk - t0 / kChunk;
-    hipLaunchKernelGGL(cache_fill_runs_kernel, dim3(chunks, units), dim3(64), 0, s, (const bf16_t *)Kfull,
+    hipLaunchKernelGGL(cache_fill_runs_kernel, dim3(chunks, units), dim3(2 * kWave), 0, s, (const bf16_t *)Kfull,
                        (const bf16_t *)Vnew, (const bf16_t *)Hfull, Mfull, nnz_new, *c, t0, n_k, ld);
 }
 

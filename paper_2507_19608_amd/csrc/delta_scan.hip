@@ -278,6 +278,39 @@ __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int
     if (i < n) p[i] = v;
 }
 
+// Chunked prefill: the m new rows of every unit join the whole-sequence arrays behind the t0 rows these already
+// hold - keys, values and reference keys (rows of row16 16-byte pieces, [units][m] -> [units][ld] at row t0) and mask
+// rows (mwords words each) - in one launch.  blockIdx.y = unit; the threads of a unit walk the four copies in turn.
+__global__ __launch_bounds__(256) void append_rows_kernel(const uint4 *__restrict__ K, const uint4 *__restrict__ V,
+                                                          const uint4 *__restrict__ H, const uint32_t *__restrict__ M,
+                                                          uint4 *__restrict__ Kfull, uint4 *__restrict__ Vfull,
+                                                          uint4 *__restrict__ Hfull, uint32_t *__restrict__ Mfull, int t0,
+                                                          int m, int ld, int row16, int mwords) {
+    const size_t unit = blockIdx.y;
+    const int pieces = m * row16, words = m * mwords;
+    const size_t src = unit * (size_t)pieces, dst = (unit * (size_t)ld + (size_t)t0) * row16;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < 3 * pieces + words; i += gridDim.x * blockDim.x) {
+        if (i < pieces) Kfull[dst + i] = K[src + i];
+        else if (i < 2 * pieces) Vfull[dst + i - pieces] = V[src + i - pieces];
+        else if (i < 3 * pieces) Hfull[dst + i - 2 * pieces] = H[src + i - 2 * pieces];
+        else {
+            const int k = i - 3 * pieces;
+            Mfull[(unit * (size_t)ld + (size_t)t0) * mwords + k] = M[unit * (size_t)words + k];
+        }
+    }
+}
+
+void launch_append_rows(const void *K, const void *V, const void *H, const uint32_t *M, void *Kfull, void *Vfull,
+                        void *Hfull, uint32_t *Mfull, int units, int t0, int m, int ld, int d, hipStream_t s) {
+    if (units <= 0 || m <= 0) return;
+    const int row16 = d * 2 / 16, mwords = d / 32;
+    const long long per_unit = (long long)m * (3 * row16 + mwords);
+    const int blocks = (int)((per_unit + 1023) / 1024 < 1024 ? (per_unit + 1023) / 1024 : 1024);   // ~4 pieces a thread
+    hipLaunchKernelGGL(append_rows_kernel, dim3(blocks, units), dim3(256), 0, s, (const uint4 *)K, (const uint4 *)V,
+                       (const uint4 *)H, M, (uint4 *)Kfull, (uint4 *)Vfull, (uint4 *)Hfull, Mfull, t0, m, ld, row16,
+                       mwords);
+}
+
 int device_cu_count() {
     static std::atomic<int> cached[64];                          // per device ordinal; 0 = not asked yet
     int dev = 0, cus = 0;

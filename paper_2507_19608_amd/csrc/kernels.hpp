@@ -59,6 +59,11 @@ struct PrefillArgs {
 constexpr int kFusedMaxElems = 32768;
 
 void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
+
+// Chunked prefill: rows of the new piece - K, V, H [units][m][d] (bf16) and M [units][m][d/32] - are copied behind
+// row t0 of the whole-sequence arrays [units][ld][...].
+void launch_append_rows(const void *K, const void *V, const void *H, const uint32_t *M, void *Kfull, void *Vfull,
+                        void *Hfull, uint32_t *Mfull, int units, int t0, int m, int ld, int d, hipStream_t s);
 int delta_scan_num_chunks(int n);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr);
