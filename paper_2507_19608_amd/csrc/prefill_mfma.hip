@@ -1115,7 +1115,8 @@ static void launch_d(const PrefillArgs &p, void *vt, int n_pad, hipStream_t s) {
 }
 
 // A launch with fewer than four tiles per compute unit is cut along the keys, as many ways (a power of two, at most
-// 8) as bring it there; never more parts than the longest tile has runs of kSplitMinBlocks key blocks.
+// 8) as bring it there, one with fewer than eight in two; never more parts than the longest tile has runs of
+// kSplitMinBlocks key blocks.
 int prefill_mfma_ksplit(const PrefillArgs &p) {
     if (p.fused || p.rebase || !prefill_mfma_supported(p)) return 1;   // (matrix-core blocks are too cheap to pay for it)
     int GH, RT, tiles, hgroups;
@@ -1123,6 +1124,10 @@ int prefill_mfma_ksplit(const PrefillArgs &p) {
     const long long groups = (long long)p.B * p.Hkv * tiles * hgroups, want = 4LL * device_cu_count();
     int ks = 1;
     while (ks < kMaxSplit && groups * ks < want) ks *= 2;
+    // (measured: going from whole tiles to halves still pays at 5 tiles per CU - 4 x 20 heads x 4096 tokens: 2.60 ->
+    // 2.32 ms, the long tiles' tail - but not at 10, 8192 tokens: 8.05 -> 8.72 ms; and cuts finer than `want` asks for
+    // cost more than they balance)
+    if (ks == 1 && groups < 2 * want) ks = 2;
     const int longest = (p.q_off + p.nq - 1) / kTB + 1;      // key blocks of the last tile
     while (ks > 1 && longest / kSplitMinBlocks < ks) ks /= 2;
     return ks;
