@@ -159,7 +159,7 @@ __host__ __device__ inline TileGeometry tile_geometry_of(int q_off, int RT, int 
     g.win_first = sliding ? (g.i0 - W + 1 > 0 ? g.i0 - W + 1 : 0) : (g.i0 / W) * W;
     g.far_blocks = gather ? g.win_first / kTB : 0;
     g.nblocks = g.i_last / kTB + 1;
-    const int cut = (gather ? g.far_blocks : g.nblocks) / kSplitMinBlocks;
+    const int cut = (gather ? g.far_blocks : g.nblocks) / kSplitMinBlocks;   // (rounded down: up or to nearest measured worse)
     g.parts = cut < 1 ? 1 : (cut < ksplit ? cut : ksplit);
     return g;
 }
@@ -431,9 +431,12 @@ __global__ __launch_bounds__(512) void prefill_mfma_kernel(MfmaArgs a) {
         // products are exact in binary32, the sum is taken in binary64
         const bf16_t *hrow = Hp + (size_t)(f_lo * kTB - 1) * D;
         double acc = 0.0;
-#pragma unroll 4
+        u32x4 qrow[D / 8];                                        // (all of the row's loads in flight at once)
+#pragma unroll
+        for (int c8 = 0; c8 < D / 8; ++c8) qrow[c8] = *(const u32x4 *)(my_q + c8 * 8);
+#pragma unroll
         for (int c8 = 0; c8 < D / 8; ++c8) {
-            const u32x4 qv = *(const u32x4 *)(my_q + c8 * 8), hv = *(const u32x4 *)(hrow + c8 * 8);
+            const u32x4 qv = qrow[c8], hv = *(const u32x4 *)(hrow + c8 * 8);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 acc += (double)(__uint_as_float(qv[k] << 16) * __uint_as_float(hv[k] << 16));
