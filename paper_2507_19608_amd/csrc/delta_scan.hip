@@ -144,6 +144,9 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
                                             init ? init + (size_t)unit * d : nullptr, start, theta, &cnt);
     if (active) store_from_f32(chunk_out, ((size_t)unit * nchunks + chunk) * d + c, held);
     if (kFinal && lane == 0) atomicAdd(nnz + unit, cnt);
+    // (the first pass, when there is one, also clears the unit's counter for the final pass that follows it in the
+    // stream; a single-chunk scan has no first pass and its launcher clears the counters itself)
+    if (!kFinal && lane == 0 && blockIdx.x == 0 && chunk == 0) nnz[unit] = 0ull;
 }
 
 template <typename T>
@@ -361,7 +364,7 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
 // init: NULL (row 0 is the basis row) or [units][d], the reference key the rows continue from.
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s, const void *init) {
-    launch_fill_u64(nnz, 0, units, s);
+    if (delta_scan_num_chunks(n) <= 1) launch_fill_u64(nnz, 0, units, s);   // (else the first pass clears them)
     if (dtype == 0)
         scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
     else
