@@ -244,10 +244,13 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     // Short prompts on the matrix-core kernel: one launch does everything (the scan, the compaction and the V
     // re-order run inside the attention launch, once per work group); longer ones take a launch per stage.
     const bool fused = prefill_mfma_supported(a) && (int64_t)p->seq_len * p->head_dim <= kFusedMaxElems;
+    // (the scan's last launch takes the V re-order of the matrix-core kernels along where it can)
+    const bool vt_in_scan = !fused && prefill_mfma_supported(a) && delta_scan_takes_v(p->dtype, p->seq_len, p->head_dim);
     if (!fused) {
         stage_begin(kStageScan, s);
         launch_delta_scan(p->dtype, K, khat, mask_bits, ws + w.chunk_out, nnz, units, p->seq_len, p->head_dim,
-                          p->theta, s);
+                          p->theta, s, nullptr, vt_in_scan ? V : nullptr, vt_in_scan ? ws + w.vt : nullptr,
+                          prefill_mfma_n_pad(p->seq_len));
         stage_end(kStageScan, s);
         if (!launch_ok("delta_scan")) return DA_ERR_HIP;
         if (p->score_mode == DA_SCORE_GATHER || cache) {
@@ -285,6 +288,7 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     a.nch8 = nch8;
     a.ksplit = w.ksplit;
     a.part = ws + w.part;
+    a.vt_from = vt_in_scan ? prefill_mfma_n_pad(p->seq_len) / 32 : 0;   // (every block of V is in place already)
     a.plan = ws + w.plan;
     a.dense = (const uint32_t *)(ws + w.dense);
     stage_begin(kStageAttn, s);

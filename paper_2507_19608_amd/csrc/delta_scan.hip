@@ -3,6 +3,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "scan_device.hpp"
+#include "vt_device.hpp"
 
 #include <stdarg.h>
 #include <stdio.h>
@@ -155,9 +156,30 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
                                                               const T *__restrict__ out1,   // pass 1 final values
                                                               const T *__restrict__ out2,   // pass 2 final values
                                                               unsigned long long *__restrict__ nnz, int n, int d,
-                                                              int L, int nchunks, float theta) {
+                                                              int L, int nchunks, float theta,
+                                                              const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
+                                                              int n_pad) {
     const int unit = blockIdx.y;
     const int lane = threadIdx.x;
+    // Work groups past the channel waves (there are some only when the launcher was given V) have nothing to do with
+    // the scan: each re-orders one block of 32 value rows for the matrix-core prefill kernels, which need that done
+    // before they start and would otherwise pay a launch of its own for it.
+    if ((int)blockIdx.x >= (d + kWave - 1) / kWave) {
+        const int blk = (int)blockIdx.x - (d + kWave - 1) / kWave;
+        __shared__ bf16_t tile[kTB * (128 + 2)];
+        auto wave_sync = [] {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        };
+        if (d == 64)
+            transpose_v_block<64, kWave>(V + (size_t)unit * n * 64, (u32x4 *)(Vt + (size_t)unit * 64 * n_pad) + (size_t)blk * (2 * 2 * 64),
+                                         blk * kTB, n, (bf16_t(*)[64 + 2])tile, lane, wave_sync);
+        else
+            transpose_v_block<128, kWave>(V + (size_t)unit * n * 128, (u32x4 *)(Vt + (size_t)unit * 128 * n_pad) + (size_t)blk * (2 * 4 * 64),
+                                          blk * kTB, n, (bf16_t(*)[128 + 2])tile, lane, wave_sync);
+        return;
+    }
     const int c = blockIdx.x * kWave + lane;
     const bool active = c < d;
     const int cs = active ? c : 0;
@@ -342,7 +364,7 @@ int delta_scan_num_chunks(int n) { return (n + delta_scan_chunk_len(n) - 1) / de
 
 template <typename T>
 static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz, int units,
-                       int n, int d, float theta, const void *init, hipStream_t s) {
+                       int n, int d, float theta, const void *init, hipStream_t s, const void *V, void *Vt, int n_pad) {
     const int L = delta_scan_chunk_len(n), nchunks = delta_scan_num_chunks(n);
     const int cw = (d + kWave - 1) / kWave;
     T *out1 = (T *)chunk_out;
@@ -355,20 +377,26 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
                        (const T *)K, (T *)Khat, mask_bits, (const T *)out1, out2, (unsigned long long *)nnz, n, d, L,
                        nchunks, theta, (const T *)init);
     if (nchunks > 1)
-        hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw, units), dim3(kWave), 0, s, (const T *)K, (T *)Khat,
-                           mask_bits, (const T *)out1, (const T *)out2, (unsigned long long *)nnz, n, d, L, nchunks,
-                           theta);
+        hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw + (V ? n_pad / kTB : 0), units), dim3(kWave), 0, s,
+                           (const T *)K, (T *)Khat, mask_bits, (const T *)out1, (const T *)out2,
+                           (unsigned long long *)nnz, n, d, L, nchunks, theta, (const bf16_t *)V, (bf16_t *)Vt, n_pad);
 }
 
 // Khat [units][n][d] and chunk_out [2][units][delta_scan_num_chunks(n)][d] are required scratch/outputs.
 // init: NULL (row 0 is the basis row) or [units][d], the reference key the rows continue from.
+bool delta_scan_takes_v(int dtype, int n, int d) {
+    return dtype == 1 && (d == 64 || d == 128) && delta_scan_num_chunks(n) > 1;
+}
+
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
-                       int units, int n, int d, float theta, hipStream_t s, const void *init) {
+                       int units, int n, int d, float theta, hipStream_t s, const void *init, const void *V, void *Vt,
+                       int n_pad) {
     if (delta_scan_num_chunks(n) <= 1) launch_fill_u64(nnz, 0, units, s);   // (else the first pass clears them)
+    if (!V || !Vt || !delta_scan_takes_v(dtype, n, d)) V = nullptr;
     if (dtype == 0)
-        scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
+        scan_typed<float>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s, nullptr, nullptr, 0);
     else
-        scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s);
+        scan_typed<bf16_t>(K, Khat, mask_bits, chunk_out, nnz, units, n, d, theta, init, s, V, Vt, n_pad);
 }
 
 // ld > 0: the arrays have ld rows of room per unit (padded strides from prefill_mfma_n_pad(ld)) of which n are valid,

@@ -65,8 +65,13 @@ void launch_fill_u64(uint64_t *p, uint64_t v, int n, hipStream_t s);
 void launch_append_rows(const void *K, const void *V, const void *H, const uint32_t *M, void *Kfull, void *Vfull,
                         void *Hfull, uint32_t *Mfull, int units, int t0, int m, int ld, int d, hipStream_t s);
 int delta_scan_num_chunks(int n);
+// V, Vt (both or neither; used only where delta_scan_takes_v() says so): the value rows [units][n][d] are re-ordered
+// into Vt [units][d][n_pad], the operand order of the matrix-core prefill kernels, by extra work groups of the scan's
+// last launch (they have nothing to do with the scan; it saves the prefill a launch).
+bool delta_scan_takes_v(int dtype, int n, int d);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
-                       int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr);
+                       int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr,
+                       const void *V = nullptr, void *Vt = nullptr, int n_pad = 0);
 // plan: NULL, or room for units * n_pad * 2 bytes: the gather loop's column plan; dense (used with plan): room for
 // units * n_pad / 32 words (see emit_entries_kernel)
 void launch_emit_entries(int dtype, const void *K, const void *Khat, const uint32_t *mask_bits, void *ents,
