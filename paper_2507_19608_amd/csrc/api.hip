@@ -244,7 +244,7 @@ da_status prefill_checked(const da_prefill_params *p, const WsLayout &w, const v
     // Short prompts on the matrix-core kernel: one launch does everything (the scan, the compaction and the V
     // re-order run inside the attention launch, once per work group); longer ones take a launch per stage.
     const bool fused = prefill_mfma_supported(a) && (int64_t)p->seq_len * p->head_dim <= kFusedMaxElems;
-    // (the scan's last launch takes the V re-order of the matrix-core kernels along where it can)
+    // (the scan's first launch takes the V re-order of the matrix-core kernels along where it can)
     const bool vt_in_scan = !fused && prefill_mfma_supported(a) && delta_scan_takes_v(p->dtype, p->seq_len, p->head_dim);
     if (!fused) {
         stage_begin(kStageScan, s);

@@ -127,9 +127,34 @@ __global__ __launch_bounds__(64) void delta_scan_chunks_kernel(const T *__restri
                                                                T *__restrict__ chunk_out,
                                                                unsigned long long *__restrict__ nnz, int n, int d,
                                                                int L, int nchunks, float theta,
-                                                               const T *__restrict__ init) {
+                                                               const T *__restrict__ init,
+                                                               const bf16_t *__restrict__ V = nullptr,
+                                                               bf16_t *__restrict__ Vt = nullptr, int n_pad = 0) {
     const int unit = blockIdx.z, chunk = blockIdx.y;
     const int lane = threadIdx.x;
+    // Work groups past the channel waves (the first pass has some when the launcher was given V) have nothing to do
+    // with the scan: each re-orders one block of 32 value rows - blocks (L / 32) chunk .. of the unit - for the
+    // matrix-core prefill kernels, which need that done before they start and would otherwise pay a launch of its own
+    // for it (in the first pass, so that what the later passes write is still in the caches when it is read again).
+    if ((int)blockIdx.x >= (d + kWave - 1) / kWave) {
+        const int blk = chunk * (L / kTB) + (int)blockIdx.x - (d + kWave - 1) / kWave;
+        if (kFinal || blk >= n_pad / kTB) return;
+        __shared__ bf16_t tile[kTB * (128 + 2)];
+        auto wave_sync = [] {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        };
+        if (d == 64)
+            transpose_v_block<64, kWave>(V + (size_t)unit * n * 64,
+                                         (u32x4 *)(Vt + (size_t)unit * 64 * n_pad) + (size_t)blk * (2 * 2 * 64), blk * kTB,
+                                         n, (bf16_t(*)[64 + 2]) tile, lane, wave_sync);
+        else
+            transpose_v_block<128, kWave>(V + (size_t)unit * n * 128,
+                                          (u32x4 *)(Vt + (size_t)unit * 128 * n_pad) + (size_t)blk * (2 * 4 * 64), blk * kTB,
+                                          n, (bf16_t(*)[128 + 2]) tile, lane, wave_sync);
+        return;
+    }
     const int c = blockIdx.x * kWave + lane;
     const bool active = c < d;
     const T *Kp = K + (size_t)unit * n * d;
@@ -156,30 +181,9 @@ __global__ __launch_bounds__(64) void delta_scan_fixup_kernel(const T *__restric
                                                               const T *__restrict__ out1,   // pass 1 final values
                                                               const T *__restrict__ out2,   // pass 2 final values
                                                               unsigned long long *__restrict__ nnz, int n, int d,
-                                                              int L, int nchunks, float theta,
-                                                              const bf16_t *__restrict__ V, bf16_t *__restrict__ Vt,
-                                                              int n_pad) {
+                                                              int L, int nchunks, float theta) {
     const int unit = blockIdx.y;
     const int lane = threadIdx.x;
-    // Work groups past the channel waves (there are some only when the launcher was given V) have nothing to do with
-    // the scan: each re-orders one block of 32 value rows for the matrix-core prefill kernels, which need that done
-    // before they start and would otherwise pay a launch of its own for it.
-    if ((int)blockIdx.x >= (d + kWave - 1) / kWave) {
-        const int blk = (int)blockIdx.x - (d + kWave - 1) / kWave;
-        __shared__ bf16_t tile[kTB * (128 + 2)];
-        auto wave_sync = [] {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        };
-        if (d == 64)
-            transpose_v_block<64, kWave>(V + (size_t)unit * n * 64, (u32x4 *)(Vt + (size_t)unit * 64 * n_pad) + (size_t)blk * (2 * 2 * 64),
-                                         blk * kTB, n, (bf16_t(*)[64 + 2])tile, lane, wave_sync);
-        else
-            transpose_v_block<128, kWave>(V + (size_t)unit * n * 128, (u32x4 *)(Vt + (size_t)unit * 128 * n_pad) + (size_t)blk * (2 * 4 * 64),
-                                          blk * kTB, n, (bf16_t(*)[128 + 2])tile, lane, wave_sync);
-        return;
-    }
     const int c = blockIdx.x * kWave + lane;
     const bool active = c < d;
     const int cs = active ? c : 0;
@@ -370,16 +374,17 @@ static void scan_typed(const void *K, void *Khat, uint32_t *mask_bits, void *chu
     T *out1 = (T *)chunk_out;
     T *out2 = out1 + (size_t)units * nchunks * d;
     if (nchunks > 1)
-        hipLaunchKernelGGL((delta_scan_chunks_kernel<T, false>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
-                           (const T *)K, (T *)Khat, mask_bits, (const T *)nullptr, out1,
-                           (unsigned long long *)nnz, n, d, L, nchunks, theta, (const T *)init);
+        hipLaunchKernelGGL((delta_scan_chunks_kernel<T, false>), dim3(cw + (V ? L / kTB : 0), nchunks, units),
+                           dim3(kWave), 0, s, (const T *)K, (T *)Khat, mask_bits, (const T *)nullptr, out1,
+                           (unsigned long long *)nnz, n, d, L, nchunks, theta, (const T *)init, (const bf16_t *)V,
+                           (bf16_t *)Vt, n_pad);
     hipLaunchKernelGGL((delta_scan_chunks_kernel<T, true>), dim3(cw, nchunks, units), dim3(kWave), 0, s,
                        (const T *)K, (T *)Khat, mask_bits, (const T *)out1, out2, (unsigned long long *)nnz, n, d, L,
                        nchunks, theta, (const T *)init);
     if (nchunks > 1)
-        hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw + (V ? n_pad / kTB : 0), units), dim3(kWave), 0, s,
-                           (const T *)K, (T *)Khat, mask_bits, (const T *)out1, (const T *)out2,
-                           (unsigned long long *)nnz, n, d, L, nchunks, theta, (const bf16_t *)V, (bf16_t *)Vt, n_pad);
+        hipLaunchKernelGGL(delta_scan_fixup_kernel<T>, dim3(cw, units), dim3(kWave), 0, s, (const T *)K, (T *)Khat,
+                           mask_bits, (const T *)out1, (const T *)out2, (unsigned long long *)nnz, n, d, L, nchunks,
+                           theta);
 }
 
 // Khat [units][n][d] and chunk_out [2][units][delta_scan_num_chunks(n)][d] are required scratch/outputs.

@@ -67,7 +67,7 @@ void launch_append_rows(const void *K, const void *V, const void *H, const uint3
 int delta_scan_num_chunks(int n);
 // V, Vt (both or neither; used only where delta_scan_takes_v() says so): the value rows [units][n][d] are re-ordered
 // into Vt [units][d][n_pad], the operand order of the matrix-core prefill kernels, by extra work groups of the scan's
-// last launch (they have nothing to do with the scan; it saves the prefill a launch).
+// first launch (they have nothing to do with the scan; it saves the prefill a launch).
 bool delta_scan_takes_v(int dtype, int n, int d);
 void launch_delta_scan(int dtype, const void *K, void *Khat, uint32_t *mask_bits, void *chunk_out, uint64_t *nnz,
                        int units, int n, int d, float theta, hipStream_t s, const void *init = nullptr,

@@ -1,5 +1,5 @@
 // Re-ordering of value rows into the matrix-core operand order of the prefill kernels (shared by the stand-alone
-// launch, the delta scan's last launch, which takes the re-order along, and the fused short-prompt kernel).
+// launch, the delta scan's first launch, which takes the re-order along, and the fused short-prompt kernel).
 #pragma once
 #include "common.hpp"
 
