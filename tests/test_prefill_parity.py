@@ -162,6 +162,17 @@ def test_c3_sliding_window_sampled(mode):
     _sampled(wl.C3, mode, [(200, 230), (2040, 2060), (4070, 4096)], [1, 18], window_mode=da.DA_WINDOW_SLIDING)
 
 
+def test_mid_size_launch_cut_in_two_sampled():
+    """4 x 4096 tokens of C5's head shape with the window of Eq. 5 (W = 204: tiles straddle window squares): 1280 row
+    tiles, five per compute unit - few enough that the gather launch gives every tile two work groups, each on half of
+    its gather blocks, and merges them in a second launch.  Masks and nnz of every unit, sampled output rows."""
+    import dataclasses
+    w = dataclasses.replace(wl.C5, seq_len=4096, window=da.delta_attn_window_from_gamma(4096, 0.05, 512),
+                            theta=wl.theta_for(wl.C5), target_sparsity=None)
+    assert w.window == 204
+    _sampled(w, da.DA_SCORE_GATHER, [(1000, 1020), (2600, 2615), (4076, 4096)], [2, 17])
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_c5_long_context_sampled(mode):
     _sampled(wl.C5, mode, [(500, 530), (4090, 4110), (8170, 8192)], [3, 16])
